@@ -1,0 +1,225 @@
+/*
+ * ss.h — C ABI of libss: the verify-and-speculate decode step of Speculative
+ * Streaming (arXiv 2402.11131) on one AMD MI355X (gfx950).
+ *
+ * One decode step, as the paper states it (Sec. 3.2.2 and Appendix A.1): the
+ * tree draft of the previous step is flattened into T main-stream rows, every
+ * node carries gamma speculative-stream rows, the top N_s layers run
+ * multi-stream attention (Eq. 1 for main rows, Eq. 2 for stream rows, tree mask
+ * of Eq. 4 / the attention-mask figure of the appendix), the LM head turns the
+ * last hidden states into logits, the longest draft path the main stream agrees
+ * with is accepted, and the streams of the last accepted node give the next
+ * tree draft.  The five calls below are those pieces.
+ *
+ * Conventions (all calls)
+ *  - extern "C", plain pointers and sizes.  Unless a parameter says "host",
+ *    every array is DEVICE memory owned by the caller; the library never frees
+ *    or keeps it.  Outputs must not alias inputs.
+ *  - Every call only enqueues work on `stream` (a hipStream_t passed as void*,
+ *    NULL = the default stream).  No call synchronises with the device or reads
+ *    device memory on the host, so the whole step can be chained on one stream.
+ *  - Return value: SS_OK or an error code; ss_last_error() gives a thread-local
+ *    message for the last failing call of the calling thread.  On error nothing
+ *    has been enqueued.
+ *  - Errors that only the device could see (a malformed parent array, a
+ *    seq_len beyond the block table) cannot be reported by an asynchronous
+ *    call; every kernel clamps such values so that all accesses stay in bounds
+ *    and the result for that sequence is then unspecified but finite-time.
+ *    ss_check_tree_host() validates a host copy of a tree.
+ *
+ * Row order inside one sequence (T tree nodes, gamma streams, R = T*(1+gamma)
+ * rows; Sec. 3.2.3 gives the same count):
+ *    main row of node i           r = i                          0 <= i < T
+ *    stream j (1..gamma) of node i r = T + i*gamma + (j-1)
+ * Node 0 is the root (the correction token of the previous step), parent[0] =
+ * -1 and parent[i] < i.  Queries, the step's new keys/values and the LM-head
+ * rows all use this order.
+ */
+#ifndef SS_H_
+#define SS_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* status codes */
+#define SS_OK 0
+#define SS_ERR_INVALID_ARG 1 /* NULL pointer, non-positive size, bad stride     */
+#define SS_ERR_UNSUPPORTED 2 /* dtype / head_dim / T / gamma / K outside limits */
+#define SS_ERR_BAD_TREE 3    /* only from ss_check_tree_host                    */
+#define SS_ERR_WORKSPACE 4   /* workspace NULL or smaller than *_workspace_bytes */
+#define SS_ERR_HIP 5         /* a HIP runtime call failed at launch             */
+
+/* element types of the floating-point tensors */
+#define SS_F32 0
+#define SS_BF16 1
+
+/* limits */
+#define SS_MAX_T 64     /* tree nodes per sequence (ancestor sets are 64-bit) */
+#define SS_MAX_GAMMA 8  /* speculative streams per node                       */
+#define SS_MAX_K 8      /* top-k width                                        */
+
+/* flags of ss_build_mask / ss_msa_attention.
+ * Eq. 2 lets stream j attend to streams 1..j of its own node (itself
+ * included); with SS_STREAM_EXCLUDE_SELF it sees streams 1..j-1 only. */
+#define SS_STREAM_EXCLUDE_SELF 1u
+
+/* Library version (major*100 + minor). */
+int ss_version(void);
+
+/* Message of the last error on the calling thread ("" if none). */
+const char* ss_last_error(void);
+
+/*
+ * Host-side check of B trees: parent[b*T+0] == -1, 0 <= parent[b*T+i] < i, and
+ * (if max_depth >= 0) depth <= max_depth.  `parent` is HOST memory.
+ * Returns SS_OK or SS_ERR_BAD_TREE (message names the first offending entry).
+ */
+int ss_check_tree_host(const int32_t* parent, int B, int T, int max_depth);
+
+/*
+ * a1. Mask construction (Sec. 3.2.2 Eq. 4 with the reading of the appendix
+ * attention-mask figure: a node attends to every predecessor from the root and
+ * to itself; Eq. 1/Eq. 2 for which stream sees which).
+ *
+ * For each of B sequences with parent[b, 0..T): depth[i] (root 0), anc[i] = bit
+ * set of the nodes on the root->i path (bit i included), and the boolean mask
+ * over the step's own R x R block: row (i,j) may attend key (i',j') iff
+ *    j' == 0 and i' is an ancestor-or-self of i                (main keys)
+ * or j  > 0 and j' > 0 and i' == i and j' <= j                 (own streams;
+ *                                    j' < j with SS_STREAM_EXCLUDE_SELF)
+ * (j = 0 is the main row).  Prefix keys in the KV cache are visible to every
+ * row and are not part of this matrix.
+ *
+ *  parent [B,T] int32 in;  mask [B,R,R] uint8 out (1 = may attend), may be NULL;
+ *  anc [B,T] uint64 out or NULL;  depth [B,T] int32 out or NULL.
+ * Limits: 1 <= T <= SS_MAX_T, 0 <= gamma <= SS_MAX_GAMMA.
+ * An entry parent[i] outside [-1, i) is treated as -1 for i == 0 and as 0
+ * otherwise (see "Conventions").
+ */
+int ss_build_mask(const int32_t* parent, int B, int T, int gamma, uint32_t flags,
+                  uint8_t* mask, uint64_t* anc, int32_t* depth, void* stream);
+
+/*
+ * a2. Multi-stream attention for one MSA layer (Eq. 1, Eq. 2, mask as in a1):
+ * for every sequence b, row r and query head h (KV head h / (H/Hkv)),
+ *    out[b,r,h,:] = softmax_c( scale * <q[b,r,h,:], K_c> + mask[r,c] ) . V_c
+ * over the keys c = the first seq_lens[b] cached main-stream tokens of the
+ * sequence (all visible) followed by the step's R new rows (masked as in a1).
+ * Stream keys/values are never cached (Sec. 3.2.1): they exist only in
+ * k_new / v_new.
+ *
+ *  q      [B,R,H,D]      k_new, v_new [B,R,Hkv,D]      out [B,R,H,D]
+ *  k_cache [num_pages, Hkv, page_size, D]   token-major pages
+ *  v_cache [num_pages, Hkv, D, page_size]   feature-major pages: the value of
+ *          token s of a page, feature d, sits at [page, hkv, d, s]
+ *  block_table [B, max_pages_per_seq] int32: physical page of logical page p
+ *  seq_lens [B] int32: cached tokens per sequence, 0 <= seq_lens[b] <=
+ *          max_pages_per_seq*page_size (larger values are clamped on device)
+ *  parent [B,T] int32 as in a1.
+ * dtype: SS_F32 (all of q,k,v,out fp32) or SS_BF16 (bf16 storage, fp32 softmax
+ * and accumulation).  Limits: D in {64,128}, page_size in {16,32,64}, H % Hkv
+ * == 0, T <= SS_MAX_T, gamma <= SS_MAX_GAMMA.  scale is the factor applied to
+ * the dot products (1/sqrt(D) in the paper's MHA).
+ * workspace: device scratch of at least ss_msa_workspace_bytes(...) bytes with
+ * max_seq_len = max_pages_per_seq*page_size; contents need not be preserved.
+ */
+size_t ss_msa_workspace_bytes(int B, int T, int gamma, int H, int Hkv, int D, int max_seq_len,
+                              int dtype);
+int ss_msa_attention(const void* q, const void* k_new, const void* v_new, const void* k_cache,
+                     const void* v_cache, const int32_t* block_table, int max_pages_per_seq,
+                     const int32_t* seq_lens, const int32_t* parent, int B, int T, int gamma, int H,
+                     int Hkv, int D, int page_size, float scale, int dtype, uint32_t flags,
+                     void* out, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Tuning knob for a2: number of cached tokens one workgroup scans (the KV
+ * split length).  0 = choose from the problem shape (default).  Values are
+ * rounded up to a multiple of 128.  The result of a2 does not depend on it
+ * beyond floating-point rounding.  Returns the previous setting.
+ */
+int ss_msa_set_split_keys(int split_keys);
+
+/*
+ * a3. LM head with fused argmax / top-K (Sec. 3.2.1: the last layer's main row
+ * predicts y_t, stream j predicts y_{t+j}; Sec. 3.2.2: top-k tokens per stream).
+ *    z[n,v] = sum_d hidden[n,d] * W[v,d]          (never written to memory)
+ *    idx[n,0..K) = the K largest z[n,:] in decreasing order, ties -> lower v;
+ *    val[n,0..K) = those logits (fp32).
+ *  hidden [N,d], W [V,d] (dtype SS_F32 or SS_BF16), idx [N,K] int32, val [N,K] f32.
+ * Limits: 1 <= K <= SS_MAX_K, K <= V, d % 64 == 0 for SS_BF16.
+ * workspace: at least ss_lm_head_workspace_bytes(...) bytes.
+ */
+size_t ss_lm_head_workspace_bytes(int N, int d, int V, int K, int dtype);
+int ss_lm_head_argmax_topk(const void* hidden, const void* W, int N, int d, int V, int K, int dtype,
+                           int32_t* idx, float* val, void* workspace, size_t workspace_bytes,
+                           void* stream);
+
+/*
+ * a4. Greedy ("hard matching") tree verification (Sec. 3.2.2, Appendix A.1):
+ * the root is always accepted; node i is accepted iff its parent is accepted
+ * and tok[i] equals the main-stream argmax token at its parent.  `last` is the
+ * accepted node of greatest depth (ties -> lowest node index), n_accept its
+ * depth (the number of accepted draft tokens, 0..max_depth), bonus the argmax
+ * token at `last` (the correction token, next step's root).
+ *
+ *  tok, parent [B,T] int32 in.
+ *  main_argmax: argmax token of main row i of sequence b at element
+ *          main_argmax[b*argmax_batch_stride + i*argmax_node_stride]
+ *          (so idx of a3 can be passed with strides R*K and K).
+ *  n_accept, last, bonus [B] int32 out.
+ *  path       [B, max_depth+1] int32 out: node ids root..last, then -1.
+ *  out_tokens [B, max_depth+1] int32 out: tok of path[1..n_accept], then
+ *          bonus, then -1: the n_accept+1 tokens this step emits.
+ * Nodes deeper than max_depth are never accepted.  0 <= max_depth < SS_MAX_T.
+ */
+int ss_tree_verify(const int32_t* tok, const int32_t* parent, const int32_t* main_argmax,
+                   long argmax_batch_stride, long argmax_node_stride, int B, int T, int max_depth,
+                   int32_t* n_accept, int32_t* last, int32_t* bonus, int32_t* path,
+                   int32_t* out_tokens, void* stream);
+
+/*
+ * a5. Top-k tree drafting (Sec. 3.2.2; Appendix A.1): the next tree has a
+ * static shape (the template), only its tokens change.  Template node 0 is the
+ * root; node i > 0 has parent tmpl_parent[i] < i, depth dep(i) in 1..gamma and
+ * rank tmpl_rank[i] in [0,K):
+ *    next_tok[b,0] = bonus[b]
+ *    next_tok[b,i] = stream_topk[b, last[b], dep(i)-1, tmpl_rank[i]]
+ * i.e. level j of the tree holds top-k tokens of stream j of the last accepted
+ * node, and tokens of stream j are predecessors of those of stream j+1.
+ *
+ *  stream_topk: top-K token ids of stream j (1..gamma) of node i of sequence b
+ *          at stream_topk[b*topk_batch_stride + ((i*gamma)+(j-1))*K + rank]
+ *          (idx of a3 offset by T*K elements, batch stride R*K).
+ *  last, bonus [B] int32 (outputs of a4).
+ *  Template, one of:
+ *    tmpl_parent, tmpl_rank [T2] int32 DEVICE arrays, or
+ *    both NULL and branching [gamma] int32 HOST array: the full tree with
+ *    branching[j-1] children per level-(j-1) node, nodes numbered level by
+ *    level, within a level by (parent, rank); then T2 must equal
+ *    1 + sum_j prod_{m<=j} branching[m-1]  (uniform k: 1 + sum_g k^g, Sec. 3.2.3).
+ *  next_tok [B,T2] int32 out;  next_parent [T2] int32 out or NULL (the template's
+ *  parent array, the `parent` input of the next step).
+ * A template entry with depth > gamma or rank outside [0,K) yields token -1.
+ * Limits: 1 <= T2 <= SS_MAX_T, gamma <= SS_MAX_GAMMA, K <= SS_MAX_K.
+ */
+int ss_tree_draft(const int32_t* stream_topk, long topk_batch_stride, int K, const int32_t* last,
+                  const int32_t* bonus, const int32_t* tmpl_parent, const int32_t* tmpl_rank,
+                  const int32_t* branching, int B, int T, int gamma, int T2, int32_t* next_tok,
+                  int32_t* next_parent, void* stream);
+
+/*
+ * Host helper for a5: writes the full-tree template described above into HOST
+ * arrays parent_out/rank_out/depth_out (each [T2] or NULL) and returns the node
+ * count, or -1 if it would exceed `capacity` or SS_MAX_T.  All pointers HOST.
+ */
+int ss_full_tree_template_host(const int32_t* branching, int gamma, int capacity,
+                               int32_t* parent_out, int32_t* rank_out, int32_t* depth_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SS_H_ */

@@ -1,0 +1,165 @@
+"""CPU oracle of the Speculative Streaming verify-and-speculate step.
+
+TEST INFRASTRUCTURE ONLY.  This package wraps ``ss_oracle.c`` (plain C, double
+precision, written from the paper) with numpy.  Only ``tests/``, the smoke check
+and the CPU-baseline leg of ``bench.py`` may use it; the product never does, and
+this package imports nothing from the product.
+
+Array layouts are those of the C ABI of the HIP library (row order: main rows
+first, then stream rows; paged K cache token-major, V cache feature-major).
+Floating-point inputs are float32 arrays holding the stored values exactly
+(bf16 tensors are up-cast by the caller); outputs are float64.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "ss_oracle.c")
+_LIB = os.path.join(_HERE, "libss_oracle.so")
+
+EXCLUDE_SELF = 1
+
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile ss_oracle.c with gcc (-O2 -fopenmp).  Returns the library path."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.check_call(
+            ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c99", "-o", tmp, _SRC, "-lm"]
+        )
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+        _lib.ora_full_tree_template.restype = ctypes.c_int
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _f32(a):
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    return a
+
+
+def _i32(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def num_threads() -> int:
+    """Threads the OpenMP loops of the oracle use (OMP_NUM_THREADS or all cores)."""
+    v = os.environ.get("OMP_NUM_THREADS")
+    if v:
+        try:
+            return max(1, int(v.split(",")[0]))
+        except ValueError:
+            pass
+    try:
+        return len(os.sched_getaffinity(0))
+    except AttributeError:
+        return os.cpu_count() or 1
+
+
+def build_mask(parent, gamma: int, flags: int = 0):
+    """a1.  parent [B,T] -> (mask [B,R,R] uint8, anc [B,T] uint64, depth [B,T] int32)."""
+    parent = _i32(parent)
+    B, T = parent.shape
+    R = T * (1 + gamma)
+    mask = np.zeros((B, R, R), np.uint8)
+    anc = np.zeros((B, T), np.uint64)
+    depth = np.zeros((B, T), np.int32)
+    _load().ora_build_mask(_p(parent), B, T, gamma, ctypes.c_uint32(flags), _p(mask), _p(anc), _p(depth))
+    return mask, anc, depth
+
+
+def msa_attention(q, k_new, v_new, k_cache, v_cache, block_table, seq_lens, parent, gamma: int,
+                  scale: float, flags: int = 0):
+    """a2.  Returns out [B,R,H,D] float64."""
+    q, k_new, v_new = _f32(q), _f32(k_new), _f32(v_new)
+    k_cache, v_cache = _f32(k_cache), _f32(v_cache)
+    block_table, seq_lens, parent = _i32(block_table), _i32(seq_lens), _i32(parent)
+    B, R, H, D = q.shape
+    Hkv = k_new.shape[2]
+    T = parent.shape[1]
+    assert R == T * (1 + gamma) and k_new.shape == (B, R, Hkv, D) and v_new.shape == k_new.shape
+    page = k_cache.shape[2]
+    assert k_cache.shape[1] == Hkv and k_cache.shape[3] == D
+    assert v_cache.shape == (k_cache.shape[0], Hkv, D, page)
+    assert block_table.shape[0] == B and seq_lens.shape == (B,)
+    if block_table.size:
+        assert block_table.min() >= 0 and block_table.max() < k_cache.shape[0]
+    out = np.zeros((B, R, H, D), np.float64)
+    _load().ora_msa_attention(
+        _p(q), _p(k_new), _p(v_new), _p(k_cache), _p(v_cache), _p(block_table),
+        int(block_table.shape[1]), _p(seq_lens), _p(parent), B, T, gamma, H, Hkv, D, page,
+        ctypes.c_double(scale), ctypes.c_uint32(flags), _p(out))
+    return out
+
+
+def lm_head_topk(hidden, W, K: int, want_logits: bool = False):
+    """a3.  Returns (idx [N,K] int32, val [N,K] float64[, logits [N,V] float64])."""
+    hidden, W = _f32(hidden), _f32(W)
+    N, d = hidden.shape
+    V = W.shape[0]
+    assert W.shape[1] == d and 1 <= K <= V
+    idx = np.zeros((N, K), np.int32)
+    val = np.zeros((N, K), np.float64)
+    logits = np.zeros((N, V), np.float64) if want_logits else None
+    _load().ora_lm_head_topk(_p(hidden), _p(W), N, d, V, K, _p(idx), _p(val), _p(logits))
+    return (idx, val, logits) if want_logits else (idx, val)
+
+
+def tree_verify(tok, parent, main_argmax, max_depth: int):
+    """a4.  tok, parent, main_argmax [B,T] -> dict(n_accept, last, bonus, path, out_tokens)."""
+    tok, parent, a = _i32(tok), _i32(parent), _i32(main_argmax)
+    B, T = tok.shape
+    assert parent.shape == (B, T) and a.shape == (B, T) and T <= 64
+    n_accept = np.zeros(B, np.int32)
+    last = np.zeros(B, np.int32)
+    bonus = np.zeros(B, np.int32)
+    path = np.zeros((B, max_depth + 1), np.int32)
+    out_tokens = np.zeros((B, max_depth + 1), np.int32)
+    _load().ora_tree_verify(_p(tok), _p(parent), _p(a), ctypes.c_long(T), ctypes.c_long(1), B, T,
+                            max_depth, _p(n_accept), _p(last), _p(bonus), _p(path), _p(out_tokens))
+    return dict(n_accept=n_accept, last=last, bonus=bonus, path=path, out_tokens=out_tokens)
+
+
+def full_tree_template(branching):
+    """Full tree of Sec. 3.2.3 with per-level branching -> (parent, rank, depth) int32 arrays."""
+    br = _i32(branching)
+    cap = 1 << 16
+    parent = np.zeros(cap, np.int32)
+    rank = np.zeros(cap, np.int32)
+    depth = np.zeros(cap, np.int32)
+    n = _load().ora_full_tree_template(_p(br), int(br.size), cap, _p(parent), _p(rank), _p(depth))
+    if n < 0:
+        raise ValueError("tree too large")
+    return parent[:n].copy(), rank[:n].copy(), depth[:n].copy()
+
+
+def tree_draft(stream_topk, last, bonus, tmpl_parent, tmpl_rank):
+    """a5.  stream_topk [B,T,gamma,K] -> (next_tok [B,T2], next_parent [T2])."""
+    tk = _i32(stream_topk)
+    B, T, gamma, K = tk.shape
+    last, bonus = _i32(last), _i32(bonus)
+    tp, tr = _i32(tmpl_parent), _i32(tmpl_rank)
+    T2 = tp.shape[0]
+    next_tok = np.zeros((B, T2), np.int32)
+    next_parent = np.zeros(T2, np.int32)
+    _load().ora_tree_draft(_p(tk), ctypes.c_long(T * gamma * K), K, _p(last), _p(bonus), _p(tp),
+                           _p(tr), B, T, gamma, T2, _p(next_tok), _p(next_parent))
+    return next_tok, next_parent

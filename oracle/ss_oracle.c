@@ -1,0 +1,339 @@
+/*
+ * ss_oracle.c — TEST INFRASTRUCTURE, not part of the product.
+ *
+ * A plain, slow CPU statement of what the verify-and-speculate step of
+ * Speculative Streaming (arXiv 2402.11131) computes, written from the paper.
+ * Floating point is done in double.  Nothing here is blocked, fused or
+ * reordered: every function is the definition written out as loops, so that it
+ * can be checked against the paper by eye.  It shares no code with the HIP
+ * library and must only be used by the tests, by the smoke check and by the
+ * CPU-baseline leg of the benchmark.
+ *
+ * Row order inside a sequence of T tree nodes with gamma streams
+ * (R = T*(1+gamma) rows, the batch size of Sec. 3.2.3):
+ *   main row of node i: r = i;  stream j (1..gamma) of node i: r = T+i*gamma+j-1.
+ * Node 0 is the root, parent[0] = -1, parent[i] < i.
+ *
+ * Readings of the paper used here (each is pinned by a test):
+ *  - Eq. 2 writes S_{t(<=j)}: stream j sees streams 1..j of ITS OWN node, itself
+ *    included.  Flag ORA_EXCLUDE_SELF gives the strict reading 1..j-1.
+ *  - Eq. 4 as printed only links adjacent levels; the appendix attention-mask
+ *    figure says a node attends to all its predecessors from the root and to
+ *    itself, and that tokens are replicated per path, so ancestry follows
+ *    parent[] and siblings / other branches are invisible.
+ *  - "time step t" of Eq. 1/2 for a tree is a tree NODE: the streams of node i
+ *    see the main rows of i's ancestors-or-self and i's own streams only; main
+ *    rows never see stream keys.
+ *  - Verification (Appendix A.1, "hard" matching): root always accepted; a node
+ *    is accepted iff its parent is and its token equals the main-stream argmax
+ *    at the parent; the deepest accepted node wins, ties -> lowest index.
+ *  - Drafting (Sec. 3.2.2, Appendix A.1): new root = argmax at the last accepted
+ *    node; level j of the new tree = top-k tokens of stream j of that node.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define ORA_EXCLUDE_SELF 1u
+
+/* ------------------------------------------------------------------ tree */
+
+/* Parent of node i with the same clamping rule the ABI documents: node 0 is the
+ * root; for i > 0 a parent outside [0,i) counts as 0. */
+static int ora_parent(const int32_t* parent, int i) {
+  if (i == 0) return -1;
+  int p = parent[i];
+  if (p < 0 || p >= i) return 0;
+  return p;
+}
+
+/* depth = number of edges from the root (walk up). */
+static int ora_depth(const int32_t* parent, int i) {
+  int d = 0;
+  while (i > 0) {
+    i = ora_parent(parent, i);
+    d++;
+  }
+  return d;
+}
+
+/* 1 iff a lies on the path root..i (a == i counts). */
+static int ora_is_anc_or_self(const int32_t* parent, int a, int i) {
+  while (i >= 0) {
+    if (i == a) return 1;
+    i = ora_parent(parent, i);
+  }
+  return 0;
+}
+
+/* row -> (node, stream); stream 0 = main row. */
+static void ora_row_split(int r, int T, int gamma, int* node, int* strm) {
+  if (r < T) {
+    *node = r;
+    *strm = 0;
+  } else {
+    *node = (r - T) / gamma;
+    *strm = (r - T) % gamma + 1;
+  }
+}
+
+/* May row (i,j) attend the step's own key (i2,j2)?  Eq. 1, Eq. 2, Eq. 4 with the
+ * appendix figure's reading. */
+static int ora_visible(const int32_t* parent, int i, int j, int i2, int j2, uint32_t flags) {
+  if (j2 == 0) return ora_is_anc_or_self(parent, i2, i); /* main key: ancestors and self */
+  if (j == 0) return 0;                                  /* main rows never see stream keys */
+  if (i2 != i) return 0;                                 /* only the node's own streams */
+  return (flags & ORA_EXCLUDE_SELF) ? (j2 < j) : (j2 <= j);
+}
+
+/* a1: depth, ancestor bit sets and the dense R x R boolean mask.  Any output may be NULL. */
+void ora_build_mask(const int32_t* parent, int B, int T, int gamma, uint32_t flags, uint8_t* mask,
+                    uint64_t* anc, int32_t* depth) {
+  int R = T * (1 + gamma);
+  for (int b = 0; b < B; b++) {
+    const int32_t* par = parent + (size_t)b * T;
+    for (int i = 0; i < T; i++) {
+      if (depth) depth[(size_t)b * T + i] = ora_depth(par, i);
+      if (anc) {
+        uint64_t bits = 0;
+        for (int a = 0; a < T; a++)
+          if (ora_is_anc_or_self(par, a, i)) bits |= (uint64_t)1 << a;
+        anc[(size_t)b * T + i] = bits;
+      }
+    }
+    if (!mask) continue;
+    for (int r = 0; r < R; r++) {
+      int i, j;
+      ora_row_split(r, T, gamma, &i, &j);
+      for (int c = 0; c < R; c++) {
+        int i2, j2;
+        ora_row_split(c, T, gamma, &i2, &j2);
+        mask[((size_t)b * R + r) * R + c] = (uint8_t)ora_visible(par, i, j, i2, j2, flags);
+      }
+    }
+  }
+}
+
+/* ------------------------------------------------------------------ MSA */
+
+/*
+ * a2: multi-stream attention, Eq. 1 (main rows) and Eq. 2 (stream rows), one
+ * layer.  Inputs are float arrays holding exactly the stored values (a bf16
+ * tensor is passed up-cast); all arithmetic is double; out is double.
+ * Layouts as in the ABI: q/out [B,R,H,D], k_new/v_new [B,R,Hkv,D], k_cache
+ * [pages,Hkv,page,D], v_cache [pages,Hkv,D,page], block_table [B,max_pages].
+ */
+void ora_msa_attention(const float* q, const float* k_new, const float* v_new, const float* k_cache,
+                       const float* v_cache, const int32_t* block_table, int max_pages,
+                       const int32_t* seq_lens, const int32_t* parent, int B, int T, int gamma, int H,
+                       int Hkv, int D, int page, double scale, uint32_t flags, double* out) {
+  int R = T * (1 + gamma);
+  int g = H / Hkv;
+#pragma omp parallel for collapse(2) schedule(dynamic)
+  for (int b = 0; b < B; b++) {
+    for (int h = 0; h < H; h++) {
+      int hk = h / g;
+      int L = seq_lens[b];
+      if (L < 0) L = 0;
+      if (L > max_pages * page) L = max_pages * page;
+      const int32_t* par = parent + (size_t)b * T;
+      int C = L + R; /* keys: L cached main-stream tokens, then the R new rows */
+      double* s = (double*)malloc(sizeof(double) * (size_t)C);
+      double* o = (double*)malloc(sizeof(double) * (size_t)D);
+      for (int r = 0; r < R; r++) {
+        int i, j;
+        ora_row_split(r, T, gamma, &i, &j);
+        const float* qv = q + (((size_t)b * R + r) * H + h) * D;
+        /* scores; masked keys get -inf */
+        for (int c = 0; c < C; c++) {
+          double dot = 0.0;
+          if (c < L) {
+            size_t pg = (size_t)block_table[(size_t)b * max_pages + c / page];
+            const float* kv = k_cache + ((pg * Hkv + hk) * page + (size_t)(c % page)) * D;
+            for (int d = 0; d < D; d++) dot += (double)qv[d] * (double)kv[d];
+            s[c] = scale * dot;
+          } else {
+            int i2, j2;
+            ora_row_split(c - L, T, gamma, &i2, &j2);
+            if (ora_visible(par, i, j, i2, j2, flags)) {
+              const float* kv = k_new + (((size_t)b * R + (c - L)) * Hkv + hk) * D;
+              for (int d = 0; d < D; d++) dot += (double)qv[d] * (double)kv[d];
+              s[c] = scale * dot;
+            } else {
+              s[c] = -INFINITY;
+            }
+          }
+        }
+        /* softmax over all keys (the row's own key is always visible, so max is finite) */
+        double mx = -INFINITY;
+        for (int c = 0; c < C; c++)
+          if (s[c] > mx) mx = s[c];
+        double den = 0.0;
+        for (int c = 0; c < C; c++) {
+          s[c] = (s[c] == -INFINITY) ? 0.0 : exp(s[c] - mx);
+          den += s[c];
+        }
+        /* weighted sum of values */
+        for (int d = 0; d < D; d++) o[d] = 0.0;
+        for (int c = 0; c < C; c++) {
+          double p = s[c] / den;
+          if (p == 0.0) continue;
+          if (c < L) {
+            size_t pg = (size_t)block_table[(size_t)b * max_pages + c / page];
+            const float* vv = v_cache + (pg * Hkv + hk) * (size_t)D * page + (size_t)(c % page);
+            for (int d = 0; d < D; d++) o[d] += p * (double)vv[(size_t)d * page];
+          } else {
+            const float* vv = v_new + (((size_t)b * R + (c - L)) * Hkv + hk) * D;
+            for (int d = 0; d < D; d++) o[d] += p * (double)vv[d];
+          }
+        }
+        double* ov = out + (((size_t)b * R + r) * H + h) * D;
+        for (int d = 0; d < D; d++) ov[d] = o[d];
+      }
+      free(s);
+      free(o);
+    }
+  }
+}
+
+/* ------------------------------------------------------------------ LM head */
+
+typedef struct {
+  double z;
+  int32_t v;
+} ora_cand;
+
+/* larger logit first; equal logits -> lower token id first */
+static int ora_cand_cmp(const void* a, const void* b) {
+  const ora_cand* x = (const ora_cand*)a;
+  const ora_cand* y = (const ora_cand*)b;
+  if (x->z > y->z) return -1;
+  if (x->z < y->z) return 1;
+  return (x->v > y->v) - (x->v < y->v);
+}
+
+/*
+ * a3: z[n,v] = sum_d hidden[n,d]*W[v,d] in double, then a full sort of every
+ * row; idx/val get the first K entries.  If logits != NULL it receives all of
+ * z ([N,V] doubles).
+ */
+void ora_lm_head_topk(const float* hidden, const float* W, int N, int d, int V, int K, int32_t* idx,
+                      double* val, double* logits) {
+#pragma omp parallel for schedule(dynamic)
+  for (int n = 0; n < N; n++) {
+    ora_cand* c = (ora_cand*)malloc(sizeof(ora_cand) * (size_t)V);
+    for (int v = 0; v < V; v++) {
+      double acc = 0.0;
+      const float* hv = hidden + (size_t)n * d;
+      const float* wv = W + (size_t)v * d;
+      for (int e = 0; e < d; e++) acc += (double)hv[e] * (double)wv[e];
+      c[v].z = acc;
+      c[v].v = v;
+      if (logits) logits[(size_t)n * V + v] = acc;
+    }
+    qsort(c, (size_t)V, sizeof(ora_cand), ora_cand_cmp);
+    for (int k = 0; k < K; k++) {
+      idx[(size_t)n * K + k] = c[k].v;
+      val[(size_t)n * K + k] = c[k].z;
+    }
+    free(c);
+  }
+}
+
+/* ------------------------------------------------------------------ verify */
+
+/*
+ * a4: greedy longest-path verification.  a[i] = main-stream argmax token at
+ * node i, read at main_argmax[b*batch_stride + i*node_stride].
+ */
+void ora_tree_verify(const int32_t* tok, const int32_t* parent, const int32_t* main_argmax,
+                     long batch_stride, long node_stride, int B, int T, int max_depth,
+                     int32_t* n_accept, int32_t* last, int32_t* bonus, int32_t* path,
+                     int32_t* out_tokens) {
+  for (int b = 0; b < B; b++) {
+    const int32_t* par = parent + (size_t)b * T;
+    const int32_t* tk = tok + (size_t)b * T;
+    const int32_t* a = main_argmax + (size_t)b * batch_stride;
+    int ok[64];
+    int best = 0, best_depth = 0;
+    ok[0] = 1;
+    for (int i = 1; i < T; i++) {
+      int p = ora_parent(par, i);
+      int dep = ora_depth(par, i);
+      ok[i] = ok[p] && tk[i] == a[(size_t)p * node_stride] && dep <= max_depth;
+      if (ok[i] && dep > best_depth) {
+        best = i;
+        best_depth = dep;
+      }
+    }
+    n_accept[b] = best_depth;
+    last[b] = best;
+    bonus[b] = a[(size_t)best * node_stride];
+    int32_t* pth = path + (size_t)b * (max_depth + 1);
+    int32_t* ot = out_tokens + (size_t)b * (max_depth + 1);
+    for (int k = 0; k <= max_depth; k++) {
+      pth[k] = -1;
+      ot[k] = -1;
+    }
+    for (int n = best, k = best_depth; n >= 0; n = ora_parent(par, n), k--) pth[k] = n;
+    for (int k = 1; k <= best_depth; k++) ot[k - 1] = tk[pth[k]];
+    ot[best_depth] = bonus[b];
+  }
+}
+
+/* ------------------------------------------------------------------ draft */
+
+/*
+ * Full tree with branching[j-1] children per node of level j-1: nodes numbered
+ * level by level, inside a level by (parent, rank).  Returns the node count
+ * (1 + sum_j prod_{m<=j} branching[m-1]; uniform k: 1 + sum_g k^g, Sec. 3.2.3)
+ * or -1 if it exceeds capacity.  Outputs may be NULL.
+ */
+int ora_full_tree_template(const int32_t* branching, int gamma, int capacity, int32_t* parent_out,
+                           int32_t* rank_out, int32_t* depth_out) {
+  int n = 1, level_begin = 0, level_end = 1;
+  if (capacity < 1) return -1;
+  if (parent_out) parent_out[0] = -1;
+  if (rank_out) rank_out[0] = 0;
+  if (depth_out) depth_out[0] = 0;
+  for (int j = 1; j <= gamma; j++) {
+    int k = branching[j - 1];
+    for (int p = level_begin; p < level_end; p++) {
+      for (int r = 0; r < k; r++) {
+        if (n >= capacity) return -1;
+        if (parent_out) parent_out[n] = p;
+        if (rank_out) rank_out[n] = r;
+        if (depth_out) depth_out[n] = j;
+        n++;
+      }
+    }
+    level_begin = level_end;
+    level_end = n;
+  }
+  return n;
+}
+
+/*
+ * a5: next tree draft from a template.  stream_topk[b*batch_stride +
+ * ((i*gamma)+(j-1))*K + rank] = rank-th token of stream j of node i.
+ */
+void ora_tree_draft(const int32_t* stream_topk, long batch_stride, int K, const int32_t* last,
+                    const int32_t* bonus, const int32_t* tmpl_parent, const int32_t* tmpl_rank, int B,
+                    int T, int gamma, int T2, int32_t* next_tok, int32_t* next_parent) {
+  (void)T;
+  for (int b = 0; b < B; b++) {
+    const int32_t* tk = stream_topk + (size_t)b * batch_stride;
+    int node = last[b];
+    next_tok[(size_t)b * T2] = bonus[b];
+    for (int i = 1; i < T2; i++) {
+      int j = ora_depth(tmpl_parent, i); /* level j draws from stream j */
+      int r = tmpl_rank[i];
+      int32_t t = -1;
+      if (j >= 1 && j <= gamma && r >= 0 && r < K) t = tk[((size_t)node * gamma + (j - 1)) * K + r];
+      next_tok[(size_t)b * T2 + i] = t;
+    }
+  }
+  if (next_parent)
+    for (int i = 0; i < T2; i++) next_parent[i] = (i == 0) ? -1 : ora_parent(tmpl_parent, i);
+}
