@@ -97,8 +97,9 @@ int ss_check_tree_host(const int32_t* parent, int B, int T, int max_depth);
  *  parent [B,T] int32 in;  mask [B,R,R] uint8 out (1 = may attend), may be NULL;
  *  anc [B,T] uint64 out or NULL;  depth [B,T] int32 out or NULL.
  * Limits: 1 <= T <= SS_MAX_T, 0 <= gamma <= SS_MAX_GAMMA.
- * An entry parent[i] outside [-1, i) is treated as -1 for i == 0 and as 0
- * otherwise (see "Conventions").
+ * Node 0 is always taken as the root; for i > 0 an entry parent[i] outside
+ * [0, i) is treated as 0 (see "Conventions").  All calls that read a parent
+ * array apply this rule.
  */
 int ss_build_mask(const int32_t* parent, int B, int T, int gamma, uint32_t flags,
                   uint8_t* mask, uint64_t* anc, int32_t* depth, void* stream);
@@ -116,7 +117,9 @@ int ss_build_mask(const int32_t* parent, int B, int T, int gamma, uint32_t flags
  *  k_cache [num_pages, Hkv, page_size, D]   token-major pages
  *  v_cache [num_pages, Hkv, D, page_size]   feature-major pages: the value of
  *          token s of a page, feature d, sits at [page, hkv, d, s]
- *  block_table [B, max_pages_per_seq] int32: physical page of logical page p
+ *  block_table [B, max_pages_per_seq] int32: physical page of logical page p,
+ *          in [0, num_pages); entries outside that range are clamped on device
+ *          (num_pages = first extent of k_cache / v_cache)
  *  seq_lens [B] int32: cached tokens per sequence, 0 <= seq_lens[b] <=
  *          max_pages_per_seq*page_size (larger values are clamped on device)
  *  parent [B,T] int32 as in a1.
@@ -131,9 +134,10 @@ size_t ss_msa_workspace_bytes(int B, int T, int gamma, int H, int Hkv, int D, in
                               int dtype);
 int ss_msa_attention(const void* q, const void* k_new, const void* v_new, const void* k_cache,
                      const void* v_cache, const int32_t* block_table, int max_pages_per_seq,
-                     const int32_t* seq_lens, const int32_t* parent, int B, int T, int gamma, int H,
-                     int Hkv, int D, int page_size, float scale, int dtype, uint32_t flags,
-                     void* out, void* workspace, size_t workspace_bytes, void* stream);
+                     int num_pages, const int32_t* seq_lens, const int32_t* parent, int B, int T,
+                     int gamma, int H, int Hkv, int D, int page_size, float scale, int dtype,
+                     uint32_t flags, void* out, void* workspace, size_t workspace_bytes,
+                     void* stream);
 
 /*
  * Tuning knob for a2: number of cached tokens one workgroup scans (the KV

@@ -1,0 +1,268 @@
+"""Python binding of libss.so: argument marshalling only.
+
+Every function has the name of the C entry point it calls (see include/ss.h),
+takes torch tensors that already live on the GPU, checks their shapes / dtypes /
+contiguity, and passes raw device pointers plus the current HIP stream.  Output
+tensors and workspaces are allocated here with torch when the caller does not
+pass them; no arithmetic of the method happens in Python.  There is no CPU
+fallback: if libss.so has not been built, the first call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libss.so")
+
+SS_OK = 0
+SS_F32, SS_BF16 = 0, 1
+SS_STREAM_EXCLUDE_SELF = 1
+SS_MAX_T, SS_MAX_GAMMA, SS_MAX_K = 64, 8, 8
+
+EXPORTS = (
+    "ss_version", "ss_last_error", "ss_check_tree_host", "ss_build_mask", "ss_msa_workspace_bytes",
+    "ss_msa_attention", "ss_msa_set_split_keys", "ss_lm_head_workspace_bytes", "ss_lm_head_argmax_topk",
+    "ss_tree_verify", "ss_tree_draft", "ss_full_tree_template_host",
+)
+
+_lib = None
+
+
+class SSError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__("libss error %d: %s" % (code, msg))
+        self.code = code
+
+
+def load_library() -> ctypes.CDLL:
+    """Loads libss.so (after torch, so that both share one HIP runtime)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            "libss.so is not built (%s missing): run `python -m paper_2402_11131_amd.build` "
+            "or __graft_entry__.build(); there is no fallback path" % LIB_PATH)
+    lib = ctypes.CDLL(LIB_PATH)
+    c = ctypes
+    vp, i32, u32, sz, lng = c.c_void_p, c.c_int, c.c_uint32, c.c_size_t, c.c_long
+    lib.ss_version.restype = i32
+    lib.ss_last_error.restype = c.c_char_p
+    lib.ss_check_tree_host.argtypes = [vp, i32, i32, i32]
+    lib.ss_build_mask.argtypes = [vp, i32, i32, i32, u32, vp, vp, vp, vp]
+    lib.ss_msa_workspace_bytes.argtypes = [i32] * 8
+    lib.ss_msa_workspace_bytes.restype = sz
+    lib.ss_msa_attention.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, i32, i32, i32, i32, i32, i32, i32,
+                                     c.c_float, i32, u32, vp, vp, sz, vp]
+    lib.ss_msa_set_split_keys.argtypes = [i32]
+    lib.ss_lm_head_workspace_bytes.argtypes = [i32] * 5
+    lib.ss_lm_head_workspace_bytes.restype = sz
+    lib.ss_lm_head_argmax_topk.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, sz, vp]
+    lib.ss_tree_verify.argtypes = [vp, vp, vp, lng, lng, i32, i32, i32, vp, vp, vp, vp, vp, vp]
+    lib.ss_tree_draft.argtypes = [vp, lng, i32, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, vp]
+    lib.ss_full_tree_template_host.argtypes = [vp, i32, i32, vp, vp, vp]
+    for name in EXPORTS:
+        getattr(lib, name)
+    _lib = lib
+    return lib
+
+
+def _check(rc: int):
+    if rc != SS_OK:
+        raise SSError(rc, load_library().ss_last_error().decode())
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dev(t: torch.Tensor, dtype, name: str) -> int:
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous() and t.dtype == dtype):
+        raise TypeError("%s must be a contiguous GPU tensor of dtype %s" % (name, dtype))
+    return t.data_ptr()
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return SS_F32
+    if t.dtype == torch.bfloat16:
+        return SS_BF16
+    raise TypeError("unsupported dtype %s" % t.dtype)
+
+
+def ss_version() -> int:
+    return load_library().ss_version()
+
+
+def ss_check_tree_host(parent, max_depth: int = -1) -> None:
+    """parent: CPU int32 tensor [B,T].  Raises SSError on a malformed tree."""
+    p = parent.to(torch.int32).contiguous().cpu()
+    B, T = p.shape
+    _check(load_library().ss_check_tree_host(p.data_ptr(), B, T, max_depth))
+
+
+def ss_build_mask(parent: torch.Tensor, gamma: int, flags: int = 0, want_mask: bool = True):
+    """a1.  parent [B,T] int32 -> (mask [B,R,R] uint8 or None, anc [B,T] int64 (bit pattern of the
+    uint64 ancestor sets), depth [B,T] int32)."""
+    lib = load_library()
+    B, T = parent.shape
+    R = T * (1 + gamma)
+    dev = parent.device
+    mask = torch.empty((B, R, R), dtype=torch.uint8, device=dev) if want_mask else None
+    anc = torch.empty((B, T), dtype=torch.int64, device=dev)
+    depth = torch.empty((B, T), dtype=torch.int32, device=dev)
+    _check(lib.ss_build_mask(_dev(parent, torch.int32, "parent"), B, T, gamma, flags,
+                             mask.data_ptr() if want_mask else None, anc.data_ptr(), depth.data_ptr(), _stream()))
+    return mask, anc, depth
+
+
+def ss_msa_workspace_bytes(B, T, gamma, H, Hkv, D, max_seq_len, dtype_code) -> int:
+    return load_library().ss_msa_workspace_bytes(B, T, gamma, H, Hkv, D, max_seq_len, dtype_code)
+
+
+def ss_msa_set_split_keys(split_keys: int) -> int:
+    return load_library().ss_msa_set_split_keys(int(split_keys))
+
+
+def ss_msa_attention(q, k_new, v_new, k_cache, v_cache, block_table, seq_lens, parent, gamma: int, scale: float,
+                     flags: int = 0, out: Optional[torch.Tensor] = None,
+                     workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """a2.  q [B,R,H,D]; k_new, v_new [B,R,Hkv,D]; k_cache [P,Hkv,page,D]; v_cache [P,Hkv,D,page];
+    block_table [B,max_pages] int32; seq_lens [B] int32; parent [B,T] int32.  Returns out [B,R,H,D]."""
+    lib = load_library()
+    dt = q.dtype
+    code = _dtype_code(q)
+    B, R, H, D = q.shape
+    Hkv = k_new.shape[2]
+    T = parent.shape[1]
+    P, _, page, _ = k_cache.shape
+    if R != T * (1 + gamma) or tuple(k_new.shape) != (B, R, Hkv, D) or tuple(v_new.shape) != (B, R, Hkv, D):
+        raise ValueError("q / k_new / v_new shapes do not match B,R,H,Hkv,D")
+    if tuple(k_cache.shape) != (P, Hkv, page, D) or tuple(v_cache.shape) != (P, Hkv, D, page):
+        raise ValueError("k_cache must be [P,Hkv,page,D] and v_cache [P,Hkv,D,page]")
+    if block_table.shape[0] != B or tuple(seq_lens.shape) != (B,) or parent.shape[0] != B:
+        raise ValueError("block_table / seq_lens / parent batch size mismatch")
+    max_pages = block_table.shape[1]
+    if out is None:
+        out = torch.empty_like(q)
+    need = lib.ss_msa_workspace_bytes(B, T, gamma, H, Hkv, D, max_pages * page, code)
+    if workspace is None:
+        workspace = torch.empty(max(need, 1), dtype=torch.uint8, device=q.device)
+    _check(lib.ss_msa_attention(
+        _dev(q, dt, "q"), _dev(k_new, dt, "k_new"), _dev(v_new, dt, "v_new"), _dev(k_cache, dt, "k_cache"),
+        _dev(v_cache, dt, "v_cache"), _dev(block_table, torch.int32, "block_table"), max_pages, P,
+        _dev(seq_lens, torch.int32, "seq_lens"), _dev(parent, torch.int32, "parent"), B, T, gamma, H, Hkv, D, page,
+        float(scale), code, flags, _dev(out, dt, "out"), _dev(workspace, torch.uint8, "workspace"),
+        workspace.numel(), _stream()))
+    return out
+
+
+def ss_lm_head_workspace_bytes(N, d, V, K, dtype_code) -> int:
+    return load_library().ss_lm_head_workspace_bytes(N, d, V, K, dtype_code)
+
+
+def ss_lm_head_argmax_topk(hidden, W, K: int, idx=None, val=None, workspace=None):
+    """a3.  hidden [N,d], W [V,d] -> (idx [N,K] int32, val [N,K] float32)."""
+    lib = load_library()
+    dt = hidden.dtype
+    code = _dtype_code(hidden)
+    N, d = hidden.shape
+    V = W.shape[0]
+    if W.shape[1] != d:
+        raise ValueError("hidden and W disagree on d")
+    if idx is None:
+        idx = torch.empty((N, K), dtype=torch.int32, device=hidden.device)
+    if val is None:
+        val = torch.empty((N, K), dtype=torch.float32, device=hidden.device)
+    need = lib.ss_lm_head_workspace_bytes(N, d, V, K, code)
+    if workspace is None:
+        workspace = torch.empty(max(need, 1), dtype=torch.uint8, device=hidden.device)
+    _check(lib.ss_lm_head_argmax_topk(_dev(hidden, dt, "hidden"), _dev(W, dt, "W"), N, d, V, K, code,
+                                      _dev(idx, torch.int32, "idx"), _dev(val, torch.float32, "val"),
+                                      _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream()))
+    return idx, val
+
+
+def ss_tree_verify(tok, parent, main_argmax, max_depth: int, batch_stride: Optional[int] = None,
+                   node_stride: Optional[int] = None, offset: int = 0) -> dict:
+    """a4.  tok, parent [B,T] int32.  main_argmax: int32 GPU tensor; the arg-max token of main row i
+    of sequence b is element offset + b*batch_stride + i*node_stride of its storage (defaults: a
+    contiguous [B,T] tensor)."""
+    lib = load_library()
+    B, T = tok.shape
+    if batch_stride is None:
+        batch_stride, node_stride = T, 1
+    dev = tok.device
+    i32 = torch.int32
+    res = dict(n_accept=torch.empty(B, dtype=i32, device=dev), last=torch.empty(B, dtype=i32, device=dev),
+               bonus=torch.empty(B, dtype=i32, device=dev),
+               path=torch.empty((B, max_depth + 1), dtype=i32, device=dev),
+               out_tokens=torch.empty((B, max_depth + 1), dtype=i32, device=dev))
+    need = offset + (B - 1) * batch_stride + (T - 1) * node_stride + 1 if B > 0 else 0
+    if main_argmax.numel() < need:
+        raise ValueError("main_argmax too small for the given strides")
+    _check(lib.ss_tree_verify(_dev(tok, i32, "tok"), _dev(parent, i32, "parent"),
+                              _dev(main_argmax, i32, "main_argmax") + 4 * offset, batch_stride, node_stride, B, T,
+                              max_depth, res["n_accept"].data_ptr(), res["last"].data_ptr(),
+                              res["bonus"].data_ptr(), res["path"].data_ptr(), res["out_tokens"].data_ptr(),
+                              _stream()))
+    return res
+
+
+def ss_full_tree_template_host(branching: Sequence[int], capacity: int = SS_MAX_T):
+    """Host helper: full tree with per-level branching -> (parent, rank, depth) CPU int32 tensors."""
+    lib = load_library()
+    br = torch.tensor(list(branching), dtype=torch.int32)
+    par = torch.zeros(SS_MAX_T, dtype=torch.int32)
+    rank = torch.zeros(SS_MAX_T, dtype=torch.int32)
+    dep = torch.zeros(SS_MAX_T, dtype=torch.int32)
+    n = lib.ss_full_tree_template_host(br.data_ptr(), len(branching), capacity, par.data_ptr(), rank.data_ptr(),
+                                       dep.data_ptr())
+    if n < 0:
+        raise SSError(2, lib.ss_last_error().decode())
+    return par[:n].clone(), rank[:n].clone(), dep[:n].clone()
+
+
+def ss_tree_draft(stream_topk, K: int, last, bonus, T: int, gamma: int, tmpl_parent=None, tmpl_rank=None,
+                  branching: Optional[Sequence[int]] = None, T2: Optional[int] = None,
+                  batch_stride: Optional[int] = None, offset: int = 0):
+    """a5.  stream_topk: int32 GPU tensor; rank-th token of stream j of node i of sequence b is element
+    offset + b*batch_stride + ((i*gamma)+(j-1))*K + rank (default: contiguous [B,T,gamma,K]).
+    Template: device tensors tmpl_parent/tmpl_rank [T2], or per-level `branching`.
+    Returns (next_tok [B,T2], next_parent [T2])."""
+    lib = load_library()
+    B = last.shape[0]
+    i32 = torch.int32
+    if batch_stride is None:
+        batch_stride = T * gamma * K
+    br_ptr = None
+    br = None
+    if tmpl_parent is None:
+        if branching is None:
+            raise ValueError("give a template or per-level branching")
+        br = torch.tensor(list(branching), dtype=i32)
+        br_ptr = br.data_ptr()
+        if T2 is None:
+            T2 = 1
+            width = 1
+            for k in branching:
+                width *= int(k)
+                T2 += width
+    else:
+        T2 = tmpl_parent.shape[0]
+    dev = last.device
+    next_tok = torch.empty((B, T2), dtype=i32, device=dev)
+    next_parent = torch.empty(T2, dtype=i32, device=dev)
+    need = offset + (B - 1) * batch_stride + T * gamma * K if B > 0 else 0
+    if stream_topk.numel() < need:
+        raise ValueError("stream_topk too small for the given strides")
+    _check(lib.ss_tree_draft(_dev(stream_topk, i32, "stream_topk") + 4 * offset, batch_stride, K,
+                             _dev(last, i32, "last"), _dev(bonus, i32, "bonus"),
+                             None if tmpl_parent is None else _dev(tmpl_parent, i32, "tmpl_parent"),
+                             None if tmpl_rank is None else _dev(tmpl_rank, i32, "tmpl_rank"), br_ptr, B, T, gamma,
+                             T2, next_tok.data_ptr(), next_parent.data_ptr(), _stream()))
+    return next_tok, next_parent

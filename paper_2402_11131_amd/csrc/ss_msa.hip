@@ -1,0 +1,345 @@
+// a2: multi-stream attention (Eq. 1 main rows, Eq. 2 stream rows) over a paged
+// KV cache.  This file holds the entry point, the split planning, the fp32
+// kernel and the kernel that merges the per-split partial results.
+#include <math.h>
+#include <stdlib.h>
+
+#include "ss_msa.h"
+
+namespace ss {
+
+// ------------------------------------------------------------------ fp32 kernel
+//
+// One workgroup = (row chunk of 32 rows, split, sequence, head); wave w owns 8 of
+// the rows.  Keys are taken 64 at a time: the K tile sits in LDS token-major
+// (padded), the V tile feature-major (padded); in the score phase a lane owns a
+// key, in the P.V phase it owns output features.  Softmax is the usual running
+// max / running sum in the log2 domain.
+template <int D>
+__global__ __launch_bounds__(256) void msa_f32_kernel(MsaArgs a) {
+  constexpr int RC = 32, RW = 8, KT = 64, DL = D / 64;
+  __shared__ float Qs[RC][D];
+  __shared__ float Ks[KT][D + 1];
+  __shared__ float Vs[D][KT + 1];
+  __shared__ float Ps[4][RW][KT];
+  __shared__ int par[SS_MAX_T];
+  __shared__ uint64_t anc[SS_MAX_T];
+
+  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+  const int chunk = blockIdx.x, s = blockIdx.y;
+  const int b = blockIdx.z / a.H, h = blockIdx.z % a.H, hk = h / a.g;
+  const int L = clamp_len(a.seq_lens[b], a);
+  const int n_active = active_splits(L, a);
+  if (s >= n_active) return;
+  const bool is_last = (s == n_active - 1);
+  const int k0 = s * a.split_keys;
+  const int n_prefix = max(0, min(L, k0 + a.split_keys) - k0);
+  const int n_new = is_last ? a.R : 0;
+  const int total = n_prefix + n_new;
+  const int r0 = chunk * RC;
+  const int R = a.R, T = a.T;
+
+  const float* q = (const float*)a.q;
+  const float* k_new = (const float*)a.k_new;
+  const float* v_new = (const float*)a.v_new;
+  const float* k_cache = (const float*)a.k_cache;
+  const float* v_cache = (const float*)a.v_cache;
+
+  if (tid < T) par[tid] = clamp_parent(a.parent[(size_t)b * T + tid], tid);
+  for (int e = tid; e < RC * D; e += 256) {
+    const int r = e / D, d = e % D;
+    Qs[r][d] = (r0 + r < R) ? q[(((size_t)b * R + r0 + r) * a.H + h) * D + d] : 0.f;
+  }
+  __syncthreads();
+  compute_anc(par, T, anc, tid);
+  __syncthreads();
+
+  RowVis vis[RW];
+  float m[RW], l[RW], o[RW][DL];
+#pragma unroll
+  for (int i = 0; i < RW; ++i) {
+    vis[i] = make_row_vis(min(r0 + w * RW + i, R - 1), T, a.gamma, anc, (a.flags & SS_STREAM_EXCLUDE_SELF) != 0);
+    m[i] = -1e30f;
+    l[i] = 0.f;
+#pragma unroll
+    for (int dd = 0; dd < DL; ++dd) o[i][dd] = 0.f;
+  }
+
+  for (int t0 = 0; t0 < total; t0 += KT) {
+    __syncthreads();  // the previous tile has been consumed
+    // K tile: consecutive threads take consecutive features of one key
+    for (int e = tid; e < KT * D; e += 256) {
+      const int kk = e / D, d = e % D, u = t0 + kk;
+      float v = 0.f;
+      if (u < n_prefix) {
+        const int tok = k0 + u;
+        int pg = a.block_table[(size_t)b * a.max_pages + (tok >> a.page_shift)];
+        pg = min(max(pg, 0), a.num_pages - 1);
+        v = k_cache[(((size_t)pg * a.Hkv + hk) * a.page + (tok & (a.page - 1))) * D + d];
+      } else if (u < total) {
+        v = k_new[(((size_t)b * R + (u - n_prefix)) * a.Hkv + hk) * D + d];
+      }
+      Ks[kk][d] = v;
+    }
+    // V tile: consecutive threads take consecutive tokens (contiguous inside a feature-major page)
+    for (int e = tid; e < KT * D; e += 256) {
+      const int kk = e % KT, d = e / KT, u = t0 + kk;
+      float v = 0.f;
+      if (u < n_prefix) {
+        const int tok = k0 + u;
+        int pg = a.block_table[(size_t)b * a.max_pages + (tok >> a.page_shift)];
+        pg = min(max(pg, 0), a.num_pages - 1);
+        v = v_cache[(((size_t)pg * a.Hkv + hk) * D + d) * a.page + (tok & (a.page - 1))];
+      } else if (u < total) {
+        v = v_new[(((size_t)b * R + (u - n_prefix)) * a.Hkv + hk) * D + d];
+      }
+      Vs[d][kk] = v;
+    }
+    __syncthreads();
+
+    // scores of this lane's key against the wave's 8 rows
+    float sc[RW];
+#pragma unroll
+    for (int i = 0; i < RW; ++i) sc[i] = 0.f;
+#pragma unroll 4
+    for (int d = 0; d < D; ++d) {
+      const float kd = Ks[lane][d];
+#pragma unroll
+      for (int i = 0; i < RW; ++i) sc[i] = fmaf(Qs[w * RW + i][d], kd, sc[i]);
+    }
+    const int u = t0 + lane;
+#pragma unroll
+    for (int i = 0; i < RW; ++i) {
+      bool vis_ok = u < total;
+      if (u >= n_prefix) vis_ok = vis_ok && row_sees(vis[i], u - n_prefix, T);
+      const float sv = vis_ok ? sc[i] * a.scale_log2 : -INFINITY;
+      float mx = sv;
+      for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+      const float m_new = fmaxf(m[i], mx);
+      const float alpha = exp2f(m[i] - m_new);
+      const float p = exp2f(sv - m_new);
+      float ps = p;
+      for (int off = 32; off > 0; off >>= 1) ps += __shfl_xor(ps, off, 64);
+      l[i] = l[i] * alpha + ps;
+      m[i] = m_new;
+#pragma unroll
+      for (int dd = 0; dd < DL; ++dd) o[i][dd] *= alpha;
+      Ps[w][i][lane] = p;
+    }
+    // P.V: a lane owns output features lane, lane+64; the probabilities of the wave's
+    // rows are read back from LDS (same address for all lanes: a broadcast)
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll 4
+    for (int kk = 0; kk < KT; ++kk) {
+      float vk[DL];
+#pragma unroll
+      for (int dd = 0; dd < DL; ++dd) vk[dd] = Vs[lane + 64 * dd][kk];
+#pragma unroll
+      for (int i = 0; i < RW; ++i) {
+        const float pk = Ps[w][i][kk];
+#pragma unroll
+        for (int dd = 0; dd < DL; ++dd) o[i][dd] = fmaf(pk, vk[dd], o[i][dd]);
+      }
+    }
+  }
+
+#pragma unroll
+  for (int i = 0; i < RW; ++i) {
+    const int row = r0 + w * RW + i;
+    if (row >= R) continue;
+    const float inv = l[i] > 0.f ? 1.f / l[i] : 0.f;
+    if (a.n_splits == 1) {
+      float* out = (float*)a.out + (((size_t)b * R + row) * a.H + h) * D;
+#pragma unroll
+      for (int dd = 0; dd < DL; ++dd) out[lane + 64 * dd] = o[i][dd] * inv;
+    } else {
+      const size_t pr = (((size_t)b * a.H + h) * a.n_splits + s) * R + row;
+#pragma unroll
+      for (int dd = 0; dd < DL; ++dd) a.part_o[pr * D + lane + 64 * dd] = o[i][dd] * inv;
+      if (lane == 0) a.part_lse[pr] = m[i] + log2f(l[i]);
+    }
+  }
+}
+
+// ------------------------------------------------------------------ merge of splits
+//
+// out = sum_s w_s * o_s with w_s = 2^(lse_s - max) / sum; one wavefront per
+// (sequence, row, head), lanes across features.
+template <bool BF16>
+__global__ __launch_bounds__(256) void msa_combine_kernel(MsaArgs a) {
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const long item = (long)blockIdx.x * 4 + w;
+  const long n_items = (long)a.B * a.R * a.H;
+  if (item >= n_items) return;
+  const int h = item % a.H;
+  const int r = (item / a.H) % a.R;
+  const int b = item / ((long)a.H * a.R);
+  const int n_active = active_splits(clamp_len(a.seq_lens[b], a), a);
+  const size_t base = (((size_t)b * a.H + h) * a.n_splits) * a.R + r;
+  float mx = -INFINITY;
+  for (int s = 0; s < n_active; ++s) mx = fmaxf(mx, a.part_lse[base + (size_t)s * a.R]);
+  float wsum = 0.f;
+  for (int s = 0; s < n_active; ++s) wsum += exp2f(a.part_lse[base + (size_t)s * a.R] - mx);
+  const float inv = 1.f / wsum;
+  const int D = a.D;
+  for (int d0 = 2 * lane; d0 < D; d0 += 128) {
+    float acc0 = 0.f, acc1 = 0.f;
+    for (int s = 0; s < n_active; ++s) {
+      const float ws = exp2f(a.part_lse[base + (size_t)s * a.R] - mx) * inv;
+      const float2 v = *(const float2*)(a.part_o + (base + (size_t)s * a.R) * D + d0);
+      acc0 = fmaf(ws, v.x, acc0);
+      acc1 = fmaf(ws, v.y, acc1);
+    }
+    const size_t oidx = (((size_t)b * a.R + r) * a.H + h) * D + d0;
+    if (BF16) {
+      *(uint32_t*)((uint16_t*)a.out + oidx) = pack_bf16x2(acc0, acc1);
+    } else {
+      *(float2*)((float*)a.out + oidx) = make_float2(acc0, acc1);
+    }
+  }
+}
+
+// ------------------------------------------------------------------ planning (host)
+
+static int g_split_keys_override = 0;
+
+struct MsaPlan {
+  int split_keys, n_splits, n_qc;
+  size_t part_o_bytes, part_lse_bytes, total_bytes;
+};
+
+// Chooses the split length from the shape alone (sequence lengths live on the
+// device): enough workgroups to cover the 256 compute units about twice, but no
+// split shorter than 256 cached tokens.
+static MsaPlan make_plan(int B, int R, int H, int Hkv, int D, int max_len, int dtype) {
+  MsaPlan p;
+  const int g = H / Hkv;
+  int base;
+  if (dtype == SS_BF16) {
+    const int rows = msa_bf16_rows_per_chunk(g * R);
+    p.n_qc = ceil_div(g * R, rows);
+    base = B * Hkv * p.n_qc;
+  } else {
+    p.n_qc = ceil_div(R, 32);
+    base = B * H * p.n_qc;
+  }
+  int split_keys;
+  if (g_split_keys_override > 0) {
+    split_keys = g_split_keys_override;
+  } else {
+    const int target_wgs = 512;
+    int n = ceil_div(target_wgs, base < 1 ? 1 : base);
+    const int n_cap = max_len / 256 < 1 ? 1 : max_len / 256;
+    if (n > n_cap) n = n_cap;
+    if (n < 1) n = 1;
+    split_keys = ceil_div(max_len < 1 ? 1 : max_len, n);
+  }
+  split_keys = (int)align_up((size_t)(split_keys < 128 ? 128 : split_keys), 128);
+  // the MFMA kernel keeps a split's page ids in a 4096-entry LDS table (page_size >= 16)
+  if (split_keys > 65536) split_keys = 65536;
+  p.split_keys = split_keys;
+  p.n_splits = max_len <= 0 ? 1 : ceil_div(max_len, split_keys);
+  if (p.n_splits < 1) p.n_splits = 1;
+  if (p.n_splits > 1) {
+    p.part_o_bytes = align_up((size_t)B * H * p.n_splits * R * D * sizeof(float), 256);
+    p.part_lse_bytes = align_up((size_t)B * H * p.n_splits * R * sizeof(float), 256);
+  } else {
+    p.part_o_bytes = p.part_lse_bytes = 0;
+  }
+  p.total_bytes = p.part_o_bytes + p.part_lse_bytes + 256;
+  return p;
+}
+
+static int check_shape(const char* fn, int B, int T, int gamma, int H, int Hkv, int D, int dtype) {
+  SS_REQUIRE(B >= 0, SS_ERR_INVALID_ARG, "%s: B=%d", fn, B);
+  SS_REQUIRE(T >= 1 && T <= SS_MAX_T, SS_ERR_UNSUPPORTED, "%s: T=%d outside [1,%d]", fn, T, SS_MAX_T);
+  SS_REQUIRE(gamma >= 0 && gamma <= SS_MAX_GAMMA, SS_ERR_UNSUPPORTED, "%s: gamma=%d outside [0,%d]", fn, gamma,
+             SS_MAX_GAMMA);
+  SS_REQUIRE(H >= 1 && Hkv >= 1 && H % Hkv == 0, SS_ERR_INVALID_ARG, "%s: H=%d must be a multiple of Hkv=%d", fn, H,
+             Hkv);
+  SS_REQUIRE(D == 64 || D == 128, SS_ERR_UNSUPPORTED, "%s: head dim %d not in {64,128}", fn, D);
+  SS_REQUIRE(dtype == SS_F32 || dtype == SS_BF16, SS_ERR_UNSUPPORTED, "%s: dtype %d", fn, dtype);
+  return SS_OK;
+}
+
+}  // namespace ss
+
+extern "C" {
+
+int ss_msa_set_split_keys(int split_keys) {
+  const int prev = ss::g_split_keys_override;
+  ss::g_split_keys_override = split_keys > 0 ? split_keys : 0;
+  return prev;
+}
+
+size_t ss_msa_workspace_bytes(int B, int T, int gamma, int H, int Hkv, int D, int max_seq_len, int dtype) {
+  ss::clear_error();
+  if (ss::check_shape("ss_msa_workspace_bytes", B, T, gamma, H, Hkv, D, dtype) != SS_OK) return 0;
+  if (max_seq_len < 0) max_seq_len = 0;
+  return ss::make_plan(B, T * (1 + gamma), H, Hkv, D, max_seq_len, dtype).total_bytes;
+}
+
+int ss_msa_attention(const void* q, const void* k_new, const void* v_new, const void* k_cache, const void* v_cache,
+                     const int32_t* block_table, int max_pages_per_seq, int num_pages, const int32_t* seq_lens,
+                     const int32_t* parent, int B, int T, int gamma, int H, int Hkv, int D, int page_size, float scale,
+                     int dtype, uint32_t flags, void* out, void* workspace, size_t workspace_bytes, void* stream) {
+  using namespace ss;
+  clear_error();
+  const char* fn = "ss_msa_attention";
+  if (int rc = check_shape(fn, B, T, gamma, H, Hkv, D, dtype)) return rc;
+  SS_REQUIRE(B == 0 || (q && k_new && v_new && k_cache && v_cache && block_table && seq_lens && parent && out),
+             SS_ERR_INVALID_ARG, "%s: NULL tensor argument", fn);
+  SS_REQUIRE(page_size == 16 || page_size == 32 || page_size == 64, SS_ERR_UNSUPPORTED,
+             "%s: page_size %d not in {16,32,64}", fn, page_size);
+  SS_REQUIRE(max_pages_per_seq >= 1 && num_pages >= 1, SS_ERR_INVALID_ARG, "%s: max_pages_per_seq=%d num_pages=%d", fn,
+             max_pages_per_seq, num_pages);
+  SS_REQUIRE((long)max_pages_per_seq * page_size <= (1L << 30), SS_ERR_UNSUPPORTED, "%s: sequence capacity too large",
+             fn);
+  SS_REQUIRE(scale > 0.f && isfinite(scale), SS_ERR_INVALID_ARG, "%s: scale must be positive and finite", fn);
+  SS_REQUIRE((flags & ~SS_STREAM_EXCLUDE_SELF) == 0, SS_ERR_INVALID_ARG, "%s: unknown flags 0x%x", fn, flags);
+  if (B == 0) return SS_OK;
+
+  const int R = T * (1 + gamma);
+  const int max_len = max_pages_per_seq * page_size;
+  const MsaPlan plan = make_plan(B, R, H, Hkv, D, max_len, dtype);
+  SS_REQUIRE(plan.n_splits == 1 || (workspace != nullptr && workspace_bytes >= plan.total_bytes), SS_ERR_WORKSPACE,
+             "%s: workspace of %zu bytes needed, %zu given", fn, plan.total_bytes, workspace_bytes);
+  SS_REQUIRE(plan.split_keys / page_size <= 4096, SS_ERR_UNSUPPORTED, "%s: split of %d tokens has too many pages", fn,
+             plan.split_keys);
+
+  MsaArgs a;
+  a.q = q; a.k_new = k_new; a.v_new = v_new; a.k_cache = k_cache; a.v_cache = v_cache;
+  a.block_table = block_table; a.seq_lens = seq_lens; a.parent = parent; a.out = out;
+  char* ws = (char*)(((uintptr_t)workspace + 255) & ~(uintptr_t)255);
+  a.part_o = (float*)ws;
+  a.part_lse = (float*)(ws + plan.part_o_bytes);
+  a.B = B; a.T = T; a.gamma = gamma; a.R = R; a.H = H; a.Hkv = Hkv; a.g = H / Hkv; a.D = D;
+  a.page = page_size; a.page_shift = page_size == 16 ? 4 : (page_size == 32 ? 5 : 6);
+  a.max_pages = max_pages_per_seq; a.num_pages = num_pages;
+  a.split_keys = plan.split_keys; a.n_splits = plan.n_splits; a.n_qc = plan.n_qc;
+  a.scale_log2 = scale * 1.4426950408889634f;
+  a.flags = flags;
+  hipStream_t st = (hipStream_t)stream;
+
+  if (dtype == SS_F32) {
+    dim3 grid(plan.n_qc, plan.n_splits, B * H);
+    SS_REQUIRE((long)B * H <= 65535 && plan.n_splits <= 65535, SS_ERR_UNSUPPORTED, "%s: grid too large", fn);
+    if (D == 64) hipLaunchKernelGGL(msa_f32_kernel<64>, grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL(msa_f32_kernel<128>, grid, dim3(256), 0, st, a);
+    if (int rc = check_launch(fn)) return rc;
+  } else {
+    if (int rc = launch_msa_bf16(a, st)) return rc;
+  }
+  if (plan.n_splits > 1) {
+    const long items = (long)B * R * H;
+    dim3 grid((unsigned)((items + 3) / 4));
+    if (dtype == SS_F32) hipLaunchKernelGGL(msa_combine_kernel<false>, grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL(msa_combine_kernel<true>, grid, dim3(256), 0, st, a);
+    if (int rc = check_launch(fn)) return rc;
+  }
+  return SS_OK;
+}
+
+}  // extern "C"

@@ -73,3 +73,40 @@ def enumerate_paths_verify(tok, parent, a):
             if len(path) - 1 > best[0]:
                 best = (len(path) - 1, n)
     return best  # (n_accept, last)
+
+
+# ---------------------------------------------------------------- GPU-vs-oracle comparison helpers
+def rel_err(got, ref):
+    """max over elements of |got-ref| / (|ref| + rms(ref)): the per-tensor relative error the
+    tolerances are stated in (plain relative error is meaningless at zero crossings)."""
+    import numpy as np
+    got = np.asarray(got, np.float64)
+    ref = np.asarray(ref, np.float64)
+    rms = float(np.sqrt(np.mean(ref * ref))) or 1.0
+    return float(np.max(np.abs(got - ref) / (np.abs(ref) + rms)))
+
+
+def to_np_f32(t):
+    """torch tensor (any float dtype, any device) -> float32 numpy holding the stored values."""
+    return t.detach().float().cpu().numpy()
+
+
+def oracle_subproblem(inp, b, hk, g):
+    """Inputs of one (sequence, KV head) of a batched MSA problem as a B=1, Hkv=1, H=g problem,
+    with only that sequence's pages gathered (so that large configs stay small on the CPU)."""
+    import numpy as np
+    page = inp["k_cache"].shape[2]
+    L = int(inp["seq_lens"][b])
+    npg = max(1, (L + page - 1) // page)
+    pages = inp["block_table"][b, :npg].long()
+    sub = dict(
+        q=to_np_f32(inp["q"][b:b + 1, :, hk * g:(hk + 1) * g]),
+        k_new=to_np_f32(inp["k_new"][b:b + 1, :, hk:hk + 1]),
+        v_new=to_np_f32(inp["v_new"][b:b + 1, :, hk:hk + 1]),
+        k_cache=to_np_f32(inp["k_cache"][pages, hk:hk + 1]),
+        v_cache=to_np_f32(inp["v_cache"][pages, hk:hk + 1]),
+        block_table=np.arange(npg, dtype=np.int32)[None],
+        seq_lens=np.array([L], np.int32),
+        parent=inp["parent"][b:b + 1].cpu().numpy(),
+    )
+    return sub

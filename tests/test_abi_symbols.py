@@ -1,0 +1,86 @@
+"""The C-ABI library loads without a GPU and exports every symbol include/ss.h declares;
+host-only entry points and argument validation work without touching the device."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+import torch
+
+from conftest import ROOT
+from paper_2402_11131_amd import api
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "ss.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ss_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = api.load_library()
+    names = _declared()
+    assert len(names) >= 12
+    for n in names:
+        assert getattr(lib, n) is not None
+    assert set(names) == set(api.EXPORTS)
+    assert lib.ss_version() >= 100
+
+
+def test_one_hip_runtime_in_process():
+    api.load_library()
+    maps = open("/proc/self/maps").read()
+    libs = set(re.findall(r"(/\S*libamdhip64\.so\S*)", maps))
+    assert len(libs) == 1, libs
+
+
+def test_check_tree_host():
+    api.ss_check_tree_host(torch.tensor([[-1, 0, 0, 1]], dtype=torch.int32), max_depth=2)
+    with pytest.raises(api.SSError) as e:
+        api.ss_check_tree_host(torch.tensor([[-1, 0, 2, 1]], dtype=torch.int32))
+    assert e.value.code == 3 and "parent[2]" in str(e.value)
+    with pytest.raises(api.SSError):
+        api.ss_check_tree_host(torch.tensor([[0, 0]], dtype=torch.int32))
+    with pytest.raises(api.SSError):
+        api.ss_check_tree_host(torch.tensor([[-1, 0, 1, 2]], dtype=torch.int32), max_depth=2)
+
+
+def test_full_tree_template_host_matches_closed_form(golden):
+    for gamma, k, nodes, _rows in golden("tree_size_closed_form.txt")[""]:
+        if nodes > api.SS_MAX_T:
+            with pytest.raises(api.SSError):
+                api.ss_full_tree_template_host([k] * gamma)
+            continue
+        par, rank, dep = api.ss_full_tree_template_host([k] * gamma)
+        assert len(par) == nodes
+        assert [int((dep == j).sum()) for j in range(gamma + 1)] == [k ** j for j in range(gamma + 1)]
+
+
+def test_argument_validation_needs_no_device():
+    lib = api.load_library()
+    one = ctypes.c_void_p(8)  # never dereferenced: validation fails first
+    assert lib.ss_build_mask(None, 1, 4, 2, 0, None, None, None, None) == 1
+    assert lib.ss_build_mask(one, 1, 65, 2, 0, None, None, None, None) == 2
+    assert lib.ss_build_mask(one, 1, 4, 9, 0, None, None, None, None) == 2
+    assert b"gamma" in lib.ss_last_error()
+    assert lib.ss_msa_workspace_bytes(1, 8, 3, 4, 4, 96, 128, 0) == 0      # head dim 96
+    assert lib.ss_msa_workspace_bytes(4, 16, 4, 32, 32, 128, 4096, 1) > 0
+    assert lib.ss_lm_head_workspace_bytes(320, 4096, 32000, 4, 1) >= 320 * 250 * 4 * 8
+    assert lib.ss_lm_head_workspace_bytes(320, 4096, 32000, 9, 1) == 0
+    assert lib.ss_lm_head_argmax_topk(one, one, 4, 100, 50, 2, 1, one, one, one, 1 << 20, None) == 2  # d % 64
+    assert lib.ss_tree_verify(one, one, one, 4, 1, 1, 70, 3, one, one, one, one, one, None) == 2
+    assert lib.ss_tree_draft(one, 8, 2, one, one, None, None, None, 1, 4, 2, 7, one, one, None) == 1
+    br = (ctypes.c_int32 * 2)(2, 2)
+    assert lib.ss_tree_draft(one, 8, 2, one, one, None, None, br, 1, 4, 2, 6, one, one, None) == 1  # T2 != 7
+    assert b"7" in lib.ss_last_error()
+    args = [one] * 6 + [8, 16, one, one, 1, 8, 3, 4, 4, 64, 24, ctypes.c_float(0.125), 0, 0, one, one, 1 << 20, None]
+    assert lib.ss_msa_attention(*args) == 2                                  # page size 24
+    assert b"page_size" in lib.ss_last_error()
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(api, "_lib", None)
+    monkeypatch.setattr(api, "LIB_PATH", "/nonexistent/libss.so")
+    with pytest.raises(RuntimeError, match="not built"):
+        api.load_library()
