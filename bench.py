@@ -1,0 +1,247 @@
+#!/usr/bin/env python3
+"""Benchmark of the verify-and-speculate step on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input that
+is already resident in HBM: N_s multi-stream-attention layers (each with its own
+paged KV cache and q/k/v), the LM head with fused arg-max/top-k on the last
+layer's output, greedy tree verification and tree drafting, all enqueued on one
+stream through the C ABI with no host synchronisation in between.
+
+Default workload: c4 (4 sequences, 32x128 heads, prefix 4096, 16-node trees x 4
+streams, 4 MSA layers, LM head 320 x 4096 x 32000, top-4): the only configuration
+that contains every part of the path.  `--workload c2|c3|c5` time the attention
+layer(s) of the other configurations (no LM head in those).
+
+Prints ONE JSON line.  `value` is microseconds per step.  `roofline` describes the
+dominant kernel (the bf16 MSA kernel): algorithmic bytes per launch divided by the
+kernel's own average duration, measured here with events on the launch stream
+with the split-merge kernel switched off.  `cpu_baseline` times the CPU oracle on
+a bounded sample of the same workload and scales it to a full step.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E, vendor figure
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, vendor figure
+
+# HBM traffic of one launch of the MSA kernel on workload c4, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# scaled by a copy kernel of known size (see profiles/); None until measured.
+MSA_TRAFFIC_BYTES = {"c4": None, "c2": None, "c3": None, "c5": None}
+
+
+def msa_bytes(cfg, seq_lens):
+    """Algorithmic bytes of one MSA launch: K and V prefix once, the step's new K/V block, q in, out."""
+    e = 2 if cfg.dtype == "bf16" else 4
+    kv = sum(2 * int(L) * cfg.Hkv * cfg.D * e for L in seq_lens)
+    new = cfg.B * 2 * cfg.R * cfg.Hkv * cfg.D * e
+    io = cfg.B * 2 * cfg.R * cfg.H * cfg.D * e
+    table = sum(((int(L) + cfg.page - 1) // cfg.page) * 4 for L in seq_lens)
+    return kv + new + io + table
+
+
+def msa_flops(cfg, seq_lens):
+    return sum(4 * cfg.R * (int(L) + cfg.R) * cfg.H * cfg.D for L in seq_lens)
+
+
+def timed(fn, iters, torch):
+    """Average microseconds of fn() over iters calls, events on the current stream."""
+    start = torch.cuda.Event(enable_timing=True)
+    end = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    start.record()
+    for i in range(iters):
+        fn(i)
+    end.record()
+    torch.cuda.synchronize()
+    return start.elapsed_time(end) * 1000.0 / iters
+
+
+def cpu_baseline(cfg, synth, seq_lens):
+    """Oracle on a bounded sample: MSA of one layer for one sequence and 4 of its heads; LM head for
+    8 rows over the whole vocabulary; scaled linearly to a full step."""
+    import numpy as np
+    import oracle
+    oracle.build()
+    heads = min(4, cfg.Hkv)
+    small = synth.scaled(cfg, B=1, H=heads * (cfg.H // cfg.Hkv), Hkv=heads, L_min=int(max(seq_lens)),
+                         L_max=int(max(seq_lens)))
+    inp = synth.make_msa_inputs(small, 4242)
+    f32 = lambda t: t.float().numpy()
+    args = (f32(inp["q"]), f32(inp["k_new"]), f32(inp["v_new"]), f32(inp["k_cache"]), f32(inp["v_cache"]),
+            inp["block_table"].numpy(), inp["seq_lens"].numpy(), inp["parent"].numpy(), small.gamma, inp["scale"])
+    t0 = time.perf_counter()
+    oracle.msa_attention(*args)
+    t_msa = time.perf_counter() - t0
+    keys_sample = int(max(seq_lens)) * heads
+    keys_full = sum(int(L) for L in seq_lens) * cfg.Hkv
+    est = t_msa * keys_full / keys_sample * cfg.n_layers
+    sample = "MSA: 1 sequence x %d KV heads x 1 layer (%.2f s)" % (heads, t_msa)
+    if cfg.vocab:
+        rows = 8
+        lm = synth.make_lm_head_inputs(cfg, 4242, N=rows)
+        t0 = time.perf_counter()
+        oracle.lm_head_topk(f32(lm["hidden"]), f32(lm["W"]), cfg.K)
+        t_lm = time.perf_counter() - t0
+        est += t_lm * (cfg.B * cfg.R) / rows
+        sample += "; LM head: %d of %d rows x full vocabulary (%.2f s)" % (rows, cfg.B * cfg.R, t_lm)
+    return {"value": est * 1e6, "unit": "us", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": sample + "; scaled linearly to the full step"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="c4", choices=["c2", "c3", "c4", "c5"])
+    ap.add_argument("--split-keys", type=int, default=0, help="KV split length of the MSA kernel (0 = automatic)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus %d is not supported (the path uses no collectives; "
+              "see DESIGN.md for how it would shard)" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2402_11131_amd import api, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    cfg = synth.CONFIGS[args.workload]
+    api.load_library()
+    if args.split_keys:
+        api.ss_msa_set_split_keys(args.split_keys)
+
+    # ---- inputs.  Each MSA layer has its own caches; input sets are rotated so that one rotation
+    # touches more than 512 MB and the 256 MB last-level cache cannot serve repeats.
+    seq_lens = synth.seq_lens_for(cfg, 1)
+    per_layer = msa_bytes(cfg, seq_lens)
+    n_sets = max(cfg.n_layers, int(np.ceil(768e6 / per_layer)))
+    n_sets = ((n_sets + cfg.n_layers - 1) // cfg.n_layers) * cfg.n_layers
+    layers = [synth.make_msa_inputs(cfg, 1, device=dev, layer=i) for i in range(n_sets)]
+    outs = [torch.empty_like(layers[0]["q"]) for _ in range(cfg.n_layers)]
+    ws_bytes = api.ss_msa_workspace_bytes(cfg.B, cfg.T, cfg.gamma, cfg.H, cfg.Hkv, cfg.D,
+                                          layers[0]["block_table"].shape[1] * cfg.page, api.SS_BF16)
+    msa_ws = torch.empty(max(ws_bytes, 1), dtype=torch.uint8, device=dev)
+    parent = layers[0]["parent"]
+    has_lm = cfg.vocab > 0
+    if has_lm:
+        N = cfg.B * cfg.R
+        lm = synth.make_lm_head_inputs(cfg, 1, device=dev)
+        tok_np = synth.make_draft_tokens(1, parent.cpu().numpy(), cfg.vocab)
+        tok = torch.from_numpy(tok_np).to(dev)
+        idx = torch.empty((N, cfg.K), dtype=torch.int32, device=dev)
+        val = torch.empty((N, cfg.K), dtype=torch.float32, device=dev)
+        lm_ws = torch.empty(api.ss_lm_head_workspace_bytes(N, cfg.d_model, cfg.vocab, cfg.K, api.SS_BF16),
+                            dtype=torch.uint8, device=dev)
+
+    def msa_call(layer, out, flags=0):
+        api.ss_msa_attention(layer["q"], layer["k_new"], layer["v_new"], layer["k_cache"], layer["v_cache"],
+                             layer["block_table"], layer["seq_lens"], parent, cfg.gamma, layer["scale"],
+                             flags=flags, out=out, workspace=msa_ws)
+
+    state = {}
+
+    def step(i):
+        base = (i * cfg.n_layers) % n_sets
+        for j in range(cfg.n_layers):
+            msa_call(layers[base + j], outs[j])
+        if has_lm:
+            hidden = outs[-1].view(N, cfg.d_model)
+            api.ss_lm_head_argmax_topk(hidden, lm["W"], cfg.K, idx=idx, val=val, workspace=lm_ws)
+            ver = api.ss_tree_verify(tok, parent, idx, cfg.max_depth, batch_stride=cfg.R * cfg.K, node_stride=cfg.K)
+            nxt = api.ss_tree_draft(idx, cfg.K, ver["last"], ver["bonus"], cfg.T, cfg.gamma,
+                                    branching=cfg.draft_branching, batch_stride=cfg.R * cfg.K, offset=cfg.T * cfg.K)
+            state["ver"], state["nxt"] = ver, nxt
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    if has_lm and n_sets == cfg.n_layers:
+        # Every step sees the same inputs, so the main stream's arg-max tokens are known after the warm-up.
+        # Plant the draft the way a decode loop would have produced it: along one seeded root path per
+        # sequence each draft token equals the main stream's token at its parent with probability 0.7
+        # (until the first miss), which gives the accepted lengths the paper's call-reduction ratios imply.
+        a = idx.cpu().numpy().reshape(cfg.B, cfg.R, cfg.K)[:, :cfg.T, 0]
+        par = parent.cpu().numpy()
+        rng = synth.rng_for(99)
+        for b in range(cfg.B):
+            path = synth.root_path(par[b], int(rng.integers(cfg.T)))
+            for p_, c_ in zip(path[:-1], path[1:]):
+                if rng.random() >= 0.7:
+                    break
+                tok_np[b, c_] = a[b, p_]
+        tok.copy_(torch.from_numpy(tok_np))
+        step(0)
+        torch.cuda.synchronize()
+    t_wall0 = time.perf_counter()
+    us_step = timed(step, args.steps, torch)
+    wall_s = time.perf_counter() - t_wall0
+
+    # ---- per-kernel figures (each in its own timed loop, same rotation of inputs)
+    it = max(20, args.steps)
+    us_msa_call = timed(lambda i: msa_call(layers[i % n_sets], outs[0]), it, torch)
+    us_msa_kernel = timed(lambda i: msa_call(layers[i % n_sets], outs[0], api.SS_MSA_PARTIALS_ONLY), it, torch)
+    kern = {"msa_call_us": round(us_msa_call, 2), "msa_kernel_us": round(us_msa_kernel, 2)}
+    b_msa = msa_bytes(cfg, seq_lens)
+    f_msa = msa_flops(cfg, seq_lens)
+    achieved = b_msa / (us_msa_kernel * 1e-6) / 1e9
+    roofline = {"kernel": "msa_bf16_kernel", "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                "traffic": MSA_TRAFFIC_BYTES.get(args.workload), "algorithmic_bytes": b_msa,
+                "mfma_tflops": round(f_msa / (us_msa_kernel * 1e-6) / 1e12, 1)}
+    extra = {}
+    if has_lm:
+        hidden = outs[-1].view(N, cfg.d_model)
+        us_lm = timed(lambda i: api.ss_lm_head_argmax_topk(hidden, lm["W"], cfg.K, idx=idx, val=val, workspace=lm_ws),
+                      it, torch)
+        us_ver = timed(lambda i: api.ss_tree_verify(tok, parent, idx, cfg.max_depth, batch_stride=cfg.R * cfg.K,
+                                                    node_stride=cfg.K), it, torch)
+        ver = state["ver"]
+        us_draft = timed(lambda i: api.ss_tree_draft(idx, cfg.K, ver["last"], ver["bonus"], cfg.T, cfg.gamma,
+                                                     branching=cfg.draft_branching, batch_stride=cfg.R * cfg.K,
+                                                     offset=cfg.T * cfg.K), it, torch)
+        kern.update({"lm_head_call_us": round(us_lm, 2), "verify_us": round(us_ver, 2), "draft_us": round(us_draft, 2)})
+        f_lm = 2.0 * N * cfg.vocab * cfg.d_model
+        tf = f_lm / (us_lm * 1e-6) / 1e12
+        extra["roofline_lm_head"] = {"kernel": "lm_head_bf16_kernel + reduce", "bound": "mfma", "achieved": round(tf, 1),
+                                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                     "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                                     "hbm_gbps": round((cfg.vocab * cfg.d_model * 2 + N * cfg.d_model * 2) /
+                                                       (us_lm * 1e-6) / 1e9, 1)}
+        extra["accepted_per_sequence"] = state["ver"]["n_accept"].tolist()
+
+    result = {
+        "metric": "verify+speculate step time (MSA layers + LM-head argmax/top-k + verify + draft)",
+        "value": round(us_step, 2), "unit": "us", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(us_step / 1000.0, 5), "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s: B=%d, %dx%d heads (%d KV), prefix %s, %d-node trees x %d streams (%d rows/seq), "
+                               "%d-token pages, %d MSA layer(s)%s" % (
+                                   cfg.name, cfg.B, cfg.H, cfg.D, cfg.Hkv,
+                                   cfg.L_min if cfg.L_min == cfg.L_max else "%d..%d" % (cfg.L_min, cfg.L_max),
+                                   cfg.T, cfg.gamma, cfg.R, cfg.page, cfg.n_layers,
+                                   ", LM head %dx%dx%d top-%d" % (cfg.B * cfg.R, cfg.d_model, cfg.vocab, cfg.K)
+                                   if has_lm else ""),
+                   "input_sets_rotated": n_sets, "split_keys": args.split_keys or "auto"},
+        "roofline": roofline, "kernels": kern, "timed_wall_s": round(wall_s, 3),
+    }
+    result.update(extra)
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, synth, seq_lens)
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

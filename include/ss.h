@@ -66,6 +66,10 @@ extern "C" {
  * Eq. 2 lets stream j attend to streams 1..j of its own node (itself
  * included); with SS_STREAM_EXCLUDE_SELF it sees streams 1..j-1 only. */
 #define SS_STREAM_EXCLUDE_SELF 1u
+/* ss_msa_attention only, for profiling: run the attention kernel but not the
+ * kernel that merges the KV splits; `out` is then left unwritten whenever the
+ * problem is split (the per-split partial results stay in the workspace). */
+#define SS_MSA_PARTIALS_ONLY 2u
 
 /* Library version (major*100 + minor). */
 int ss_version(void);

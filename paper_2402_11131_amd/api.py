@@ -21,6 +21,7 @@ LIB_PATH = os.path.join(_PKG, "libss.so")
 SS_OK = 0
 SS_F32, SS_BF16 = 0, 1
 SS_STREAM_EXCLUDE_SELF = 1
+SS_MSA_PARTIALS_ONLY = 2
 SS_MAX_T, SS_MAX_GAMMA, SS_MAX_K = 64, 8, 8
 
 EXPORTS = (

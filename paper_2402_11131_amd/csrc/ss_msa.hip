@@ -237,8 +237,6 @@ static MsaPlan make_plan(int B, int R, int H, int Hkv, int D, int max_len, int d
     split_keys = ceil_div(max_len < 1 ? 1 : max_len, n);
   }
   split_keys = (int)align_up((size_t)(split_keys < 128 ? 128 : split_keys), 128);
-  // the MFMA kernel keeps a split's page ids in a 4096-entry LDS table (page_size >= 16)
-  if (split_keys > 65536) split_keys = 65536;
   p.split_keys = split_keys;
   p.n_splits = max_len <= 0 ? 1 : ceil_div(max_len, split_keys);
   if (p.n_splits < 1) p.n_splits = 1;
@@ -298,7 +296,8 @@ int ss_msa_attention(const void* q, const void* k_new, const void* v_new, const 
   SS_REQUIRE((long)max_pages_per_seq * page_size <= (1L << 30), SS_ERR_UNSUPPORTED, "%s: sequence capacity too large",
              fn);
   SS_REQUIRE(scale > 0.f && isfinite(scale), SS_ERR_INVALID_ARG, "%s: scale must be positive and finite", fn);
-  SS_REQUIRE((flags & ~SS_STREAM_EXCLUDE_SELF) == 0, SS_ERR_INVALID_ARG, "%s: unknown flags 0x%x", fn, flags);
+  SS_REQUIRE((flags & ~(SS_STREAM_EXCLUDE_SELF | SS_MSA_PARTIALS_ONLY)) == 0, SS_ERR_INVALID_ARG,
+             "%s: unknown flags 0x%x", fn, flags);
   if (B == 0) return SS_OK;
 
   const int R = T * (1 + gamma);
@@ -306,8 +305,6 @@ int ss_msa_attention(const void* q, const void* k_new, const void* v_new, const 
   const MsaPlan plan = make_plan(B, R, H, Hkv, D, max_len, dtype);
   SS_REQUIRE(plan.n_splits == 1 || (workspace != nullptr && workspace_bytes >= plan.total_bytes), SS_ERR_WORKSPACE,
              "%s: workspace of %zu bytes needed, %zu given", fn, plan.total_bytes, workspace_bytes);
-  SS_REQUIRE(plan.split_keys / page_size <= 4096, SS_ERR_UNSUPPORTED, "%s: split of %d tokens has too many pages", fn,
-             plan.split_keys);
 
   MsaArgs a;
   a.q = q; a.k_new = k_new; a.v_new = v_new; a.k_cache = k_cache; a.v_cache = v_cache;
@@ -332,7 +329,7 @@ int ss_msa_attention(const void* q, const void* k_new, const void* v_new, const 
   } else {
     if (int rc = launch_msa_bf16(a, st)) return rc;
   }
-  if (plan.n_splits > 1) {
+  if (plan.n_splits > 1 && !(flags & SS_MSA_PARTIALS_ONLY)) {
     const long items = (long)B * R * H;
     dim3 grid((unsigned)((items + 3) / 4));
     if (dtype == SS_F32) hipLaunchKernelGGL(msa_combine_kernel<false>, grid, dim3(256), 0, st, a);

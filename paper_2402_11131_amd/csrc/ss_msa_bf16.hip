@@ -1,153 +1,107 @@
 // a2, bf16 path: multi-stream attention (Eq. 1 / Eq. 2) on the gfx950 matrix cores.
 //
-// Work split.  A workgroup (4 wavefronts, one per SIMD) owns one (sequence, KV
-// head, split of the cached tokens, chunk of <= 80 folded query rows).  The
-// query heads of a GQA group are folded into the row dimension, so K and V are
-// read once per KV head.  Inside the workgroup the WAVEFRONTS SPLIT THE KEYS:
-// wave w takes the 32-key blocks w, w+4, ... of the split and all query rows, so
-// no K/V tile is shared between waves and nothing in the main loop goes through
-// LDS.  The four partial (max, sum, O) states are merged through LDS at the end.
+// Work split.  A workgroup owns one (sequence, KV head, split of the cached
+// tokens, chunk of <= 80 folded query rows); the query heads of a GQA group are
+// folded into the row dimension, so K and V are read once per KV head.  The
+// workgroup consists of G groups of NW wavefronts.  Inside a group every wave
+// owns ONE 16-row query tile (its Q operands, running max / sum and a 16 x D
+// slice of O live in registers) and all NW waves walk the same sequence of
+// 32-key units; the G groups take the units of the split round-robin and their
+// partial (max, sum, O) states are merged through LDS at the end.  With 80 rows
+// that is 3 groups x 5 waves = 15 waves per compute unit, which is what hides the
+// LDS, MFMA and exp latencies (no wave depends on long instruction-level overlap).
+//
+// Memory pipeline.  The unit a group works on sits in one of its two LDS stages
+// (8 KB of K rows + 8 KB of V for D = 128).  While it is being consumed, the
+// group's waves hold the next unit in registers (16-byte global loads issued at
+// the top of the iteration, one unit = 16 KB in flight per group); it is written
+// to the other stage after the compute and one workgroup barrier per unit
+// publishes it.  Global addresses are chosen so that one K load instruction
+// covers whole 256-byte key rows (4 consecutive keys = 1 KB contiguous) and one V
+// instruction covers two 512-byte runs of a feature-major page.
 //
 // Matrix-core mapping (v_mfma_f32_16x16x32_bf16, wave64).  Scores are computed
 // transposed, S^T = K Q^T (A = 16 keys x 32 features, B = 32 features x 16
 // queries), so that a lane ends up holding 8 consecutive keys of one query
 // column; those 8 probabilities are exactly the 8 k-slots that lane must supply
 // as B operand of O^T += V^T P^T (A = 16 features x 32 keys).  For that to work
-// the two 16-key score tiles of a 32-key block interleave the keys in groups of
-// four (tile A: keys 0-3, 8-11, 16-19, 24-27; tile B: the others), which costs
-// nothing because a K row is addressed per lane anyway.  V pages are stored
-// feature-major, so the V^T operand is one 16-byte load per lane; K rows are
-// token-major, one 16-byte load per lane and k-step.  The head features are
-// consumed in the order (step, lane group) -> 8-feature chunk 4*step + group for
-// both Q and K, so every K load instruction covers 64 contiguous bytes per key.
+// the two 16-key score tiles of a unit interleave the keys in groups of four
+// (tile 0: keys 0-3, 8-11, 16-19, 24-27; tile 1: the others).  V pages are stored
+// feature-major, so a V^T operand is 16 contiguous bytes.  In LDS the K rows are
+// row-major and the V tile is feature-major, both with their 16-byte chunks
+// XOR-swizzled so that every operand read is bank-conflict free.  The head
+// features are consumed in the order (step, lane group) -> chunk 4*step + group
+// for both Q and K.
 //
 // Softmax runs in the log2 domain with the scale folded into the exponent's FMA.
 // The running maximum is only moved (and O rescaled) when it would grow by more
-// than 2^8; until then probabilities are at most 256, which fp32 accumulation
+// than 2^16; until then probabilities are at most 65536, which fp32 accumulation
 // and bf16's fp32-sized exponent hold without loss.
 //
-// Only blocks that need a mask go a slower way: the ragged last block of the
-// cached prefix (scores masked, V operand zeroed past the end) and the step's
-// own R new rows (mask generated in registers from ancestor bit sets and stream
-// ranges; V rows, which are token-major there, transposed through a per-wave
-// LDS tile).
+// Three kinds of units: full blocks of the cached prefix (no mask), the ragged
+// last block of the prefix (scores masked, V zeroed past the end so that
+// 0 * garbage cannot produce NaN) and blocks of the step's own R new rows (mask
+// generated in registers from ancestor bit sets and stream ranges; V rows are
+// token-major there: they are staged row-major and read with the LDS transpose
+// read ds_read_b64_tr_b16, which hands a lane 4 consecutive keys of one feature).
+#include <stdlib.h>
+
 #include "ss_msa.h"
+
+// Optional phase timing (development aid, compiled in with -DSS_MSA_TIMING): cycle counts per phase
+// of the key loop, summed per wave, are left behind the split log-sum-exp array in the workspace.
+#ifdef SS_MSA_TIMING
+#define SS_T(i) { const long long t_now_ = clock64(); tacc[i] += t_now_ - t_last; t_last = t_now_; }
+#define SS_KEEP(x) asm volatile("" ::"v"(x))
+#else
+#define SS_T(i)
+#define SS_KEEP(x)
+#endif
 
 namespace ss {
 
-constexpr float kLazyLog2 = 8.0f;
+constexpr float kLazyLog2 = 16.0f;
+constexpr int kMaxGroups = 4;  // wave groups per workgroup
+constexpr int kMaxWaves = 12;  // waves per workgroup: 3 per SIMD leaves each wave 168 vector registers
 
-// key (0..31) that row m of score tile X holds inside a 32-key block
+// key (0..31) that row m of score tile X holds inside a 32-key unit
 SS_DEV int block_key(int m, int X) { return 8 * (m >> 2) + (m & 3) + 4 * X; }
+// XOR swizzle of a K row's 16-byte chunks inside an LDS stage
+SS_DEV int k_swz(int row) { return (row & 3) | (((row >> 3) & 1) << 2); }
 
 SS_DEV bf16x8 as_bf16x8(uintx4 u) { return __builtin_bit_cast(bf16x8, u); }
-
 SS_DEV uintx4 ld16(const uint16_t* p) { return *reinterpret_cast<const uintx4*>(p); }
 
-struct NoMask {
-  SS_DEV bool operator()(int, int, int) const { return true; }
-  static constexpr bool kMasked = false;
-};
-
-// ragged last block of the cached prefix: key offset 8*lg + 4*X + i must lie before the end
-struct TailMask {
-  int tail, lg;
-  static constexpr bool kMasked = true;
-  SS_DEV bool operator()(int, int X, int i) const { return 8 * lg + 4 * X + i < tail; }
-};
-
-// the step's own rows: tree + stream visibility of query tile t's row against new key c0 + offset
-template <int NQT>
-struct NewMask {
-  const RowVis (&vis)[NQT];
-  int c0, lg, R, T;
-  static constexpr bool kMasked = true;
-  SS_DEV bool operator()(int t, int X, int i) const {
-    const int col = c0 + 8 * lg + 4 * X + i;
-    return (col < R) & row_sees(vis[t], col, T);
-  }
-};
-
-// One 32-key block against all query tiles of the workgroup.
-// Qs: the query operands in LDS, one 16-byte entry per (query tile, k-step, lane).
-template <int D, int NQT, class Mask>
-SS_DEV void attend_block(const bf16x8 (&Kr)[2][D / 32], const bf16x8 (&Vr)[D / 16], const uintx4* Qs, int lane,
-                         floatx4 (&O)[D / 16][NQT], float (&m)[NQT], float (&l)[NQT], float c, Mask mask) {
-  constexpr int KS = D / 32, DT = D / 16;
-  // The query operands are re-read from LDS for every block.  Hiding the lane
-  // offset from the optimiser keeps it from hoisting those reads out of the key
-  // loop into 16*NQT long-lived registers.
-  asm volatile("" : "+v"(lane));
-  floatx4 S[2][NQT];
-#pragma unroll
-  for (int X = 0; X < 2; ++X)
-#pragma unroll
-    for (int t = 0; t < NQT; ++t) S[X][t] = floatx4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-  for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-    for (int t = 0; t < NQT; ++t) {
-      const bf16x8 qop = as_bf16x8(Qs[(t * KS + ks) * 64 + lane]);
-#pragma unroll
-      for (int X = 0; X < 2; ++X) S[X][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Kr[X][ks], qop, S[X][t], 0, 0, 0);
-    }
-
-  bf16x8 P[NQT];
-#pragma unroll
-  for (int t = 0; t < NQT; ++t) {
-    if (Mask::kMasked) {
-#pragma unroll
-      for (int X = 0; X < 2; ++X)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const float sv = S[X][t][i];
-          S[X][t][i] = mask(t, X, i) ? sv : -INFINITY;
-        }
-    }
-    float mx = fmaxf(fmaxf(fmaxf(S[0][t][0], S[0][t][1]), fmaxf(S[0][t][2], S[0][t][3])),
-                     fmaxf(fmaxf(S[1][t][0], S[1][t][1]), fmaxf(S[1][t][2], S[1][t][3])));
-    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    if (__any((mx - m[t]) * c > kLazyLog2)) {
-      const float m_new = fmaxf(m[t], mx);
-      const float alpha = __builtin_amdgcn_exp2f((m[t] - m_new) * c);
-      l[t] *= alpha;
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt) O[dt][t] *= alpha;
-      m[t] = m_new;
-    }
-    const float mc = m[t] * c;
-    float ps = 0.f;
-#pragma unroll
-    for (int X = 0; X < 2; ++X)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const float p = __builtin_amdgcn_exp2f(fmaf(S[X][t][i], c, -mc));
-        ps += p;
-        P[t][4 * X + i] = (__bf16)p;
-      }
-    l[t] += ps;
-  }
-#pragma unroll
-  for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-    for (int t = 0; t < NQT; ++t) O[dt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Vr[dt], P[t], O[dt][t], 0, 0, 0);
+// LDS transpose read.  Within each group of 16 lanes, lane j passes the address of 4 consecutive
+// 16-bit elements In[j][0..3]; lane i receives Out[i][e] = In[4*e + (i >> 2)][i & 3].  With lane
+// (i = feature, group) pointing at row (i >> 2) and columns 4*(i & 3).. of a row-major tile, it
+// receives feature i of rows 0..3: four consecutive keys of one feature.
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short shortx4;
+SS_DEV uintx2 lds_read_tr16(const unsigned char* p) {
+  const shortx4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((shortx4 __attribute__((address_space(3)))*)(p));
+  return __builtin_bit_cast(uintx2, v);
 }
 
-template <int D, int NQT>
-__global__ __launch_bounds__(256, 1) void msa_bf16_kernel(MsaArgs a) {
-  constexpr int KS = D / 32, DT = D / 16, QROWS = 16 * NQT;
-  constexpr int STAGE_BYTES = 4 * 32 * D * 2;            // per-wave V tiles of the new rows
-  constexpr int MERGE_BYTES = 2 * DT * NQT * 64 * 16;    // two wave-sized O buffers
-  constexpr int BUF_BYTES = STAGE_BYTES > MERGE_BYTES ? STAGE_BYTES : MERGE_BYTES;
+// NW = waves (query tiles) per group; it only fixes how the 1 KB load slots of a unit are dealt to
+// the waves of a group.  The number of groups is a launch parameter.
+template <int D, int NW>
+__global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves / NW : kMaxGroups)) void msa_bf16_kernel(MsaArgs a, int n_groups) {
+  constexpr int KS = D / 32, DT = D / 16;
+  constexpr int K_BYTES = 32 * D * 2;           // K rows of a unit (V takes the same)
+  constexpr int STAGE_BYTES = 2 * K_BYTES;
+  constexpr int LOADS = STAGE_BYTES / 1024;     // 1 KB load slots per unit
+  constexpr int SLOTS = (LOADS + NW - 1) / NW;  // slots per wave
+  constexpr int CPR = D / 8;                    // 16-byte chunks per K row
+  constexpr int ROWS_PER_SLOT = 64 / CPR;
+  constexpr int K_SLOTS = LOADS / 2;
+  constexpr int VROW = 64;                      // bytes per feature row of the V tile (32 keys)
 
-  __shared__ int pt[4096];
-  __shared__ int par[SS_MAX_T];
-  __shared__ uint64_t anc[SS_MAX_T];
-  __shared__ float m_sh[4][QROWS];
-  __shared__ float l_sh[4][QROWS];
-  __shared__ __attribute__((aligned(16))) unsigned char buf[BUF_BYTES];
-  __shared__ uintx4 Qs[NQT * KS * 64];
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  // smem: [n_groups][2][STAGE_BYTES] stages (reused by the final merge) | par | anc | ml
+  unsigned char* stages = smem;
+  int* par = reinterpret_cast<int*>(smem + (size_t)n_groups * 2 * STAGE_BYTES);
+  uint64_t* anc = reinterpret_cast<uint64_t*>(par + SS_MAX_T);
+  float* ml = reinterpret_cast<float*>(anc + SS_MAX_T);  // [n_groups][NW][2][16]: max, sum per query
 
   // ---- which piece of work: XCD-aware order.  Workgroup ids go round-robin over
   // the 8 XCDs, so ids that are equal mod 8 share an L2: the query chunks of one
@@ -161,7 +115,11 @@ __global__ __launch_bounds__(256, 1) void msa_bf16_kernel(MsaArgs a) {
   const int hk = (group / a.n_splits) % a.Hkv;
   const int b = group / (a.n_splits * a.Hkv);
 
-  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, lq = lane & 15, lg = lane >> 4;
+  // The wave index is made known to be wave-uniform, so that everything derived from it (unit, load
+  // slot, page lookups, base addresses) is computed on the scalar unit.
+  const int tid = threadIdx.x, lane = tid & 63, lq = lane & 15, lg = lane >> 4;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int grp = w / NW, wt = w % NW;  // wave group, query tile of this wave
   const int R = a.R, T = a.T, F = a.g * R;
   const int L = clamp_len(a.seq_lens[b], a);
   const int n_active = active_splits(L, a);
@@ -176,247 +134,316 @@ __global__ __launch_bounds__(256, 1) void msa_bf16_kernel(MsaArgs a) {
   const uint16_t* v_new = (const uint16_t*)a.v_new;
   const uint16_t* k_cache = (const uint16_t*)a.k_cache;
   const uint16_t* v_cache = (const uint16_t*)a.v_cache;
+  const int32_t* my_table = a.block_table + (size_t)b * a.max_pages;
 
-  // ---- page ids of this split -> LDS (clamped), tree -> ancestor sets
-  const int lp0 = k0 >> a.page_shift;
-  const int npg = (k1 - k0 + a.page - 1) >> a.page_shift;
-  for (int i = tid; i < npg; i += 256) {
-    const int pg = a.block_table[(size_t)b * a.max_pages + lp0 + i];
-    pt[i] = min(max(pg, 0), a.num_pages - 1);
-  }
+  // ---- tree -> ancestor sets
   if (tid < T) par[tid] = clamp_parent(a.parent[(size_t)b * T + tid], tid);
   __syncthreads();
   compute_anc(par, T, anc, tid);
   __syncthreads();
 
-  // ---- query operands -> LDS in MFMA B-operand order (shared by the four waves: every
-  // wave multiplies all query rows), and per-row visibility of the step's own keys
-  for (int e = tid; e < NQT * KS * 64; e += 256) {
-    const int t = e / (KS * 64), ks = (e >> 6) % KS, ln = e & 63;
-    const int f = qc * QROWS + 16 * t + (ln & 15);
-    uintx4 u = uintx4{0u, 0u, 0u, 0u};
-    if (f < F) u = ld16(q + (((size_t)b * R + f % R) * a.H + hk * a.g + f / R) * D + (4 * ks + (ln >> 4)) * 8);
-    Qs[e] = u;
-  }
-  RowVis vis[NQT];
-#pragma unroll
-  for (int t = 0; t < NQT; ++t) {
-    const int f = qc * QROWS + 16 * t + lq;
-    vis[t] = make_row_vis(f < F ? f % R : 0, T, a.gamma, anc, (a.flags & SS_STREAM_EXCLUDE_SELF) != 0);
-  }
-  __syncthreads();
-
-  floatx4 O[DT][NQT];
-  float m[NQT], l[NQT];
-#pragma unroll
-  for (int t = 0; t < NQT; ++t) {
-    m[t] = -1e30f;
-    l[t] = 0.f;
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt) O[dt][t] = floatx4{0.f, 0.f, 0.f, 0.f};
-  }
-
-  bf16x8 Kr[2][KS], Vr[DT];
-  const size_t k_page_stride = (size_t)a.Hkv * a.page * D;  // elements per physical page
-  const int pmask = a.page - 1;
-
-  auto load_k = [&](int kb) {
-    const int key = kb + block_key(lq, 0);  // tile B's key is 4 further, on the same page
-    const int pg = pt[(key >> a.page_shift) - lp0];
-    const uint16_t* kp = k_cache + (size_t)pg * k_page_stride + ((size_t)hk * a.page + (key & pmask)) * D + lg * 8;
+  // ---- this wave's query tile: MFMA B operands (lane (lq, lg) holds features 8*(4*ks+lg).. of
+  // folded query row f) and the row's visibility of the step's own keys
+  const int f = qc * (16 * NW) + 16 * wt + lq;
+  const bool f_valid = f < F;
+  const int q_r = f_valid ? f % R : 0, q_h = hk * a.g + (f_valid ? f / R : 0);
+  bf16x8 Qr[KS];
+  {
+    const uint16_t* qp = q + (((size_t)b * R + q_r) * a.H + q_h) * D + lg * 8;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      Kr[0][ks] = as_bf16x8(ld16(kp + 32 * ks));
-      Kr[1][ks] = as_bf16x8(ld16(kp + 4 * D + 32 * ks));
+      uintx4 u = uintx4{0u, 0u, 0u, 0u};
+      if (f_valid) u = ld16(qp + 32 * ks);
+      Qr[ks] = as_bf16x8(u);
     }
-  };
-  auto load_v = [&](int kb) {
-    const int key = kb + 8 * lg;
-    const int pg = pt[(key >> a.page_shift) - lp0];
-    const uint16_t* vp = v_cache + (size_t)pg * k_page_stride + ((size_t)hk * D + lq) * a.page + (key & pmask);
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt) Vr[dt] = as_bf16x8(ld16(vp + (size_t)16 * dt * a.page));
-  };
+  }
+  const RowVis vis = make_row_vis(q_r, T, a.gamma, anc, (a.flags & SS_STREAM_EXCLUDE_SELF) != 0);
 
-  // ---- full 32-key blocks of the cached prefix: no mask, loads one block ahead,
-  // K reloaded as soon as the scores are done, V as soon as P.V is done
+  floatx4 O[DT];
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt) O[dt] = floatx4{0.f, 0.f, 0.f, 0.f};
+  float m_run = -1e30f, l_run = 0.f;
+
+  // ---- units of this split: full prefix blocks, the ragged prefix block, new-row blocks
   const int n_full = (k1 - k0) >> 5;
-  if (w < n_full) {
-    load_k(k0 + 32 * w);
-    load_v(k0 + 32 * w);
-  }
-  for (int j = w; j < n_full; j += 4) {
-    const bool more = (j + 4) < n_full;
-    bf16x8 Kc[2][KS], Vc[DT];
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      Kc[0][ks] = Kr[0][ks];
-      Kc[1][ks] = Kr[1][ks];
-    }
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt) Vc[dt] = Vr[dt];
-    if (more) {
-      load_k(k0 + 32 * (j + 4));
-      load_v(k0 + 32 * (j + 4));
-    }
-    attend_block<D, NQT>(Kc, Vc, Qs, lane, O, m, l, c, NoMask{});
-  }
-
-  // ---- blocks that need a mask, dealt round-robin to the waves after the full blocks
   const int tail = (k1 - k0) & 31;
-  const int n_new_blocks = is_last ? (R + 31) >> 5 : 0;
-  int unit = n_full;
-  if (tail) {
-    if ((unit & 3) == w) {
-      const int kb = k0 + 32 * n_full;
+  const int n_prefix_units = n_full + (tail ? 1 : 0);
+  const int n_units = n_prefix_units + (is_last ? (R + 31) >> 5 : 0);
+  const int n_iter = (n_units + n_groups - 1) / n_groups;  // same trip count for every group (barriers)
+  const size_t page_stride = (size_t)a.Hkv * a.page * D;   // elements per physical page (K and V alike)
+  const int pmask = a.page - 1;
+  unsigned char* my_stages = stages + (size_t)grp * 2 * STAGE_BYTES;
+
+  // ---- per-lane parts of all addresses (loop invariant, a handful of registers).  A unit is moved
+  // in LOADS slots of 1 KB.  K slot sl: rows ROWS_PER_SLOT*sl + lane/CPR, chunk position p = lane%CPR
+  // holding chunk p ^ k_swz(row); the swizzle's bit 2 only depends on the slot.  V slot s2 (prefix):
+  // 8-key chunks kc = 2*half + (lane&1) of features dblk*32 + lane/2, half = s2 / V_DBLK.
+  constexpr int V_DBLK = K_SLOTS / 2;  // 32-feature blocks per half unit
+  const int ril = lane / CPR, pch = lane % CPR;
+  const int k_src_lo = ril * D + ((pch ^ (ril & 3)) * 8);        // element offset, swizzle bit 2 clear
+  const int k_src_hi = ril * D + ((pch ^ (ril & 3) ^ 4) * 8);    // ... set
+  const int v_src = (lane >> 1) * a.page + (lane & 1) * 8;       // element offset inside a (page, feature block)
+  const int v_dst0 = K_BYTES + (lane >> 1) * VROW + ((((lane & 1)) ^ ((lane >> 2) & 3)) * 16);      // half 0
+  const int v_dst1 = K_BYTES + (lane >> 1) * VROW + (((2 + (lane & 1)) ^ ((lane >> 2) & 3)) * 16);  // half 1
+  // operand reads: K row of score tile 0 (tile 1 is 4 rows further), even / odd feature step; V row
+  const int rr0 = block_key(lq, 0), k_sh = (lq >> 2) & 1, k_lo = lg ^ (lq & 3);
+  const int k_rd_even = rr0 * (2 * D) + (((k_sh << 2) | k_lo) * 16);
+  const int k_rd_odd = rr0 * (2 * D) + ((((k_sh ^ 1) << 2) | k_lo) * 16);
+  const int v_rd = K_BYTES + lq * VROW + ((lg ^ ((lq >> 1) & 3)) * 16);
+
+  // Physical pages of the two 16-key halves of prefix unit u (scalar loads; equal for pages of 32 or
+  // 64 tokens).  A half past the end of the prefix gets the page of the last existing key.
+  auto fetch_pages = [&](int u, int& pg_a, int& pg_b) {
+    if (u < n_prefix_units) {
+      const int kb = k0 + 32 * u, last = k1 - 1;
+      pg_a = min(max(my_table[kb >> a.page_shift], 0), a.num_pages - 1);
+      pg_b = min(max(my_table[min(kb + 16, last & ~15) >> a.page_shift], 0), a.num_pages - 1);
+    }
+  };
+  // Load slots of unit u for this wave -> registers.  For units of the cached prefix the base address
+  // of a slot is scalar; a slot past the end of the prefix is pointed at the last existing keys (they
+  // are masked and their values zeroed later).
+  uintx4 stg[SLOTS];
+  auto load_unit = [&](int u, int pg_a, int pg_b) {
+    if (u < n_prefix_units) {
+      const int kb = k0 + 32 * u, last = k1 - 1;
 #pragma unroll
-      for (int X = 0; X < 2; ++X) {
-        const int key = kb + min(block_key(lq, X), tail - 1);
-        const int pg = pt[(key >> a.page_shift) - lp0];
-        const uint16_t* kp = k_cache + (size_t)pg * k_page_stride + ((size_t)hk * a.page + (key & pmask)) * D + lg * 8;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) Kr[X][ks] = as_bf16x8(ld16(kp + 32 * ks));
-      }
-      {
-        // the lane's 8 keys start at 8*lg; nv of them exist.  Address a chunk that
-        // exists, then zero what lies past the end so that 0 * garbage cannot be NaN.
-        const int nv = min(max(tail - 8 * lg, 0), 8);
-        const int key = kb + (nv > 0 ? 8 * lg : ((tail - 1) & ~7));
-        const int pg = pt[(key >> a.page_shift) - lp0];
-        const uint16_t* vp = v_cache + (size_t)pg * k_page_stride + ((size_t)hk * D + lq) * a.page + (key & pmask);
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-          uintx4 u = ld16(vp + (size_t)16 * dt * a.page);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const uint32_t keep = nv >= 2 * e + 2 ? 0xffffffffu : (nv == 2 * e + 1 ? 0x0000ffffu : 0u);
-            u[e] &= keep;
-          }
-          Vr[dt] = as_bf16x8(u);
+      for (int j = 0; j < SLOTS; ++j) {
+        const int sl = wt + NW * j;
+        if (sl < K_SLOTS) {
+          const int key0 = min(kb + ROWS_PER_SLOT * sl, last & ~(ROWS_PER_SLOT - 1));
+          const int pg = key0 - kb >= 16 ? pg_b : pg_a;
+          const uint16_t* base = k_cache + (size_t)pg * page_stride + ((size_t)hk * a.page + (key0 & pmask)) * D;
+          const bool hi = ((ROWS_PER_SLOT * sl) >> 3) & 1;
+          stg[j] = ld16(base + (hi ? k_src_hi : k_src_lo));
+        } else if (sl < LOADS) {
+          const int s2 = sl - K_SLOTS, half = s2 / V_DBLK, dblk = s2 % V_DBLK;
+          const int key0 = min(kb + 16 * half, last & ~15);
+          const int pg = key0 - kb >= 16 ? pg_b : pg_a;
+          const uint16_t* base =
+              v_cache + (size_t)pg * page_stride + ((size_t)hk * D + dblk * 32) * a.page + (key0 & pmask);
+          stg[j] = ld16(base + v_src);
         }
       }
-      attend_block<D, NQT>(Kr, Vr, Qs, lane, O, m, l, c, TailMask{tail, lg});
+    } else {
+      // new rows (rare): per-lane row clamp; V rows are token-major and are staged row-major
+      const int c0 = 32 * (u - n_prefix_units);
+#pragma unroll
+      for (int j = 0; j < SLOTS; ++j) {
+        const int sl = wt + NW * j;
+        if (sl < LOADS) {
+          const bool is_k = sl < K_SLOTS;
+          const int rr = ROWS_PER_SLOT * (is_k ? sl : sl - K_SLOTS) + ril;
+          const size_t row = ((size_t)b * R + min(c0 + rr, R - 1)) * a.Hkv + hk;
+          stg[j] = is_k ? ld16(k_new + row * D + ((pch ^ k_swz(rr)) * 8)) : ld16(v_new + row * D + pch * 8);
+        }
+      }
     }
-    ++unit;
+  };
+  // Registers -> LDS stage (layouts as the operand reads expect them).
+  auto store_unit = [&](int u, unsigned char* st) {
+    const bool is_new = u >= n_prefix_units;
+#pragma unroll
+    for (int j = 0; j < SLOTS; ++j) {
+      const int sl = wt + NW * j;
+      if (sl < K_SLOTS) {
+        *reinterpret_cast<uintx4*>(st + sl * 1024 + lane * 16) = stg[j];
+      } else if (sl < LOADS) {
+        const int s2 = sl - K_SLOTS;
+        if (!is_new) {
+          const int half = s2 / V_DBLK, dblk = s2 % V_DBLK;
+          *reinterpret_cast<uintx4*>(st + dblk * (32 * VROW) + (half ? v_dst1 : v_dst0)) = stg[j];
+        } else {
+          const int rr = ROWS_PER_SLOT * s2 + ril;
+          *reinterpret_cast<uintx4*>(st + K_BYTES + rr * (2 * D) + ((pch ^ (2 * (rr & 3))) * 16)) = stg[j];
+        }
+      }
+    }
+  };
+
+  // ---- prologue: first unit of this group into stage 0; page ids are fetched one unit ahead of
+  // the loads that need them
+  int pg_a = 0, pg_b = 0, pgn_a = 0, pgn_b = 0;
+  fetch_pages(grp, pg_a, pg_b);
+  fetch_pages(grp + n_groups, pgn_a, pgn_b);
+  if (grp < n_units) {
+    load_unit(grp, pg_a, pg_b);
+    store_unit(grp, my_stages);
   }
-  for (int nb = 0; nb < n_new_blocks; ++nb, ++unit) {
-    if ((unit & 3) != w) continue;
-    const int c0 = 32 * nb;
+  __syncthreads();
+
+#ifdef SS_MSA_TIMING
+  long long tacc[8] = {0, 0, 0, 0, 0, 0, 0, 0}, t_last = clock64();
+#endif
+  for (int it = 0; it < n_iter; ++it) {
+    const int u = grp + it * n_groups;
+    const int u_next = u + n_groups;
+    unsigned char* st = my_stages + (it & 1) * STAGE_BYTES;
+    if (u_next < n_units) load_unit(u_next, pgn_a, pgn_b);  // in flight while this unit is computed
+    fetch_pages(u_next + n_groups, pgn_a, pgn_b);           // page ids of the unit after that
+    SS_T(0);
+
+    if (u < n_units) {
+      const bool is_new = u >= n_prefix_units;
+      // ---- scores S^T = K Q^T
+      floatx4 S[2];
 #pragma unroll
-    for (int X = 0; X < 2; ++X) {
-      const int row = min(c0 + block_key(lq, X), R - 1);
-      const uint16_t* kp = k_new + (((size_t)b * R + row) * a.Hkv + hk) * D + lg * 8;
+      for (int X = 0; X < 2; ++X) {
+        floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) Kr[X][ks] = as_bf16x8(ld16(kp + 32 * ks));
+        for (int ks = 0; ks < KS; ++ks) {
+          const uintx4 kop = *reinterpret_cast<const uintx4*>(st + ((ks & 1) ? k_rd_odd : k_rd_even) +
+                                                              (ks >> 1) * 128 + X * (8 * D));
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kop), Qr[ks], acc, 0, 0, 0);
+        }
+        S[X] = acc;
+      }
+      SS_KEEP(S[0]);
+      SS_KEEP(S[1]);
+      SS_T(1);
+      // ---- mask (only the ragged prefix block and the new rows)
+      if (u >= n_full) {
+        const int c0 = 32 * (u - n_prefix_units);
+#pragma unroll
+        for (int X = 0; X < 2; ++X)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int off = 8 * lg + 4 * X + i;
+            const bool see_tail = off < tail;
+            const bool see_new = (c0 + off < R) & row_sees(vis, c0 + off, T);
+            const float sv = S[X][i];
+            S[X][i] = (is_new ? see_new : see_tail) ? sv : -INFINITY;
+          }
+      }
+      // ---- online softmax (log2 domain, lazy rescale), probabilities to bf16
+      float mx = fmaxf(fmaxf(fmaxf(S[0][0], S[0][1]), fmaxf(S[0][2], S[0][3])),
+                       fmaxf(fmaxf(S[1][0], S[1][1]), fmaxf(S[1][2], S[1][3])));
+      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      if (__any((mx - m_run) * c > kLazyLog2)) {
+        const float m_new = fmaxf(m_run, mx);
+        const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
+        l_run *= alpha;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) O[dt] *= alpha;
+        m_run = m_new;
+      }
+      const float mc = m_run * c;
+      bf16x8 P;
+      float ps = 0.f;
+#pragma unroll
+      for (int X = 0; X < 2; ++X)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float pr = __builtin_amdgcn_exp2f(fmaf(S[X][i], c, -mc));
+          ps += pr;
+          P[4 * X + i] = (__bf16)pr;
+        }
+      l_run += ps;
+      SS_KEEP(P);
+      SS_T(2);
+      // ---- O^T += V^T P^T
+      if (u < n_full) {
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+          const uintx4 vv = *reinterpret_cast<const uintx4*>(st + v_rd + dt * (16 * VROW));
+          O[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vv), P, O[dt], 0, 0, 0);
+        }
+      } else if (!is_new) {
+        const int nv = min(max(tail - 8 * lg, 0), 8);  // how many of this lane's 8 tokens exist
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+          uintx4 vv = *reinterpret_cast<const uintx4*>(st + v_rd + dt * (16 * VROW));
+#pragma unroll
+          for (int e = 0; e < 4; ++e) vv[e] &= nv >= 2 * e + 2 ? 0xffffffffu : (nv == 2 * e + 1 ? 0x0000ffffu : 0u);
+          O[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vv), P, O[dt], 0, 0, 0);
+        }
+      } else {
+        const unsigned char* vb = st + K_BYTES;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+          uintx2 half[2];
+#pragma unroll
+          for (int hh = 0; hh < 2; ++hh) {
+            const int row = 8 * lg + 4 * hh + (lq >> 2);  // keys 8*lg + 4*hh .. +3 reach this lane
+            const int ch = 2 * dt + ((lq & 3) >> 1);      // 16-byte chunk with features 16*dt + 4*(lq&3)..
+            half[hh] = lds_read_tr16(vb + row * (2 * D) + ((ch ^ (2 * (row & 3))) * 16) + (lq & 1) * 8);
+          }
+          const uintx4 vv = uintx4{half[0][0], half[0][1], half[1][0], half[1][1]};
+          O[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vv), P, O[dt], 0, 0, 0);
+        }
+      }
     }
-    // V rows are token-major here: stage the 32 rows in this wave's LDS tile, then gather columns
-    uint16_t* vst = reinterpret_cast<uint16_t*>(buf) + w * 32 * D;
-#pragma unroll
-    for (int n = 0; n < DT; ++n) {
-      const int id = lane + 64 * n;
-      const int row = id / (D / 8), ch = id % (D / 8);
-      const int src = min(c0 + row, R - 1);
-      *reinterpret_cast<uintx4*>(vst + row * D + ch * 8) =
-          ld16(v_new + (((size_t)b * R + src) * a.Hkv + hk) * D + ch * 8);
+
+    SS_KEEP(O[0]);
+    SS_KEEP(O[DT - 1]);
+    SS_T(3);
+    if (u_next < n_units) store_unit(u_next, my_stages + ((it + 1) & 1) * STAGE_BYTES);
+    SS_T(4);
+    __syncthreads();  // the next stage is complete, this one may be overwritten after the next barrier
+    SS_T(5);
+  }
+#ifdef SS_MSA_TIMING
+  if (lane == 0 && blockIdx.x < 64) {
+    long long* dbg = (long long*)a.part_lse + 1000000 + (blockIdx.x * 16 + w) * 8;
+    for (int i = 0; i < 6; ++i) dbg[i] = tacc[i];
+    dbg[6] = n_iter;
+  }
+#endif
+
+  // ---- merge the groups.  Every wave reduces its sum over the four lane groups; groups > 0 leave
+  // (max, sum, O) in LDS; group 0 brings everything to a common maximum, adds and stores.
+  l_run += __shfl_xor(l_run, 16, 64);
+  l_run += __shfl_xor(l_run, 32, 64);
+  floatx4* obuf = reinterpret_cast<floatx4*>(stages);  // [(grp-1)*NW + wt][DT][64]
+  float* my_ml = ml + (grp * NW + wt) * 32;
+  if (grp > 0) {
+    if (lg == 0) {
+      my_ml[lq] = m_run;
+      my_ml[16 + lq] = l_run;
     }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) obuf[(((grp - 1) * NW + wt) * DT + dt) * 64 + lane] = O[dt];
+  }
+  __syncthreads();
+  if (grp > 0) return;
+
+  float mm = m_run;
+  for (int g2 = 1; g2 < n_groups; ++g2) mm = fmaxf(mm, ml[(g2 * NW + wt) * 32 + lq]);
+  {
+    const float fac = __builtin_amdgcn_exp2f((m_run - mm) * c);
+    l_run *= fac;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) O[dt] *= fac;
+  }
+  for (int g2 = 1; g2 < n_groups; ++g2) {
+    const float* oml = ml + (g2 * NW + wt) * 32;
+    const float fac = __builtin_amdgcn_exp2f((oml[lq] - mm) * c);
+    l_run += oml[16 + lq] * fac;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) O[dt] += obuf[(((g2 - 1) * NW + wt) * DT + dt) * 64 + lane] * fac;
+  }
+
+  // ---- normalise and store.  A lane holds features 16*dt + 4*lg .. +3 of its query row.
+  if (!f_valid) return;
+  const float inv = l_run > 0.f ? 1.f / l_run : 0.f;
+  if (a.n_splits == 1) {
+    uint16_t* op = (uint16_t*)a.out + (((size_t)b * R + q_r) * a.H + q_h) * D + 4 * lg;
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) {
-      uintx4 u;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const uint32_t lo = vst[(8 * lg + 2 * e) * D + 16 * dt + lq];
-        const uint32_t hi = vst[(8 * lg + 2 * e + 1) * D + 16 * dt + lq];
-        u[e] = lo | (hi << 16);
-      }
-      Vr[dt] = as_bf16x8(u);
+      const floatx4 v = O[dt] * inv;
+      *reinterpret_cast<uintx2*>(op + 16 * dt) = uintx2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
     }
-    __builtin_amdgcn_wave_barrier();
-    attend_block<D, NQT>(Kr, Vr, Qs, lane, O, m, l, c, NewMask<NQT>{vis, c0, lg, R, T});
-  }
-
-  // ---- merge the four waves.  First agree on a common maximum per query and
-  // bring every wave's sum and O to it, then add the O's pairwise through LDS.
+  } else {
+    const size_t pr = (((size_t)b * a.H + q_h) * a.n_splits + s) * R + q_r;
+    float* op = a.part_o + pr * D + 4 * lg;
 #pragma unroll
-  for (int t = 0; t < NQT; ++t) {
-    l[t] += __shfl_xor(l[t], 16, 64);
-    l[t] += __shfl_xor(l[t], 32, 64);
-  }
-  __syncthreads();  // all waves are done with the staging tiles in buf
-  if (lg == 0) {
-#pragma unroll
-    for (int t = 0; t < NQT; ++t) {
-      m_sh[w][16 * t + lq] = m[t];
-      l_sh[w][16 * t + lq] = l[t];
-    }
-  }
-  __syncthreads();
-  float mw[NQT], lw[NQT];
-#pragma unroll
-  for (int t = 0; t < NQT; ++t) {
-    const int qi = 16 * t + lq;
-    const float mm = fmaxf(fmaxf(m_sh[0][qi], m_sh[1][qi]), fmaxf(m_sh[2][qi], m_sh[3][qi]));
-    float ll = 0.f;
-#pragma unroll
-    for (int ww = 0; ww < 4; ++ww) ll += l_sh[ww][qi] * __builtin_amdgcn_exp2f((m_sh[ww][qi] - mm) * c);
-    const float fac = __builtin_amdgcn_exp2f((m[t] - mm) * c);
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt) O[dt][t] *= fac;
-    mw[t] = mm;
-    lw[t] = ll;
-  }
-  floatx4* obuf = reinterpret_cast<floatx4*>(buf);
-  constexpr int WAVE_TILES = DT * NQT * 64;
-  if (w >= 2) {
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-      for (int t = 0; t < NQT; ++t) obuf[(w - 2) * WAVE_TILES + (dt * NQT + t) * 64 + lane] = O[dt][t];
-  }
-  __syncthreads();
-  if (w < 2) {
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-      for (int t = 0; t < NQT; ++t) O[dt][t] += obuf[w * WAVE_TILES + (dt * NQT + t) * 64 + lane];
-  }
-  __syncthreads();
-  if (w == 1) {
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-      for (int t = 0; t < NQT; ++t) obuf[(dt * NQT + t) * 64 + lane] = O[dt][t];
-  }
-  __syncthreads();
-  if (w != 0) return;
-
-  // ---- wave 0 finishes: normalise and store.  A lane holds features 16*dt+4*lg..+3 of query 16*t+lq.
-#pragma unroll
-  for (int t = 0; t < NQT; ++t) {
-    const int f = qc * QROWS + 16 * t + lq;
-    if (f >= F) continue;
-    const int hg = f / R, r = f % R, h = hk * a.g + hg;
-    const float inv = lw[t] > 0.f ? 1.f / lw[t] : 0.f;
-    if (a.n_splits == 1) {
-      uint16_t* op = (uint16_t*)a.out + (((size_t)b * R + r) * a.H + h) * D + 4 * lg;
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt) {
-        const floatx4 v = (O[dt][t] + obuf[(dt * NQT + t) * 64 + lane]) * inv;
-        *reinterpret_cast<uintx2*>(op + 16 * dt) = uintx2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
-      }
-    } else {
-      const size_t pr = (((size_t)b * a.H + h) * a.n_splits + s) * R + r;
-      float* op = a.part_o + pr * D + 4 * lg;
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt)
-        *reinterpret_cast<floatx4*>(op + 16 * dt) = (O[dt][t] + obuf[(dt * NQT + t) * 64 + lane]) * inv;
-      if (lg == 0) a.part_lse[pr] = mw[t] * c + __log2f(lw[t]);
-    }
+    for (int dt = 0; dt < DT; ++dt) *reinterpret_cast<floatx4*>(op + 16 * dt) = O[dt] * inv;
+    if (lg == 0) a.part_lse[pr] = mm * c + __log2f(l_run);
   }
 }
 
+// Folded query rows one workgroup takes (a multiple of 16, at most 80).
 int msa_bf16_rows_per_chunk(int F) {
   if (F <= 80) return 16 * ceil_div(F < 1 ? 1 : F, 16);
   int best = 80, best_pad = ceil_div(F, 80) * 80 - F;
@@ -431,22 +458,53 @@ int msa_bf16_rows_per_chunk(int F) {
   return best;
 }
 
-template <int D>
-static int launch_d(const MsaArgs& a, hipStream_t stream) {
-  const int rows = msa_bf16_rows_per_chunk(a.g * a.R);
+// Wave groups per workgroup for NW query tiles: as many as fit kMaxWaves waves, at most kMaxGroups.
+static int groups_for(int nw) {
+  static const int forced = []() {
+    const char* e = getenv("SS_MSA_GROUPS");  // tuning aid
+    const int v = e ? atoi(e) : 0;
+    return (v >= 1 && v <= kMaxGroups) ? v : 0;
+  }();
+  int g = kMaxWaves / nw;
+  if (g > kMaxGroups) g = kMaxGroups;
+  if (forced && forced <= g) g = forced;
+  return g < 1 ? 1 : g;
+}
+
+template <int D, int NW>
+static int launch_dn(const MsaArgs& a, hipStream_t stream) {
+  const int n_groups = groups_for(NW);
   const int G = a.B * a.Hkv * a.n_splits;
   const long wgs = (long)ceil_div(G, 8) * 8 * a.n_qc;
   SS_REQUIRE(wgs <= 0x7fffffffL, SS_ERR_UNSUPPORTED, "ss_msa_attention: grid too large");
-  dim3 grid((unsigned)wgs), block(256);
+  const size_t stage_bytes = 2 * 32 * D * 2;
+  const size_t merge_bytes = (size_t)(n_groups - 1) * NW * (D / 16) * 64 * 16;
+  size_t lds = (size_t)n_groups * 2 * stage_bytes;
+  if (merge_bytes > lds) lds = merge_bytes;
+  lds += SS_MAX_T * 4 + SS_MAX_T * 8 + (size_t)n_groups * NW * 32 * 4;
+  auto kern = msa_bf16_kernel<D, NW>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e != hipSuccess) SS_FAIL(SS_ERR_HIP, "ss_msa_attention: hipFuncSetAttribute: %s", hipGetErrorString(e));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(64 * NW * n_groups), lds, stream, a, n_groups);
+  return check_launch("ss_msa_attention");
+}
+
+template <int D>
+static int launch_d(const MsaArgs& a, hipStream_t stream) {
+  const int rows = msa_bf16_rows_per_chunk(a.g * a.R);
   switch (rows / 16) {
-    case 1: hipLaunchKernelGGL((msa_bf16_kernel<D, 1>), grid, block, 0, stream, a); break;
-    case 2: hipLaunchKernelGGL((msa_bf16_kernel<D, 2>), grid, block, 0, stream, a); break;
-    case 3: hipLaunchKernelGGL((msa_bf16_kernel<D, 3>), grid, block, 0, stream, a); break;
-    case 4: hipLaunchKernelGGL((msa_bf16_kernel<D, 4>), grid, block, 0, stream, a); break;
-    case 5: hipLaunchKernelGGL((msa_bf16_kernel<D, 5>), grid, block, 0, stream, a); break;
+    case 1: return launch_dn<D, 1>(a, stream);
+    case 2: return launch_dn<D, 2>(a, stream);
+    case 3: return launch_dn<D, 3>(a, stream);
+    case 4: return launch_dn<D, 4>(a, stream);
+    case 5: return launch_dn<D, 5>(a, stream);
     default: SS_FAIL(SS_ERR_UNSUPPORTED, "ss_msa_attention: bad row chunk %d", rows);
   }
-  return check_launch("ss_msa_attention");
 }
 
 int launch_msa_bf16(const MsaArgs& a, hipStream_t stream) {
