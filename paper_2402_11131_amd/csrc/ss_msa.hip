@@ -165,39 +165,52 @@ __global__ __launch_bounds__(256) void msa_f32_kernel(MsaArgs a) {
 
 // ------------------------------------------------------------------ merge of splits
 //
-// out = sum_s w_s * o_s with w_s = 2^(lse_s - max) / sum; one wavefront per
-// (sequence, row, head), lanes across features.
+// out = sum_s w_s * o_s with w_s = 2^(lse_s - max) / sum.  One thread per (sequence, row, head,
+// 4 features).  The partial outputs are fetched four splits at a time without waiting for the
+// log-sum-exps (their addresses do not depend on them) and folded in with a running maximum, so the
+// kernel is one round of independent loads deep; splits a sequence does not use are never read.
 template <bool BF16>
 __global__ __launch_bounds__(256) void msa_combine_kernel(MsaArgs a) {
-  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const long item = (long)blockIdx.x * 4 + w;
-  const long n_items = (long)a.B * a.R * a.H;
-  if (item >= n_items) return;
+  const int dq = a.D >> 2;  // threads per row
+  const long t = (long)blockIdx.x * 256 + threadIdx.x;
+  const long item = t / dq;
+  const int d0 = (int)(t % dq) * 4;
+  if (item >= (long)a.B * a.R * a.H) return;
   const int h = item % a.H;
   const int r = (item / a.H) % a.R;
   const int b = item / ((long)a.H * a.R);
   const int n_active = active_splits(clamp_len(a.seq_lens[b], a), a);
   const size_t base = (((size_t)b * a.H + h) * a.n_splits) * a.R + r;
-  float mx = -INFINITY;
-  for (int s = 0; s < n_active; ++s) mx = fmaxf(mx, a.part_lse[base + (size_t)s * a.R]);
-  float wsum = 0.f;
-  for (int s = 0; s < n_active; ++s) wsum += exp2f(a.part_lse[base + (size_t)s * a.R] - mx);
-  const float inv = 1.f / wsum;
-  const int D = a.D;
-  for (int d0 = 2 * lane; d0 < D; d0 += 128) {
-    float acc0 = 0.f, acc1 = 0.f;
-    for (int s = 0; s < n_active; ++s) {
-      const float ws = exp2f(a.part_lse[base + (size_t)s * a.R] - mx) * inv;
-      const float2 v = *(const float2*)(a.part_o + (base + (size_t)s * a.R) * D + d0);
-      acc0 = fmaf(ws, v.x, acc0);
-      acc1 = fmaf(ws, v.y, acc1);
+  float m = -INFINITY, wsum = 0.f;
+  floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};
+  for (int s0 = 0; s0 < n_active; s0 += 4) {
+    floatx4 v[4];
+    float l[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int s = min(s0 + i, n_active - 1);
+      const size_t row = base + (size_t)s * a.R;
+      v[i] = *reinterpret_cast<const floatx4*>(a.part_o + row * a.D + d0);
+      l[i] = a.part_lse[row];
     }
-    const size_t oidx = (((size_t)b * a.R + r) * a.H + h) * D + d0;
-    if (BF16) {
-      *(uint32_t*)((uint16_t*)a.out + oidx) = pack_bf16x2(acc0, acc1);
-    } else {
-      *(float2*)((float*)a.out + oidx) = make_float2(acc0, acc1);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (s0 + i < n_active && l[i] > -INFINITY) {
+        const float m_new = fmaxf(m, l[i]);
+        const float keep = exp2f(m - m_new), w = exp2f(l[i] - m_new);
+        acc = acc * keep + v[i] * w;
+        wsum = wsum * keep + w;
+        m = m_new;
+      }
     }
+  }
+  const float inv = wsum > 0.f ? 1.f / wsum : 0.f;
+  acc *= inv;
+  const size_t oidx = (((size_t)b * a.R + r) * a.H + h) * a.D + d0;
+  if (BF16) {
+    *reinterpret_cast<uintx2*>((uint16_t*)a.out + oidx) = uintx2{pack_bf16x2(acc[0], acc[1]), pack_bf16x2(acc[2], acc[3])};
+  } else {
+    *reinterpret_cast<floatx4*>((float*)a.out + oidx) = acc;
   }
 }
 
@@ -206,17 +219,20 @@ __global__ __launch_bounds__(256) void msa_combine_kernel(MsaArgs a) {
 static int g_split_keys_override = 0;
 
 struct MsaPlan {
-  int split_keys, n_splits, n_qc;
+  int split_keys, n_splits, n_qc, groups;
   size_t part_o_bytes, part_lse_bytes, total_bytes;
 };
 
-// Chooses the split length from the shape alone (sequence lengths live on the
-// device): enough workgroups to cover the 256 compute units about twice, but no
-// split shorter than 256 cached tokens.
+// Chooses the split length from the shape alone (sequence lengths live on the device): just enough
+// splits for about 512 workgroups (two resident per compute unit), because every further split costs
+// a workgroup set-up and fp32 partial results that the merge kernel reads back; no split shorter
+// than 256 cached tokens.  When even that leaves the chip short of workgroups the MFMA path runs two
+// wave groups per workgroup (a split inside the workgroup, merged through LDS).
 static MsaPlan make_plan(int B, int R, int H, int Hkv, int D, int max_len, int dtype) {
   MsaPlan p;
   const int g = H / Hkv;
   int base;
+  p.groups = 1;
   if (dtype == SS_BF16) {
     const int rows = msa_bf16_rows_per_chunk(g * R);
     p.n_qc = ceil_div(g * R, rows);
@@ -225,21 +241,21 @@ static MsaPlan make_plan(int B, int R, int H, int Hkv, int D, int max_len, int d
     p.n_qc = ceil_div(R, 32);
     base = B * H * p.n_qc;
   }
+  if (base < 1) base = 1;
+  const int len = max_len < 1 ? 1 : max_len;
   int split_keys;
   if (g_split_keys_override > 0) {
     split_keys = g_split_keys_override;
   } else {
-    const int target_wgs = 512;
-    int n = ceil_div(target_wgs, base < 1 ? 1 : base);
-    const int n_cap = max_len / 256 < 1 ? 1 : max_len / 256;
+    int n = ceil_div(512, base);
+    const int n_cap = len / 256 < 1 ? 1 : len / 256;
     if (n > n_cap) n = n_cap;
-    if (n < 1) n = 1;
-    split_keys = ceil_div(max_len < 1 ? 1 : max_len, n);
+    split_keys = ceil_div(len, n);
   }
-  split_keys = (int)align_up((size_t)(split_keys < 128 ? 128 : split_keys), 128);
+  split_keys = (int)align_up((size_t)(split_keys < 64 ? 64 : split_keys), 64);
   p.split_keys = split_keys;
-  p.n_splits = max_len <= 0 ? 1 : ceil_div(max_len, split_keys);
-  if (p.n_splits < 1) p.n_splits = 1;
+  p.n_splits = ceil_div(len, split_keys);
+  if (dtype == SS_BF16 && (long)base * p.n_splits < 384) p.groups = 2;
   if (p.n_splits > 1) {
     p.part_o_bytes = align_up((size_t)B * H * p.n_splits * R * D * sizeof(float), 256);
     p.part_lse_bytes = align_up((size_t)B * H * p.n_splits * R * sizeof(float), 256);
@@ -315,7 +331,7 @@ int ss_msa_attention(const void* q, const void* k_new, const void* v_new, const 
   a.B = B; a.T = T; a.gamma = gamma; a.R = R; a.H = H; a.Hkv = Hkv; a.g = H / Hkv; a.D = D;
   a.page = page_size; a.page_shift = page_size == 16 ? 4 : (page_size == 32 ? 5 : 6);
   a.max_pages = max_pages_per_seq; a.num_pages = num_pages;
-  a.split_keys = plan.split_keys; a.n_splits = plan.n_splits; a.n_qc = plan.n_qc;
+  a.split_keys = plan.split_keys; a.n_splits = plan.n_splits; a.n_qc = plan.n_qc; a.groups = plan.groups;
   a.scale_log2 = scale * 1.4426950408889634f;
   a.flags = flags;
   hipStream_t st = (hipStream_t)stream;
@@ -330,8 +346,8 @@ int ss_msa_attention(const void* q, const void* k_new, const void* v_new, const 
     if (int rc = launch_msa_bf16(a, st)) return rc;
   }
   if (plan.n_splits > 1 && !(flags & SS_MSA_PARTIALS_ONLY)) {
-    const long items = (long)B * R * H;
-    dim3 grid((unsigned)((items + 3) / 4));
+    const long threads = (long)B * R * H * (D / 4);
+    dim3 grid((unsigned)((threads + 255) / 256));
     if (dtype == SS_F32) hipLaunchKernelGGL(msa_combine_kernel<false>, grid, dim3(256), 0, st, a);
     else hipLaunchKernelGGL(msa_combine_kernel<true>, grid, dim3(256), 0, st, a);
     if (int rc = check_launch(fn)) return rc;

@@ -46,6 +46,8 @@
 // read ds_read_b64_tr_b16, which hands a lane 4 consecutive keys of one feature).
 #include <stdlib.h>
 
+#include <type_traits>
+
 #include "ss_msa.h"
 
 // Optional phase timing (development aid, compiled in with -DSS_MSA_TIMING): cycle counts per phase
@@ -62,7 +64,7 @@ namespace ss {
 
 constexpr float kLazyLog2 = 16.0f;
 constexpr int kMaxGroups = 4;  // wave groups per workgroup
-constexpr int kMaxWaves = 12;  // waves per workgroup: 3 per SIMD leaves each wave 168 vector registers
+constexpr int kMaxWaves = 16;  // waves per workgroup: 4 per SIMD leaves each wave 128 vector registers
 
 // key (0..31) that row m of score tile X holds inside a 32-key unit
 SS_DEV int block_key(int m, int X) { return 8 * (m >> 2) + (m & 3) + 4 * X; }
@@ -87,14 +89,15 @@ SS_DEV uintx2 lds_read_tr16(const unsigned char* p) {
 template <int D, int NW>
 __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves / NW : kMaxGroups)) void msa_bf16_kernel(MsaArgs a, int n_groups) {
   constexpr int KS = D / 32, DT = D / 16;
-  constexpr int K_BYTES = 32 * D * 2;           // K rows of a unit (V takes the same)
+  constexpr int K_BYTES = 32 * D * 2;          // K rows of a unit (V takes the same)
   constexpr int STAGE_BYTES = 2 * K_BYTES;
-  constexpr int LOADS = STAGE_BYTES / 1024;     // 1 KB load slots per unit
-  constexpr int SLOTS = (LOADS + NW - 1) / NW;  // slots per wave
-  constexpr int CPR = D / 8;                    // 16-byte chunks per K row
+  constexpr int K_SLOTS = K_BYTES / 1024;      // 1 KB load slots of a unit's K rows (V: as many)
+  constexpr int LW = NW >= 4 ? 4 : NW >= 2 ? 2 : 1;  // waves of a group that move data: divides K_SLOTS
+  constexpr int KJ = K_SLOTS / LW;             // K slots per loading wave, and V slots per loading wave
+  constexpr int CPR = D / 8;                   // 16-byte chunks per K row
   constexpr int ROWS_PER_SLOT = 64 / CPR;
-  constexpr int K_SLOTS = LOADS / 2;
-  constexpr int VROW = 64;                      // bytes per feature row of the V tile (32 keys)
+  constexpr int V_DBLK = K_SLOTS / 2;          // 32-feature blocks per 16-key half of the V tile
+  constexpr int VROW = 64;                     // bytes per feature row of the V tile (32 keys)
 
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   // smem: [n_groups][2][STAGE_BYTES] stages (reused by the final merge) | par | anc | ml
@@ -103,6 +106,9 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
   uint64_t* anc = reinterpret_cast<uint64_t*>(par + SS_MAX_T);
   float* ml = reinterpret_cast<float*>(anc + SS_MAX_T);  // [n_groups][NW][2][16]: max, sum per query
 
+#ifdef SS_MSA_TIMING
+  const long long t_entry = clock64();
+#endif
   // ---- which piece of work: XCD-aware order.  Workgroup ids go round-robin over
   // the 8 XCDs, so ids that are equal mod 8 share an L2: the query chunks of one
   // (sequence, KV head, split) are given such ids and read K/V through one L2.
@@ -116,7 +122,7 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
   const int b = group / (a.n_splits * a.Hkv);
 
   // The wave index is made known to be wave-uniform, so that everything derived from it (unit, load
-  // slot, page lookups, base addresses) is computed on the scalar unit.
+  // slots, base addresses) is computed on the scalar unit.
   const int tid = threadIdx.x, lane = tid & 63, lq = lane & 15, lg = lane >> 4;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int grp = w / NW, wt = w % NW;  // wave group, query tile of this wave
@@ -125,25 +131,62 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
   const int n_active = active_splits(L, a);
   if (s >= n_active) return;
   const bool is_last = (s == n_active - 1);
-  const int k0 = s * a.split_keys;
-  const int k1 = max(k0, min(L, k0 + a.split_keys));
+  // Key range of this split, in 32-key units.  The last active split also takes the step's own rows
+  // (and the tree work that goes with them), so it is given that much less of the prefix.
+  int k0, k1;
+  {
+    const int nu = (L + 31) >> 5, extra = ((R + 31) >> 5) + 2;
+    int per = (nu + extra + n_active / 2) / n_active;
+    if (per < 1) per = 1;
+    while (per > 1 && (n_active - 1) * per >= nu) --per;
+    k0 = min(s * per * 32, L);
+    k1 = is_last ? L : min((s + 1) * per * 32, L);
+  }
   const float c = a.scale_log2;
 
   const uint16_t* q = (const uint16_t*)a.q;
   const uint16_t* k_new = (const uint16_t*)a.k_new;
   const uint16_t* v_new = (const uint16_t*)a.v_new;
-  const uint16_t* k_cache = (const uint16_t*)a.k_cache;
-  const uint16_t* v_cache = (const uint16_t*)a.v_cache;
   const int32_t* my_table = a.block_table + (size_t)b * a.max_pages;
+  const size_t page_stride = (size_t)a.Hkv * a.page * D;  // elements per physical page (K and V alike)
+  const uint16_t* k_head = (const uint16_t*)a.k_cache + (size_t)hk * a.page * D;  // this head inside page 0
+  const uint16_t* v_head = (const uint16_t*)a.v_cache + (size_t)hk * a.page * D;
+  const int pmask = a.page - 1;
 
-  // ---- tree -> ancestor sets
-  if (tid < T) par[tid] = clamp_parent(a.parent[(size_t)b * T + tid], tid);
-  __syncthreads();
-  compute_anc(par, T, anc, tid);
-  __syncthreads();
+  // ---- units of this split: full 32-key blocks of the prefix, its ragged last block, blocks of
+  // the step's own rows (last split only).  The first n_main * n_groups full blocks go through the
+  // pipelined main loop, n_main per group; whatever is left is handled one by one afterwards.
+  const int n_full = (k1 - k0) >> 5;
+  const int tail = (k1 - k0) & 31;
+  const int n_prefix_units = n_full + (tail ? 1 : 0);
+  const int n_units = n_prefix_units + (is_last ? (R + 31) >> 5 : 0);
+  const int n_main = n_full / n_groups;
+  unsigned char* my_stages = stages + (size_t)grp * 2 * STAGE_BYTES;
+
+  // Physical pages of the two 16-key halves of this group's main-loop units (equal for pages of 32
+  // or 64 tokens).  Lane i of every wave keeps the pair for loop iteration jbase + i; one gather
+  // serves 64 iterations and a page id reaches the scalar unit through a lane read, so that no
+  // memory wait sits between issuing a unit's loads and computing on the previous unit.
+  int tab_a = 0, tab_b = 0;
+  auto refill_pages = [&](int jbase) {
+    if (n_main > 0) {
+      const int uu = grp + min(jbase + lane, n_main - 1) * n_groups;
+      const int kb = k0 + 32 * uu;
+      tab_a = min(max(my_table[kb >> a.page_shift], 0), a.num_pages - 1);
+      tab_b = min(max(my_table[(kb + 16) >> a.page_shift], 0), a.num_pages - 1);
+    }
+  };
+  refill_pages(0);
+  // The tree's ancestor sets go to LDS now, while the first loads are in flight; only the split that
+  // scans the step's own rows needs them.
+  if (is_last) {
+    if (tid < T) par[tid] = clamp_parent(a.parent[(size_t)b * T + tid], tid);
+    __syncthreads();
+    compute_anc(par, T, anc, tid);
+  }
 
   // ---- this wave's query tile: MFMA B operands (lane (lq, lg) holds features 8*(4*ks+lg).. of
-  // folded query row f) and the row's visibility of the step's own keys
+  // folded query row f)
   const int f = qc * (16 * NW) + 16 * wt + lq;
   const bool f_valid = f < F;
   const int q_r = f_valid ? f % R : 0, q_h = hk * a.g + (f_valid ? f / R : 0);
@@ -157,240 +200,289 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
       Qr[ks] = as_bf16x8(u);
     }
   }
-  const RowVis vis = make_row_vis(q_r, T, a.gamma, anc, (a.flags & SS_STREAM_EXCLUDE_SELF) != 0);
 
   floatx4 O[DT];
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt) O[dt] = floatx4{0.f, 0.f, 0.f, 0.f};
   float m_run = -1e30f, l_run = 0.f;
 
-  // ---- units of this split: full prefix blocks, the ragged prefix block, new-row blocks
-  const int n_full = (k1 - k0) >> 5;
-  const int tail = (k1 - k0) & 31;
-  const int n_prefix_units = n_full + (tail ? 1 : 0);
-  const int n_units = n_prefix_units + (is_last ? (R + 31) >> 5 : 0);
-  const int n_iter = (n_units + n_groups - 1) / n_groups;  // same trip count for every group (barriers)
-  const size_t page_stride = (size_t)a.Hkv * a.page * D;   // elements per physical page (K and V alike)
-  const int pmask = a.page - 1;
-  unsigned char* my_stages = stages + (size_t)grp * 2 * STAGE_BYTES;
-
-  // ---- per-lane parts of all addresses (loop invariant, a handful of registers).  A unit is moved
-  // in LOADS slots of 1 KB.  K slot sl: rows ROWS_PER_SLOT*sl + lane/CPR, chunk position p = lane%CPR
-  // holding chunk p ^ k_swz(row); the swizzle's bit 2 only depends on the slot.  V slot s2 (prefix):
-  // 8-key chunks kc = 2*half + (lane&1) of features dblk*32 + lane/2, half = s2 / V_DBLK.
-  constexpr int V_DBLK = K_SLOTS / 2;  // 32-feature blocks per half unit
+  // ---- per-lane and per-slot parts of the main loop's addresses (loop invariant).  A unit is moved
+  // in 1 KB slots.  K slot sl: rows ROWS_PER_SLOT*sl + lane/CPR, chunk position p = lane%CPR holding
+  // chunk p ^ k_swz(row); the swizzle's bit 2 only depends on the slot.  V slot s2: 8-key chunks
+  // kc = 2*half + (lane&1) of features dblk*32 + lane/2, half = s2 / V_DBLK, dblk = s2 % V_DBLK.
+  // The first LW waves of a group move the data: wave wt takes K slots and V slots wt + LW*j.
   const int ril = lane / CPR, pch = lane % CPR;
-  const int k_src_lo = ril * D + ((pch ^ (ril & 3)) * 8);        // element offset, swizzle bit 2 clear
-  const int k_src_hi = ril * D + ((pch ^ (ril & 3) ^ 4) * 8);    // ... set
-  const int v_src = (lane >> 1) * a.page + (lane & 1) * 8;       // element offset inside a (page, feature block)
+  const bool loader = wt < LW;
   const int v_dst0 = K_BYTES + (lane >> 1) * VROW + ((((lane & 1)) ^ ((lane >> 2) & 3)) * 16);      // half 0
   const int v_dst1 = K_BYTES + (lane >> 1) * VROW + (((2 + (lane & 1)) ^ ((lane >> 2) & 3)) * 16);  // half 1
+  const int v_lsrc = (lane >> 1) * a.page + (lane & 1) * 8;  // element offset inside a (page, feature block)
+  int k_lsrc[KJ], k_ldst[KJ], v_ldst[KJ];                    // per lane
+  int k_soff[KJ], v_soff[KJ];                                // scalar element offsets from the half's base
+  bool k_second[KJ], v_second[KJ];
+#pragma unroll
+  for (int j = 0; j < KJ; ++j) {
+    const int sl = (loader ? wt : 0) + LW * j, r0 = ROWS_PER_SLOT * sl;
+    k_second[j] = r0 >= 16;
+    k_soff[j] = (r0 & 15) * D;
+    k_lsrc[j] = ril * D + ((pch ^ (ril & 3) ^ (((r0 >> 3) & 1) << 2)) * 8);
+    k_ldst[j] = sl * 1024 + lane * 16;
+    const int half = sl / V_DBLK, dblk = sl % V_DBLK;
+    v_second[j] = half != 0;
+    v_soff[j] = dblk * 32 * a.page;
+    v_ldst[j] = dblk * (32 * VROW) + (half ? v_dst1 : v_dst0);
+  }
   // operand reads: K row of score tile 0 (tile 1 is 4 rows further), even / odd feature step; V row
   const int rr0 = block_key(lq, 0), k_sh = (lq >> 2) & 1, k_lo = lg ^ (lq & 3);
   const int k_rd_even = rr0 * (2 * D) + (((k_sh << 2) | k_lo) * 16);
   const int k_rd_odd = rr0 * (2 * D) + ((((k_sh ^ 1) << 2) | k_lo) * 16);
   const int v_rd = K_BYTES + lq * VROW + ((lg ^ ((lq >> 1) & 3)) * 16);
 
-  // Physical pages of the two 16-key halves of prefix unit u (scalar loads; equal for pages of 32 or
-  // 64 tokens).  A half past the end of the prefix gets the page of the last existing key.
-  auto fetch_pages = [&](int u, int& pg_a, int& pg_b) {
-    if (u < n_prefix_units) {
-      const int kb = k0 + 32 * u, last = k1 - 1;
-      pg_a = min(max(my_table[kb >> a.page_shift], 0), a.num_pages - 1);
-      pg_b = min(max(my_table[min(kb + 16, last & ~15) >> a.page_shift], 0), a.num_pages - 1);
-    }
-  };
-  // Load slots of unit u for this wave -> registers.  For units of the cached prefix the base address
-  // of a slot is scalar; a slot past the end of the prefix is pointed at the last existing keys (they
-  // are masked and their values zeroed later).
-  uintx4 stg[SLOTS];
-  auto load_unit = [&](int u, int pg_a, int pg_b) {
-    if (u < n_prefix_units) {
-      const int kb = k0 + 32 * u, last = k1 - 1;
+  // Main-loop unit u (a full block of the prefix) -> registers: scalar base per half, 16 bytes per lane.
+  uintx4 stg[2 * KJ];
+  auto load_main = [&](int u, int pg_a, int pg_b) {
+    const int kb = k0 + 32 * u;
+    const int o_a = kb & pmask, o_b = (kb + 16) & pmask;
+    const size_t g_a = (size_t)pg_a * page_stride, g_b = (size_t)pg_b * page_stride;
+    const uint16_t* ka = k_head + g_a + (size_t)o_a * D;
+    const uint16_t* kb2 = k_head + g_b + (size_t)o_b * D;
+    const uint16_t* va = v_head + g_a + o_a;
+    const uint16_t* vb = v_head + g_b + o_b;
 #pragma unroll
-      for (int j = 0; j < SLOTS; ++j) {
-        const int sl = wt + NW * j;
-        if (sl < K_SLOTS) {
-          const int key0 = min(kb + ROWS_PER_SLOT * sl, last & ~(ROWS_PER_SLOT - 1));
-          const int pg = key0 - kb >= 16 ? pg_b : pg_a;
-          const uint16_t* base = k_cache + (size_t)pg * page_stride + ((size_t)hk * a.page + (key0 & pmask)) * D;
-          const bool hi = ((ROWS_PER_SLOT * sl) >> 3) & 1;
-          stg[j] = ld16(base + (hi ? k_src_hi : k_src_lo));
-        } else if (sl < LOADS) {
-          const int s2 = sl - K_SLOTS, half = s2 / V_DBLK, dblk = s2 % V_DBLK;
-          const int key0 = min(kb + 16 * half, last & ~15);
-          const int pg = key0 - kb >= 16 ? pg_b : pg_a;
-          const uint16_t* base =
-              v_cache + (size_t)pg * page_stride + ((size_t)hk * D + dblk * 32) * a.page + (key0 & pmask);
-          stg[j] = ld16(base + v_src);
-        }
-      }
-    } else {
-      // new rows (rare): per-lane row clamp; V rows are token-major and are staged row-major
-      const int c0 = 32 * (u - n_prefix_units);
+    for (int j = 0; j < KJ; ++j) stg[j] = ld16((k_second[j] ? kb2 : ka) + k_soff[j] + k_lsrc[j]);
 #pragma unroll
-      for (int j = 0; j < SLOTS; ++j) {
-        const int sl = wt + NW * j;
-        if (sl < LOADS) {
-          const bool is_k = sl < K_SLOTS;
-          const int rr = ROWS_PER_SLOT * (is_k ? sl : sl - K_SLOTS) + ril;
-          const size_t row = ((size_t)b * R + min(c0 + rr, R - 1)) * a.Hkv + hk;
-          stg[j] = is_k ? ld16(k_new + row * D + ((pch ^ k_swz(rr)) * 8)) : ld16(v_new + row * D + pch * 8);
-        }
-      }
-    }
+    for (int j = 0; j < KJ; ++j) stg[KJ + j] = ld16((v_second[j] ? vb : va) + v_soff[j] + v_lsrc);
   };
-  // Registers -> LDS stage (layouts as the operand reads expect them).
-  auto store_unit = [&](int u, unsigned char* st) {
-    const bool is_new = u >= n_prefix_units;
+  auto store_main = [&](unsigned char* st) {
 #pragma unroll
-    for (int j = 0; j < SLOTS; ++j) {
-      const int sl = wt + NW * j;
-      if (sl < K_SLOTS) {
-        *reinterpret_cast<uintx4*>(st + sl * 1024 + lane * 16) = stg[j];
-      } else if (sl < LOADS) {
-        const int s2 = sl - K_SLOTS;
-        if (!is_new) {
-          const int half = s2 / V_DBLK, dblk = s2 % V_DBLK;
-          *reinterpret_cast<uintx4*>(st + dblk * (32 * VROW) + (half ? v_dst1 : v_dst0)) = stg[j];
-        } else {
-          const int rr = ROWS_PER_SLOT * s2 + ril;
-          *reinterpret_cast<uintx4*>(st + K_BYTES + rr * (2 * D) + ((pch ^ (2 * (rr & 3))) * 16)) = stg[j];
-        }
-      }
-    }
+    for (int j = 0; j < KJ; ++j) *reinterpret_cast<uintx4*>(st + k_ldst[j]) = stg[j];
+#pragma unroll
+    for (int j = 0; j < KJ; ++j) *reinterpret_cast<uintx4*>(st + v_ldst[j]) = stg[KJ + j];
   };
-
-  // ---- prologue: first unit of this group into stage 0; page ids are fetched one unit ahead of
-  // the loads that need them
-  int pg_a = 0, pg_b = 0, pgn_a = 0, pgn_b = 0;
-  fetch_pages(grp, pg_a, pg_b);
-  fetch_pages(grp + n_groups, pgn_a, pgn_b);
-  if (grp < n_units) {
-    load_unit(grp, pg_a, pg_b);
-    store_unit(grp, my_stages);
-  }
-  __syncthreads();
 
 #ifdef SS_MSA_TIMING
-  long long tacc[8] = {0, 0, 0, 0, 0, 0, 0, 0}, t_last = clock64();
+  long long tacc[8] = {0, 0, 0, 0, 0, 0, 0, 0}, t_last = 0;
 #endif
-  for (int it = 0; it < n_iter; ++it) {
-    const int u = grp + it * n_groups;
-    const int u_next = u + n_groups;
-    unsigned char* st = my_stages + (it & 1) * STAGE_BYTES;
-    if (u_next < n_units) load_unit(u_next, pgn_a, pgn_b);  // in flight while this unit is computed
-    fetch_pages(u_next + n_groups, pgn_a, pgn_b);           // page ids of the unit after that
-    SS_T(0);
-
-    if (u < n_units) {
-      const bool is_new = u >= n_prefix_units;
-      // ---- scores S^T = K Q^T
-      floatx4 S[2];
+  // One unit out of an LDS stage: scores, softmax update, O += P V.  `full` (a compile-time flag) is
+  // the unmasked main-loop flavour; otherwise the unit may be ragged or consist of the step's own rows
+  // and `vis` tells which of those this lane's query row may see.
+  auto compute = [&](auto full, int u, const unsigned char* st, const RowVis& vis) {
+    constexpr bool FULL = decltype(full)::value;
+    const bool is_new = !FULL && u >= n_prefix_units;
+    // The masked flavours recompute their lane-dependent offsets on every call (the lane id is
+    // laundered) instead of keeping them in registers across the loops.
+    int ln = lane;
+    if (!FULL) asm volatile("" : "+v"(ln));
+    const int mq = ln & 15, mg = ln >> 4;
+    // ---- scores S^T = K Q^T
+    floatx4 S[2];
 #pragma unroll
-      for (int X = 0; X < 2; ++X) {
-        floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int X = 0; X < 2; ++X) {
+      floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          const uintx4 kop = *reinterpret_cast<const uintx4*>(st + ((ks & 1) ? k_rd_odd : k_rd_even) +
-                                                              (ks >> 1) * 128 + X * (8 * D));
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kop), Qr[ks], acc, 0, 0, 0);
-        }
-        S[X] = acc;
+      for (int ks = 0; ks < KS; ++ks) {
+        const uintx4 kop = *reinterpret_cast<const uintx4*>(st + ((ks & 1) ? k_rd_odd : k_rd_even) +
+                                                            (ks >> 1) * 128 + X * (8 * D));
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kop), Qr[ks], acc, 0, 0, 0);
       }
-      SS_KEEP(S[0]);
-      SS_KEEP(S[1]);
-      SS_T(1);
-      // ---- mask (only the ragged prefix block and the new rows)
-      if (u >= n_full) {
-        const int c0 = 32 * (u - n_prefix_units);
-#pragma unroll
-        for (int X = 0; X < 2; ++X)
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const int off = 8 * lg + 4 * X + i;
-            const bool see_tail = off < tail;
-            const bool see_new = (c0 + off < R) & row_sees(vis, c0 + off, T);
-            const float sv = S[X][i];
-            S[X][i] = (is_new ? see_new : see_tail) ? sv : -INFINITY;
-          }
-      }
-      // ---- online softmax (log2 domain, lazy rescale), probabilities to bf16
-      float mx = fmaxf(fmaxf(fmaxf(S[0][0], S[0][1]), fmaxf(S[0][2], S[0][3])),
-                       fmaxf(fmaxf(S[1][0], S[1][1]), fmaxf(S[1][2], S[1][3])));
-      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      if (__any((mx - m_run) * c > kLazyLog2)) {
-        const float m_new = fmaxf(m_run, mx);
-        const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
-        l_run *= alpha;
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) O[dt] *= alpha;
-        m_run = m_new;
-      }
-      const float mc = m_run * c;
-      bf16x8 P;
-      float ps = 0.f;
+      S[X] = acc;
+    }
+    SS_KEEP(S[0]);
+    SS_KEEP(S[1]);
+    SS_T(1);
+    // ---- mask (only the ragged prefix block and the new rows)
+    if (!FULL && u >= n_full) {
+      const int c0 = 32 * (u - n_prefix_units);
 #pragma unroll
       for (int X = 0; X < 2; ++X)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const float pr = __builtin_amdgcn_exp2f(fmaf(S[X][i], c, -mc));
-          ps += pr;
-          P[4 * X + i] = (__bf16)pr;
+          const int off = 8 * mg + 4 * X + i;
+          const bool see_tail = off < tail;
+          const bool see_new = (c0 + off < R) & row_sees(vis, c0 + off, T);
+          const float sv = S[X][i];
+          S[X][i] = (is_new ? see_new : see_tail) ? sv : -INFINITY;
         }
-      l_run += ps;
-      SS_KEEP(P);
-      SS_T(2);
-      // ---- O^T += V^T P^T
-      if (u < n_full) {
+    }
+    // ---- online softmax (log2 domain, lazy rescale), probabilities to bf16
+    float mx = fmaxf(fmaxf(fmaxf(S[0][0], S[0][1]), fmaxf(S[0][2], S[0][3])),
+                     fmaxf(fmaxf(S[1][0], S[1][1]), fmaxf(S[1][2], S[1][3])));
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    if (__any((mx - m_run) * c > kLazyLog2)) {
+      const float m_new = fmaxf(m_run, mx);
+      const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
+      l_run *= alpha;
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-          const uintx4 vv = *reinterpret_cast<const uintx4*>(st + v_rd + dt * (16 * VROW));
-          O[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vv), P, O[dt], 0, 0, 0);
+      for (int dt = 0; dt < DT; ++dt) O[dt] *= alpha;
+      m_run = m_new;
+    }
+    const float mc = m_run * c;
+    bf16x8 P;
+    float ps = 0.f;
+#pragma unroll
+    for (int X = 0; X < 2; ++X)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float pr = __builtin_amdgcn_exp2f(fmaf(S[X][i], c, -mc));
+        ps += pr;
+        P[4 * X + i] = (__bf16)pr;
+      }
+    l_run += ps;
+    SS_KEEP(P);
+    SS_T(2);
+    // ---- O^T += V^T P^T
+    if (FULL || u < n_full) {
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) {
+        const uintx4 vv = *reinterpret_cast<const uintx4*>(st + v_rd + dt * (16 * VROW));
+        O[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vv), P, O[dt], 0, 0, 0);
+      }
+    } else if (!is_new) {
+      const int nv = min(max(tail - 8 * mg, 0), 8);  // how many of this lane's 8 tokens exist
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) {
+        uintx4 vv = *reinterpret_cast<const uintx4*>(st + v_rd + dt * (16 * VROW));
+#pragma unroll
+        for (int e = 0; e < 4; ++e) vv[e] &= nv >= 2 * e + 2 ? 0xffffffffu : (nv == 2 * e + 1 ? 0x0000ffffu : 0u);
+        O[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vv), P, O[dt], 0, 0, 0);
+      }
+    } else {
+      const unsigned char* vb = st + K_BYTES;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) {
+        uintx2 half[2];
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {
+          const int row = 8 * mg + 4 * hh + (mq >> 2);  // keys 8*lg + 4*hh .. +3 reach this lane
+          const int ch = 2 * dt + ((mq & 3) >> 1);      // 16-byte chunk with features 16*dt + 4*(lq&3)..
+          half[hh] = lds_read_tr16(vb + row * (2 * D) + ((ch ^ (2 * (row & 3))) * 16) + (mq & 1) * 8);
         }
-      } else if (!is_new) {
-        const int nv = min(max(tail - 8 * lg, 0), 8);  // how many of this lane's 8 tokens exist
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-          uintx4 vv = *reinterpret_cast<const uintx4*>(st + v_rd + dt * (16 * VROW));
-#pragma unroll
-          for (int e = 0; e < 4; ++e) vv[e] &= nv >= 2 * e + 2 ? 0xffffffffu : (nv == 2 * e + 1 ? 0x0000ffffu : 0u);
-          O[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vv), P, O[dt], 0, 0, 0);
-        }
-      } else {
-        const unsigned char* vb = st + K_BYTES;
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-          uintx2 half[2];
-#pragma unroll
-          for (int hh = 0; hh < 2; ++hh) {
-            const int row = 8 * lg + 4 * hh + (lq >> 2);  // keys 8*lg + 4*hh .. +3 reach this lane
-            const int ch = 2 * dt + ((lq & 3) >> 1);      // 16-byte chunk with features 16*dt + 4*(lq&3)..
-            half[hh] = lds_read_tr16(vb + row * (2 * D) + ((ch ^ (2 * (row & 3))) * 16) + (lq & 1) * 8);
-          }
-          const uintx4 vv = uintx4{half[0][0], half[0][1], half[1][0], half[1][1]};
-          O[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vv), P, O[dt], 0, 0, 0);
-        }
+        const uintx4 vv = uintx4{half[0][0], half[0][1], half[1][0], half[1][1]};
+        O[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vv), P, O[dt], 0, 0, 0);
       }
     }
+  };
 
+  // ---- main loop over full blocks of the prefix: while a group computes on one LDS stage, its waves
+  // hold the next unit in registers (loads issued at the top), write it to the other stage after the
+  // compute, and one barrier per unit publishes it.
+  const RowVis no_vis = RowVis{0, 0, 0};
+  if (n_main > 0 && loader) {
+    load_main(grp, __builtin_amdgcn_readlane(tab_a, 0), __builtin_amdgcn_readlane(tab_b, 0));
+    store_main(my_stages);
+  }
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): nothing from the prologue (Q, page ids) is pending inside the loop
+  __syncthreads();
+#ifdef SS_MSA_TIMING
+  t_last = clock64();
+  const long long t_loop0 = t_last;
+#endif
+  for (int it = 0; it + 1 < n_main; ++it) {
+    const int u = grp + it * n_groups;
+    const int jn = it + 1;
+    if ((jn & 63) == 0) refill_pages(jn);
+    if (loader)
+      load_main(u + n_groups, __builtin_amdgcn_readlane(tab_a, jn & 63), __builtin_amdgcn_readlane(tab_b, jn & 63));
+    SS_T(0);
+    compute(std::true_type{}, u, my_stages + (it & 1) * STAGE_BYTES, no_vis);
     SS_KEEP(O[0]);
     SS_KEEP(O[DT - 1]);
     SS_T(3);
-    if (u_next < n_units) store_unit(u_next, my_stages + ((it + 1) & 1) * STAGE_BYTES);
+    if (loader) store_main(my_stages + (jn & 1) * STAGE_BYTES);
     SS_T(4);
     __syncthreads();  // the next stage is complete, this one may be overwritten after the next barrier
     SS_T(5);
   }
+  if (n_main > 0) {
+    compute(std::true_type{}, grp + (n_main - 1) * n_groups, my_stages + ((n_main - 1) & 1) * STAGE_BYTES, no_vis);
+    __syncthreads();  // the stages are free for what follows
+  }
 #ifdef SS_MSA_TIMING
-  if (lane == 0 && blockIdx.x < 64) {
-    long long* dbg = (long long*)a.part_lse + 1000000 + (blockIdx.x * 16 + w) * 8;
+  if (lane == 0 && blockIdx.x < 1024) {
+    long long* dbg = (long long*)a.part_lse + 1000000 + (blockIdx.x * 16 + w) * 16;
     for (int i = 0; i < 6; ++i) dbg[i] = tacc[i];
-    dbg[6] = n_iter;
+    dbg[6] = n_main;
+    dbg[7] = t_loop0 - t_entry;
+    dbg[8] = t_entry;
+    dbg[9] = clock64();
+    dbg[10] = __builtin_amdgcn_s_getreg(4 | (31 << 11));
+    dbg[11] = __builtin_amdgcn_s_getreg(20 | (31 << 11));
   }
 #endif
 
+  // ---- the remaining units (leftover full blocks, the ragged block, the step's own rows), pipelined
+  // the same way.  Addresses are per lane here, clamped to existing keys / rows; what is read in
+  // excess is masked.  The lane id is laundered wherever addresses are formed, so that none of this
+  // arithmetic is kept in registers across the loops.
+  const int u_odd0 = n_main * n_groups;
+  const int n_odd_iter = (n_units - u_odd0 + n_groups - 1) / n_groups;
+  if (n_odd_iter > 0) {
+    const RowVis vis = is_last ? make_row_vis(q_r, T, a.gamma, anc, (a.flags & SS_STREAM_EXCLUDE_SELF) != 0) : no_vis;
+    auto load_odd = [&](int u) {
+      int lane2 = lane;
+      asm volatile("" : "+v"(lane2));
+      const int ril2 = lane2 / CPR, pch2 = lane2 % CPR;
+      const bool is_new = u >= n_prefix_units;
+      const int kb = k0 + 32 * u, last = k1 - 1;  // prefix units
+      const int c0 = 32 * (u - n_prefix_units);   // units of new rows
+#pragma unroll
+      for (int j = 0; j < KJ; ++j) {
+        const int sl = wt + LW * j;
+        const int rr = ROWS_PER_SLOT * sl + ril2;
+        const uint16_t *ksrc, *vsrc;
+        if (!is_new) {
+          const int key = min(kb + rr, last);
+          const int pg = min(max(my_table[key >> a.page_shift], 0), a.num_pages - 1);
+          ksrc = k_head + (size_t)pg * page_stride + (size_t)(key & pmask) * D;
+          const int half = sl / V_DBLK, dblk = sl % V_DBLK;
+          const int vkey = min(kb + 16 * half + (lane2 & 1) * 8, last & ~7);
+          const int vpg = min(max(my_table[vkey >> a.page_shift], 0), a.num_pages - 1);
+          vsrc = v_head + (size_t)vpg * page_stride + (size_t)(dblk * 32 + (lane2 >> 1)) * a.page + (vkey & pmask);
+        } else {
+          const size_t row = ((size_t)b * R + min(c0 + rr, R - 1)) * a.Hkv + hk;
+          ksrc = k_new + row * D;
+          vsrc = v_new + row * D + pch2 * 8;
+        }
+        stg[j] = ld16(ksrc + ((pch2 ^ k_swz(rr)) * 8));
+        stg[KJ + j] = ld16(vsrc);
+      }
+    };
+    auto store_odd = [&](int u, unsigned char* st) {
+      int lane2 = lane;
+      asm volatile("" : "+v"(lane2));
+      const int ril2 = lane2 / CPR, pch2 = lane2 % CPR;
+      const bool is_new = u >= n_prefix_units;
+#pragma unroll
+      for (int j = 0; j < KJ; ++j) {
+        const int sl = wt + LW * j;
+        *reinterpret_cast<uintx4*>(st + sl * 1024 + lane2 * 16) = stg[j];
+        if (!is_new) {
+          const int half = sl / V_DBLK, dblk = sl % V_DBLK;
+          const int chunk = (2 * half + (lane2 & 1)) ^ ((lane2 >> 2) & 3);
+          *reinterpret_cast<uintx4*>(st + K_BYTES + (dblk * 32 + (lane2 >> 1)) * VROW + chunk * 16) = stg[KJ + j];
+        } else {
+          const int rr = ROWS_PER_SLOT * sl + ril2;
+          *reinterpret_cast<uintx4*>(st + K_BYTES + rr * (2 * D) + ((pch2 ^ (2 * (rr & 3))) * 16)) = stg[KJ + j];
+        }
+      }
+    };
+    if (loader && u_odd0 + grp < n_units) {
+      load_odd(u_odd0 + grp);
+      store_odd(u_odd0 + grp, my_stages);
+    }
+    __syncthreads();
+    for (int jo = 0; jo < n_odd_iter; ++jo) {
+      const int u = u_odd0 + jo * n_groups + grp, un = u + n_groups;
+      if (loader && un < n_units) load_odd(un);
+      if (u < n_units) compute(std::false_type{}, u, my_stages + (jo & 1) * STAGE_BYTES, vis);
+      if (loader && un < n_units) store_odd(un, my_stages + ((jo + 1) & 1) * STAGE_BYTES);
+      __syncthreads();
+    }
+  }
+
+#ifdef SS_MSA_TIMING
+  const long long t_odd = clock64();
+#endif
   // ---- merge the groups.  Every wave reduces its sum over the four lane groups; groups > 0 leave
   // (max, sum, O) in LDS; group 0 brings everything to a common maximum, adds and stores.
   l_run += __shfl_xor(l_run, 16, 64);
@@ -441,6 +533,13 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
     for (int dt = 0; dt < DT; ++dt) *reinterpret_cast<floatx4*>(op + 16 * dt) = O[dt] * inv;
     if (lg == 0) a.part_lse[pr] = mm * c + __log2f(l_run);
   }
+#ifdef SS_MSA_TIMING
+  if (lane == 0 && blockIdx.x < 1024) {
+    long long* dbg = (long long*)a.part_lse + 1000000 + (blockIdx.x * 16 + w) * 16;
+    dbg[12] = clock64();
+    dbg[13] = t_odd;
+  }
+#endif
 }
 
 // Folded query rows one workgroup takes (a multiple of 16, at most 80).
@@ -458,22 +557,24 @@ int msa_bf16_rows_per_chunk(int F) {
   return best;
 }
 
-// Wave groups per workgroup for NW query tiles: as many as fit kMaxWaves waves, at most kMaxGroups.
-static int groups_for(int nw) {
+// Wave groups per workgroup for NW query tiles: what the plan asks for (or the SS_MSA_GROUPS tuning
+// override), as far as kMaxWaves waves allow.
+static int groups_for(int nw, int wanted) {
   static const int forced = []() {
-    const char* e = getenv("SS_MSA_GROUPS");  // tuning aid
+    const char* e = getenv("SS_MSA_GROUPS");
     const int v = e ? atoi(e) : 0;
     return (v >= 1 && v <= kMaxGroups) ? v : 0;
   }();
-  int g = kMaxWaves / nw;
-  if (g > kMaxGroups) g = kMaxGroups;
-  if (forced && forced <= g) g = forced;
+  int cap = kMaxWaves / nw;
+  if (cap > kMaxGroups) cap = kMaxGroups;
+  int g = forced ? forced : wanted;
+  if (g > cap) g = cap;
   return g < 1 ? 1 : g;
 }
 
 template <int D, int NW>
 static int launch_dn(const MsaArgs& a, hipStream_t stream) {
-  const int n_groups = groups_for(NW);
+  const int n_groups = groups_for(NW, a.groups);
   const int G = a.B * a.Hkv * a.n_splits;
   const long wgs = (long)ceil_div(G, 8) * 8 * a.n_qc;
   SS_REQUIRE(wgs <= 0x7fffffffL, SS_ERR_UNSUPPORTED, "ss_msa_attention: grid too large");
