@@ -16,14 +16,29 @@ struct LmArgs {
   const void* W;       // [V,d]
   int N, d, V, K;
   int n_tiles;         // vocabulary tiles
-  float* cand_val;     // [N, n_tiles, K]
-  int32_t* cand_idx;   // [N, n_tiles, K]
+  uint64_t* cand_key;  // [N, n_tiles, K] candidates as ordered keys
   int32_t* idx;        // [N,K]
   float* val;          // [N,K]
 };
 
 SS_DEV bool cand_better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
 SS_DEV bool cand_after(float v, int i, float pv, int pi) { return v < pv || (v == pv && i > pi); }
+
+// A candidate as one 64-bit key whose unsigned order is the candidate order: the logit mapped to an
+// order-preserving unsigned pattern in the high word, the complement of the token id in the low word
+// (equal logits -> lower id first).  Key 0 ranks below every real candidate.
+SS_DEV uint64_t cand_key(float v, int id) {
+  v += 0.f;  // -0 -> +0, so that the two zeros tie
+  const uint32_t u = __float_as_uint(v);
+  const uint32_t o = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+  return ((uint64_t)o << 32) | (uint32_t)(0xffffffffu - (uint32_t)id);
+}
+SS_DEV float key_value(uint64_t k) {
+  const uint32_t o = (uint32_t)(k >> 32);
+  return k == 0 ? -INFINITY : __uint_as_float((o & 0x80000000u) ? (o ^ 0x80000000u) : ~o);
+}
+SS_DEV int key_id(uint64_t k) { return k == 0 ? INT_MAX : (int)(0xffffffffu - (uint32_t)k); }
+
 
 // ------------------------------------------------------------------ fp32 kernel (small problems)
 //
@@ -88,8 +103,7 @@ __global__ __launch_bounds__(256) void lm_head_f32_kernel(LmArgs a) {
       }
       if (lane == 0) {
         const size_t o = ((size_t)row * a.n_tiles + blockIdx.x) * a.K + k;
-        a.cand_val[o] = bv;
-        a.cand_idx[o] = bi;
+        a.cand_key[o] = bi == INT_MAX ? 0 : cand_key(bv, bi);
       }
       pv = bv;
       pi = bi;
@@ -99,191 +113,318 @@ __global__ __launch_bounds__(256) void lm_head_f32_kernel(LmArgs a) {
 
 // ------------------------------------------------------------------ bf16 MFMA kernel
 //
-// Workgroup = 4 waves; tile = (64*MT rows) x 128 vocabulary columns; wave w owns
-// rows [16*MT*w, 16*MT*(w+1)) and all 128 columns, so the W tile is shared by the
-// waves (through LDS, 16-byte chunks XOR-swizzled against bank conflicts) while
-// each wave streams its own rows of `hidden` straight into MFMA A operands.
-// With N <= 320 a workgroup covers all rows: W is read from HBM exactly once.
-// v_mfma_f32_16x16x32_bf16: A = 16 rows x 32 features, B = 32 features x 16
-// columns; inside a 64-feature stage, step s and lane group g use the 8-feature
-// chunk 4*s + g for both operands.
-template <int MT>
-__global__ __launch_bounds__(256, 1) void lm_head_bf16_kernel(LmArgs a) {
-  constexpr int BN = 128, BK = 64, NT = BN / 16, NS = 3;
-  __shared__ __attribute__((aligned(16))) uint16_t Ws[NS][BN * BK];
-  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, lq = lane & 15, lg = lane >> 4;
-  const int v0 = blockIdx.x * BN;
-  const int row0 = blockIdx.y * (64 * MT) + w * (16 * MT);
-  const uint16_t* hidden = (const uint16_t*)a.hidden;
-  const uint16_t* W = (const uint16_t*)a.W;
-  const int d = a.d, n_k = d / BK;
+// The product is computed transposed, logits^T = W . hidden^T, with
+// v_mfma_f32_32x32x16_bf16 (A = 32 token ids x 16 features, B = 16 features x 32
+// rows).  In the 32x32 result a lane holds 16 token ids of ONE row, so the top-K
+// over the vocabulary is mostly a per-lane affair: no logit is ever exchanged
+// between lanes, only K-entry candidate lists.
+//
+// Workgroup = 4 waves; tile = 128 token ids x 64*RT rows; wave w owns ids
+// [32*w, 32*w+32) and all rows: 2*RT accumulator tiles (160 accumulation registers
+// for RT = 5).  With N <= 320 one workgroup column covers all rows, so W is read
+// from HBM exactly once, and the 250 workgroups of a 32000-token vocabulary fill
+// the chip once.  Each workgroup has to pull all of `hidden` through its L1, which
+// makes L2 -> compute-unit traffic (hidden once per workgroup, W once) the
+// resource to watch: requests are full 128-byte lines throughout.
+//
+// Feeding the matrix cores.  Features go in blocks of 64 (one line per row).
+// W rows belong to one wave only, so they are loaded straight into operand
+// registers: lane (m, h) takes bytes [32*c + 16*h, +16) of row m for step c, i.e.
+// step c covers features 64*J + 16*c .. +15 and a load instruction touches 32
+// lines with 32 contiguous bytes each.  Four blocks are in flight per wave (the
+// ring is filled three blocks ahead of use): 12 KB per wave against the HBM
+// latency, with one wave per SIMD.  `hidden` is shared by the waves and goes
+// through LDS: three buffers of 64*RT rows x 128 bytes, 16-byte chunks
+// XOR-swizzled ((row >> 1) & 7) so that the operand reads (32 rows x one chunk,
+// 16 lanes per LDS cycle over 64 banks) are conflict free; a block is fetched
+// (from L2) into registers three blocks ahead, written to LDS one block later,
+// and one barrier per block publishes it.  Loads complete in order, so within a
+// step the `hidden` loads are issued before the W loads: waiting for them never
+// waits for younger W blocks.
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 
-  // W tile loader: 4 passes, thread -> (row = tid/8 + 32*pass, 16-byte chunk tid%8)
-  const uint16_t* wsrc[4];
-  int wdst[4];
+template <int KT>
+struct TopList {  // the KT best keys seen so far, best first
+  uint64_t k[KT];
+  SS_DEV void clear() {
 #pragma unroll
-  for (int p = 0; p < 4; ++p) {
-    const int vr = (tid >> 3) + 32 * p, ch = tid & 7;
-    wsrc[p] = W + (size_t)min(v0 + vr, a.V - 1) * d + ch * 8;
-    wdst[p] = vr * BK + ((ch ^ (vr & 7)) * 8);
+    for (int j = 0; j < KT; ++j) k[j] = 0;
   }
-  // A rows of this wave (clamped; rows >= N are computed and dropped)
-  const uint16_t* asrc[MT];
+  SS_DEV void insert(uint64_t c) {
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt) asrc[mt] = hidden + (size_t)min(row0 + 16 * mt + lq, a.N - 1) * d + lg * 8;
+    for (int j = 0; j < KT; ++j) {
+      const uint64_t hi = k[j] > c ? k[j] : c, lo = k[j] > c ? c : k[j];
+      k[j] = hi;
+      c = lo;
+    }
+  }
+};
 
-  typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 v8bf;
-  floatx4 acc[MT][NT];
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
+template <int RT, int KT>
+__global__ __launch_bounds__(256, 1) void lm_head_bf16_kernel(LmArgs a) {
+  constexpr int ROWS = 64 * RT;  // rows of `hidden` per workgroup
+  constexpr int NRT = 2 * RT;    // 32-row accumulator tiles per wave
+  constexpr int HB = ROWS * 128; // bytes of one block of `hidden` in LDS
+  constexpr int HL = 2 * RT;     // 16-byte chunks of it per thread
+  extern __shared__ __attribute__((aligned(16))) unsigned char hbuf[];  // [3][HB], reused by the epilogue
+#ifdef SS_LM_TIMING
+  const long long t_entry = clock64();
+#endif
+  const int tid = threadIdx.x, lane = tid & 63, ln = lane & 31, lh = lane >> 5;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int v0 = blockIdx.x * 128 + 32 * w;  // first token id of this wave
+  const int row0 = blockIdx.y * ROWS;        // first row of this workgroup
+  const int d = a.d, n_k = d / 64;
 
-  uintx4 wg[2][4];     // W tiles in flight: loaded two stages ahead of their use
-  uintx4 an[MT][2];    // next stage's A operands
-  uintx4 ac[MT][2];    // current stage's A operands
-
-  auto gload_w = [&](int kt, uintx4 (&dst)[4]) {
+  // Sources as 32-bit byte offsets from a scalar base that moves with the feature block, so that a
+  // load needs no vector arithmetic (the host checks that the matrices are below 2 GiB).  W operand:
+  // row v0 + ln, bytes 16*lh.. of each 32-byte piece; ids past the vocabulary are clamped and their
+  // logits dropped later.  hidden staging: thread -> rows tid/8 + 32*i, chunk tid%8; rows past N are
+  // clamped and dropped later.
+  const uint32_t w_voff = ((uint32_t)min(v0 + ln, a.V - 1) * (uint32_t)d + 8 * lh) * 2;
+  uint32_t h_voff[HL];
 #pragma unroll
-    for (int p = 0; p < 4; ++p) dst[p] = *reinterpret_cast<const uintx4*>(wsrc[p] + (size_t)kt * BK);
+  for (int i = 0; i < HL; ++i) h_voff[i] = ((uint32_t)min(row0 + (tid >> 3) + 32 * i, a.N - 1) * (uint32_t)d + (tid & 7) * 8) * 2;
+  const int hdst = (tid >> 3) * 128 + (((tid & 7) ^ ((tid >> 4) & 7)) * 16);
+  // hidden operand reads: row 32*rt + ln, logical chunk 2*c + lh
+  int hrd[4];
+#pragma unroll
+  for (int c = 0; c < 4; ++c) hrd[c] = ln * 128 + (((2 * c + lh) ^ ((ln >> 1) & 7)) * 16);
+
+  floatx16 acc[NRT];
+#pragma unroll
+  for (int rt = 0; rt < NRT; ++rt)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[rt][e] = 0.f;
+
+  uintx4 wq[4][4];   // ring of W blocks in flight: [block % 4][step]
+  uintx4 hs[2][HL];  // two blocks of `hidden` on their way to LDS
+
+  auto load_w = [&](int J, uintx4 (&dst)[4]) {
+    const unsigned char* base = (const unsigned char*)a.W + (size_t)J * 128;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) dst[c] = *reinterpret_cast<const uintx4*>(base + w_voff + 32 * c);
   };
-  auto store_w = [&](int stage, const uintx4 (&src)[4]) {
+  auto load_h = [&](int J, uintx4 (&dst)[HL]) {
+    const unsigned char* base = (const unsigned char*)a.hidden + (size_t)J * 128;
 #pragma unroll
-    for (int p = 0; p < 4; ++p) *reinterpret_cast<uintx4*>(&Ws[stage][wdst[p]]) = src[p];
+    for (int i = 0; i < HL; ++i) dst[i] = *reinterpret_cast<const uintx4*>(base + h_voff[i]);
   };
-  auto gload_a = [&](int kt, uintx4 (&dst)[MT][2]) {
+  auto store_h = [&](int buf, const uintx4 (&src)[HL]) {
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-      for (int s2 = 0; s2 < 2; ++s2)
-        dst[mt][s2] = *reinterpret_cast<const uintx4*>(asrc[mt] + (size_t)kt * BK + 32 * s2);
+    for (int i = 0; i < HL; ++i) *reinterpret_cast<uintx4*>(hbuf + buf * HB + hdst + i * (32 * 128)) = src[i];
   };
-
-  // prologue: stage 0 in LDS, stage 1 in registers
-  gload_w(0, wg[0]);
-  if (n_k > 1) gload_w(1, wg[1]);
-  gload_a(0, ac);
-  store_w(0, wg[0]);
+  // prologue: hidden blocks 0 and 1 in LDS, block 2 and W blocks 0..2 on their way
+  load_h(0, hs[0]);
+  load_h(min(1, n_k - 1), hs[1]);
+  store_h(0, hs[0]);
+  store_h(1, hs[1]);
+  load_h(min(2, n_k - 1), hs[1]);
+  load_w(0, wq[0]);
+  load_w(min(1, n_k - 1), wq[1]);
+  load_w(min(2, n_k - 1), wq[2]);
   __syncthreads();
 
-  for (int kt = 0; kt < n_k; ++kt) {
-    const int stage = kt % NS;
-    // wg[kt&1] is free (its tile went to LDS at the end of the last iteration): start W(kt+2).
-    // W(kt+1), in the other half, is stored after this stage's MFMAs, two iterations after its load.
-    if (kt + 2 < n_k) {
-      if (kt & 1) gload_w(kt + 2, wg[1]);
-      else gload_w(kt + 2, wg[0]);
-    }
-    if (kt + 1 < n_k) gload_a(kt + 1, an);
+  // Block J: W from ring slot J % 4, hidden from LDS buffer J % 3.  Top of the step: start hidden
+  // block J+3 (register set J % 2) and W block J+3 (the slot block J-1 left); bottom: hidden block
+  // J+2, started a step earlier in the other register set, goes to the buffer block J-1 was read from
+  // (every wave passed the previous barrier since).  Past the end the last block is fetched again
+  // instead, which keeps the steps free of conditions (a condition around the MFMAs would cost a
+  // register copy per accumulator).  The scheduling fences keep the loads at the top of the step.
+  int buf = 0;
+#ifdef SS_LM_TIMING
+  long long tacc[4] = {0, 0, 0, 0}, t_last = clock64();
+#define SS_LT(i) { __builtin_amdgcn_sched_barrier(0); const long long t_now_ = clock64(); tacc[i] += t_now_ - t_last; t_last = t_now_; __builtin_amdgcn_sched_barrier(0); }
+#else
+#define SS_LT(i)
+#endif
+  // A step is four MFMA rounds (16 features each, 2*RT MFMAs).  The L1 takes a load instruction of a
+  // wave only every ~18 cycles and the four waves share it, so the step's global loads and LDS writes
+  // are dealt to the rounds and, inside a round, placed between the MFMAs (scheduling groups) instead
+  // of stalling the wave in a burst.  The operand reads of round c+1 are issued in round c.
+  auto step = [&](int J, uintx4 (&w_now)[4], uintx4 (&w_next)[4], uintx4 (&h_new)[HL], uintx4 (&h_old)[HL]) {
+    const unsigned char* hb = hbuf + buf * HB;
+    unsigned char* hst = hbuf + (buf == 0 ? 2 : buf - 1) * HB + hdst;  // buffer (J + 2) % 3
+    const int Jn = min(J + 3, n_k - 1);
+    const unsigned char* h_base = (const unsigned char*)a.hidden + (size_t)Jn * 128;
+    const unsigned char* w_base = (const unsigned char*)a.W + (size_t)Jn * 128;
+    bf16x8 hop[2][NRT];
 #pragma unroll
-    for (int s2 = 0; s2 < 2; ++s2) {
-      v8bf bop[NT];
+    for (int rt = 0; rt < NRT; ++rt)
+      hop[0][rt] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(hb + hrd[0] + rt * (32 * 128)));
+    constexpr int NLD = HL + 4;  // global loads of the step: hidden first, then W
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt)
-        bop[nt] = __builtin_bit_cast(
-            v8bf, *reinterpret_cast<const uintx4*>(&Ws[stage][(16 * nt + lq) * BK + (((4 * s2 + lg) ^ (lq & 7)) * 8)]));
+    for (int c = 0; c < 4; ++c) {
+      if (c < 3) {
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        const v8bf aop = __builtin_bit_cast(v8bf, ac[mt][s2]);
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-          acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop, bop[nt], acc[mt][nt], 0, 0, 0);
+        for (int rt = 0; rt < NRT; ++rt)
+          hop[(c + 1) & 1][rt] =
+              __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(hb + hrd[c + 1] + rt * (32 * 128)));
       }
-    }
-    if (kt + 1 < n_k) {
-      if (kt & 1) store_w((kt + 1) % NS, wg[0]);
-      else store_w((kt + 1) % NS, wg[1]);
-    }
+      int n_ld = 0, n_st = 0;
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      ac[mt][0] = an[mt][0];
-      ac[mt][1] = an[mt][1];
+      for (int l = (c * NLD) / 4; l < ((c + 1) * NLD) / 4; ++l, ++n_ld) {
+        if (l < HL) h_new[l] = *reinterpret_cast<const uintx4*>(h_base + h_voff[l]);
+        else w_next[l - HL] = *reinterpret_cast<const uintx4*>(w_base + w_voff + 32 * (l - HL));
+      }
+#pragma unroll
+      for (int i = (c * HL) / 4; i < ((c + 1) * HL) / 4; ++i, ++n_st)
+        *reinterpret_cast<uintx4*>(hst + i * (32 * 128)) = h_old[i];
+      const bf16x8 wop = __builtin_bit_cast(bf16x8, w_now[c]);
+#pragma unroll
+      for (int rt = 0; rt < NRT; ++rt)
+        acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wop, hop[c & 1][rt], acc[rt], 0, 0, 0);
+#pragma unroll
+      for (int i = 0; i < NRT; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                 // MFMA
+        if (i < n_ld) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // global load
+        if (i < n_st) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);  // LDS write
+      }
+      __builtin_amdgcn_sched_barrier(0);
     }
+    buf = buf == 2 ? 0 : buf + 1;
+    SS_LT(1);
     __syncthreads();
+    SS_LT(3);
+  };
+  int J = 0;
+  for (; J + 4 <= n_k; J += 4) {
+    step(J, wq[0], wq[3], hs[0], hs[1]);
+    step(J + 1, wq[1], wq[0], hs[1], hs[0]);
+    step(J + 2, wq[2], wq[1], hs[0], hs[1]);
+    step(J + 3, wq[3], wq[2], hs[1], hs[0]);
   }
+  if (J < n_k) step(J, wq[0], wq[3], hs[0], hs[1]);
+  if (J + 1 < n_k) step(J + 1, wq[1], wq[0], hs[1], hs[0]);
+  if (J + 2 < n_k) step(J + 2, wq[2], wq[1], hs[0], hs[1]);
 
-  // epilogue: acc[mt][nt][i] is the logit of row row0+16*mt+4*lg+i, column v0+16*nt+lq.
-  // K rounds per row: lane-local best that comes after the previous winner, then a
-  // butterfly over the 16 lanes that share the row.
+#ifdef SS_LM_TIMING
+  const long long t_ep0 = clock64();
+#endif
+  // ---- epilogue.  acc[rt][e] on lane (ln, lh) is the logit of row row0 + 32*rt + ln and token id
+  // v0 + 8*(e/4) + 4*lh + e%4.  Per row: this lane's 16 candidates go into a K-entry list, the two
+  // lanes of a row merge theirs, the four waves' lists meet in LDS (free by now: the last step ended
+  // with a barrier), and one thread per row leaves the workgroup's K best as part blockIdx.x.
+  uint64_t* lists = reinterpret_cast<uint64_t*>(hbuf);  // [ROWS][4 waves][KT]
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt) {
+  for (int rt = 0; rt < NRT; ++rt) {
+    TopList<KT> top;
+    top.clear();
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int row = row0 + 16 * mt + 4 * lg + i;
-      float pv = INFINITY;
-      int pi = -1;
-      for (int k = 0; k < a.K; ++k) {
-        float bv = -INFINITY;
-        int bi = INT_MAX;
+    for (int e = 0; e < 16; ++e) {
+      const int id = v0 + 8 * (e >> 2) + 4 * lh + (e & 3);
+      top.insert(id < a.V ? cand_key(acc[rt][e], id) : 0);
+    }
+    uint64_t other[KT];
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-          const float v = acc[mt][nt][i];
-          const int col = v0 + 16 * nt + lq;
-          if (col < a.V && cand_after(v, col, pv, pi) && v > bv) {
-            bv = v;
-            bi = col;
-          }
-        }
+    for (int k = 0; k < KT; ++k) {
+      const uint32_t lo = __shfl_xor((uint32_t)top.k[k], 32, 64), hi = __shfl_xor((uint32_t)(top.k[k] >> 32), 32, 64);
+      other[k] = ((uint64_t)hi << 32) | lo;
+    }
 #pragma unroll
-        for (int off = 1; off < 16; off <<= 1) {
-          const float ov = __shfl_xor(bv, off, 64);
-          const int oi = __shfl_xor(bi, off, 64);
-          if (cand_better(ov, oi, bv, bi)) {
-            bv = ov;
-            bi = oi;
-          }
-        }
-        if (lq == 0 && row < a.N) {
-          const size_t o = ((size_t)row * a.n_tiles + blockIdx.x) * a.K + k;
-          a.cand_val[o] = bv;
-          a.cand_idx[o] = bi;
-        }
-        pv = bv;
-        pi = bi;
-      }
+    for (int k = 0; k < KT; ++k) top.insert(other[k]);
+    if (lh == 0) {
+#pragma unroll
+      for (int k = 0; k < KT; ++k) lists[((32 * rt + ln) * 4 + w) * KT + k] = top.k[k];
     }
   }
+  __syncthreads();
+  for (int r = tid; r < ROWS; r += 256) {
+    TopList<KT> top;
+    top.clear();
+#pragma unroll
+    for (int j = 0; j < 4 * KT; ++j) top.insert(lists[r * 4 * KT + j]);
+    const int row = row0 + r;
+    if (row < a.N) {
+      const size_t o = ((size_t)row * a.n_tiles + blockIdx.x) * a.K;
+#pragma unroll
+      for (int k = 0; k < KT; ++k)
+        if (k < a.K) a.cand_key[o + k] = top.k[k];
+    }
+  }
+#ifdef SS_LM_TIMING
+  if (lane == 0) {
+    long long* dbg = (long long*)(a.cand_key + (size_t)a.N * a.n_tiles * a.K) + 64 + (blockIdx.x * 4 + w) * 8;
+    for (int i = 0; i < 4; ++i) dbg[i] = tacc[i];
+    dbg[4] = clock64() - t_ep0;
+    dbg[5] = n_k;
+    dbg[6] = clock64() - t_entry;
+    dbg[7] = (long long)__builtin_amdgcn_s_getreg(4 | (31 << 11)) | ((long long)(__builtin_amdgcn_s_getreg(20 | (31 << 11)) & 0xf) << 32);
+  }
+#endif
 }
 
-// ------------------------------------------------------------------ merge of the tiles' candidates
-// One wavefront per row; K rounds of "best candidate that comes after the previous winner".
+// ------------------------------------------------------------------ merge of the parts' candidates
+// One wavefront per row.  Every lane folds its share of the row's candidates into a K-entry list in
+// one pass over memory; then K rounds of a wave-wide arg-max over the heads of the lists, the
+// winning lane popping its head.
 __global__ __launch_bounds__(256) void lm_head_reduce_kernel(LmArgs a) {
   const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + w;
   if (row >= a.N) return;
   const int n = a.n_tiles * a.K;
-  const float* cv = a.cand_val + (size_t)row * n;
-  const int32_t* ci = a.cand_idx + (size_t)row * n;
-  float pv = INFINITY;
-  int pi = -1;
+  const uint64_t* ck = a.cand_key + (size_t)row * n;
+  TopList<SS_MAX_K> top;
+  top.clear();
+  for (int e0 = lane; e0 < n; e0 += 256) {
+    uint64_t c[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) c[j] = e0 + 64 * j < n ? ck[e0 + 64 * j] : 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) top.insert(c[j]);
+  }
   for (int k = 0; k < a.K; ++k) {
-    float bv = -INFINITY;
-    int bi = INT_MAX;
-    for (int e = lane; e < n; e += 64) {
-      const float v = cv[e];
-      const int i = ci[e];
-      if (cand_after(v, i, pv, pi) && cand_better(v, i, bv, bi)) {
-        bv = v;
-        bi = i;
-      }
-    }
+    uint64_t best = top.k[0];
     for (int off = 32; off > 0; off >>= 1) {
-      const float ov = __shfl_xor(bv, off, 64);
-      const int oi = __shfl_xor(bi, off, 64);
-      if (cand_better(ov, oi, bv, bi)) {
-        bv = ov;
-        bi = oi;
-      }
+      const uint32_t lo = __shfl_xor((uint32_t)best, off, 64), hi = __shfl_xor((uint32_t)(best >> 32), off, 64);
+      const uint64_t o = ((uint64_t)hi << 32) | lo;
+      best = o > best ? o : best;
     }
     if (lane == 0) {
-      a.idx[(size_t)row * a.K + k] = bi;
-      a.val[(size_t)row * a.K + k] = bv;
+      a.idx[(size_t)row * a.K + k] = key_id(best);
+      a.val[(size_t)row * a.K + k] = key_value(best);
     }
-    pv = bv;
-    pi = bi;
+    if (best == top.k[0] && best != 0) {  // keys are unique (token ids are): this lane won, pop its head
+#pragma unroll
+      for (int j = 0; j + 1 < SS_MAX_K; ++j) top.k[j] = top.k[j + 1];
+      top.k[SS_MAX_K - 1] = 0;
+    }
   }
 }
 
+template <int RT, int KT>
+static int launch_lm_bf16_rk(dim3 grid, hipStream_t st, const LmArgs& a) {
+  auto kern = lm_head_bf16_kernel<RT, KT>;
+  const size_t lds = 3 * (size_t)(64 * RT) * 128;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)lds);
+    if (e != hipSuccess) SS_FAIL(SS_ERR_HIP, "ss_lm_head_argmax_topk: hipFuncSetAttribute: %s", hipGetErrorString(e));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, a);
+  return SS_OK;
+}
+template <int RT>
+static int launch_lm_bf16_r(int KT, dim3 grid, hipStream_t st, const LmArgs& a) {
+  switch (KT) {
+    case 1: return launch_lm_bf16_rk<RT, 1>(grid, st, a);
+    case 4: return launch_lm_bf16_rk<RT, 4>(grid, st, a);
+    default: return launch_lm_bf16_rk<RT, 8>(grid, st, a);
+  }
+}
+static int launch_lm_bf16(int RT, int KT, dim3 grid, hipStream_t st, const LmArgs& a) {
+  switch (RT) {
+    case 1: return launch_lm_bf16_r<1>(KT, grid, st, a);
+    case 2: return launch_lm_bf16_r<2>(KT, grid, st, a);
+    case 3: return launch_lm_bf16_r<3>(KT, grid, st, a);
+    case 4: return launch_lm_bf16_r<4>(KT, grid, st, a);
+    default: return launch_lm_bf16_r<5>(KT, grid, st, a);
+  }
+}
+
+// Candidate parts per row: one per vocabulary tile (64 ids in the fp32 kernel, 128 in the MFMA kernel).
 static int lm_tiles(int V, int dtype) { return ceil_div(V, dtype == SS_BF16 ? 128 : 64); }
 
 static int lm_check(const char* fn, int N, int d, int V, int K, int dtype) {
@@ -292,6 +433,8 @@ static int lm_check(const char* fn, int N, int d, int V, int K, int dtype) {
   SS_REQUIRE(K <= V, SS_ERR_INVALID_ARG, "%s: K=%d exceeds V=%d", fn, K, V);
   SS_REQUIRE(dtype == SS_F32 || dtype == SS_BF16, SS_ERR_UNSUPPORTED, "%s: dtype %d", fn, dtype);
   SS_REQUIRE(dtype != SS_BF16 || d % 64 == 0, SS_ERR_UNSUPPORTED, "%s: bf16 path needs d %% 64 == 0 (d=%d)", fn, d);
+  SS_REQUIRE(dtype != SS_BF16 || ((long)(N < 1 ? 1 : N) * d < (1L << 30) && (long)V * d < (1L << 30)), SS_ERR_UNSUPPORTED,
+             "%s: hidden (%d x %d) or W (%d x %d) has 2^30 elements or more: too large for the bf16 path", fn, N, d, V, d);
   return SS_OK;
 }
 
@@ -320,8 +463,7 @@ int ss_lm_head_argmax_topk(const void* hidden, const void* W, int N, int d, int 
   a.hidden = hidden; a.W = W; a.N = N; a.d = d; a.V = V; a.K = K;
   a.n_tiles = lm_tiles(V, dtype);
   char* ws = (char*)(((uintptr_t)workspace + 255) & ~(uintptr_t)255);
-  a.cand_val = (float*)ws;
-  a.cand_idx = (int32_t*)(ws + (size_t)N * a.n_tiles * K * 4);
+  a.cand_key = (uint64_t*)ws;
   a.idx = idx; a.val = val;
   hipStream_t st = (hipStream_t)stream;
   if (dtype == SS_F32) {
@@ -329,17 +471,12 @@ int ss_lm_head_argmax_topk(const void* hidden, const void* W, int N, int d, int 
     SS_REQUIRE(grid.y <= 65535, SS_ERR_UNSUPPORTED, "%s: N too large", fn);
     hipLaunchKernelGGL(lm_head_f32_kernel, grid, dim3(256), 0, st, a);
   } else {
-    int MT = ceil_div(N, 64);
-    if (MT > 5) MT = 5;
-    dim3 grid(a.n_tiles, ceil_div(N, 64 * MT));
+    int RT = ceil_div(N, 64);
+    if (RT > 5) RT = 5;
+    dim3 grid(ceil_div(V, 128), ceil_div(N, 64 * RT));
     SS_REQUIRE(grid.y <= 65535, SS_ERR_UNSUPPORTED, "%s: N too large", fn);
-    switch (MT) {
-      case 1: hipLaunchKernelGGL(lm_head_bf16_kernel<1>, grid, dim3(256), 0, st, a); break;
-      case 2: hipLaunchKernelGGL(lm_head_bf16_kernel<2>, grid, dim3(256), 0, st, a); break;
-      case 3: hipLaunchKernelGGL(lm_head_bf16_kernel<3>, grid, dim3(256), 0, st, a); break;
-      case 4: hipLaunchKernelGGL(lm_head_bf16_kernel<4>, grid, dim3(256), 0, st, a); break;
-      default: hipLaunchKernelGGL(lm_head_bf16_kernel<5>, grid, dim3(256), 0, st, a); break;
-    }
+    const int KT = K == 1 ? 1 : (K <= 4 ? 4 : 8);
+    if (int rc = launch_lm_bf16(RT, KT, grid, st, a)) return rc;
   }
   if (int rc = check_launch(fn)) return rc;
   hipLaunchKernelGGL(lm_head_reduce_kernel, dim3(ceil_div(N, 4)), dim3(256), 0, st, a);
