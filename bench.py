@@ -31,9 +31,11 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E, vendor figure
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, vendor figure
 
-# HBM traffic of one launch of the MSA kernel on workload c4, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# scaled by a copy kernel of known size (see profiles/); None until measured.
-MSA_TRAFFIC_BYTES = {"c4": None, "c2": None, "c3": None, "c5": None}
+# HBM traffic of one launch of the MSA kernel, from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE; KiB
+# per dispatch), each scaled by what the same counter reads for the 256 MiB device copy of --calibrate-copy
+# (FETCH_SIZE reads half of the bytes the copy fetches: factor 2.0; WRITE_SIZE factor 1.0).  c4: 139727 KiB
+# x 2.0 fetched + 23680 KiB written (the fp32 split partials).  Summaries are under profiles/.
+MSA_TRAFFIC_BYTES = {"c4": int((139727.2 * 2.0 + 23680.0) * 1024), "c2": None, "c3": None, "c5": None}
 
 
 def msa_bytes(cfg, seq_lens):
@@ -64,35 +66,49 @@ def timed(fn, iters, torch):
 
 
 def cpu_baseline(cfg, synth, seq_lens):
-    """Oracle on a bounded sample: MSA of one layer for one sequence and 4 of its heads; LM head for
-    8 rows over the whole vocabulary; scaled linearly to a full step."""
+    """The oracle on the same workload, whole steps (every MSA layer on its own inputs, the LM head, verify,
+    draft), repeated until about 10 s of CPU time have been spent (at most 8 steps); the mean step is reported."""
     import numpy as np
     import oracle
     oracle.build()
-    heads = min(4, cfg.Hkv)
-    small = synth.scaled(cfg, B=1, H=heads * (cfg.H // cfg.Hkv), Hkv=heads, L_min=int(max(seq_lens)),
-                         L_max=int(max(seq_lens)))
-    inp = synth.make_msa_inputs(small, 4242)
     f32 = lambda t: t.float().numpy()
-    args = (f32(inp["q"]), f32(inp["k_new"]), f32(inp["v_new"]), f32(inp["k_cache"]), f32(inp["v_cache"]),
-            inp["block_table"].numpy(), inp["seq_lens"].numpy(), inp["parent"].numpy(), small.gamma, inp["scale"])
-    t0 = time.perf_counter()
-    oracle.msa_attention(*args)
-    t_msa = time.perf_counter() - t0
-    keys_sample = int(max(seq_lens)) * heads
-    keys_full = sum(int(L) for L in seq_lens) * cfg.Hkv
-    est = t_msa * keys_full / keys_sample * cfg.n_layers
-    sample = "MSA: 1 sequence x %d KV heads x 1 layer (%.2f s)" % (heads, t_msa)
+    layers = []
+    for i in range(cfg.n_layers):
+        inp = synth.make_msa_inputs(cfg, 4242, layer=i)
+        layers.append((f32(inp["q"]), f32(inp["k_new"]), f32(inp["v_new"]), f32(inp["k_cache"]), f32(inp["v_cache"]),
+                       inp["block_table"].numpy(), inp["seq_lens"].numpy(), inp["parent"].numpy(), cfg.gamma, inp["scale"]))
+    par = layers[0][7]
     if cfg.vocab:
-        rows = 8
-        lm = synth.make_lm_head_inputs(cfg, 4242, N=rows)
+        lm = synth.make_lm_head_inputs(cfg, 4242)
+        hidden, W = f32(lm["hidden"]), f32(lm["W"])
+        tok = synth.make_draft_tokens(4242, par, cfg.vocab)
+        tp, tr, _ = oracle.full_tree_template(cfg.draft_branching)
+    reps, t_all = 0, 0.0
+    while reps < 8 and t_all < 10.0:
         t0 = time.perf_counter()
-        oracle.lm_head_topk(f32(lm["hidden"]), f32(lm["W"]), cfg.K)
-        t_lm = time.perf_counter() - t0
-        est += t_lm * (cfg.B * cfg.R) / rows
-        sample += "; LM head: %d of %d rows x full vocabulary (%.2f s)" % (rows, cfg.B * cfg.R, t_lm)
-    return {"value": est * 1e6, "unit": "us", "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": sample + "; scaled linearly to the full step"}
+        for a in layers:
+            oracle.msa_attention(*a)
+        if cfg.vocab:
+            idx, _ = oracle.lm_head_topk(hidden, W, cfg.K)
+            idx = np.ascontiguousarray(idx.reshape(cfg.B, cfg.R, cfg.K))
+            ver = oracle.tree_verify(tok, par, np.ascontiguousarray(idx[:, :cfg.T, 0]), cfg.max_depth)
+            topk = np.ascontiguousarray(idx[:, cfg.T:, :].reshape(cfg.B, cfg.T, cfg.gamma, cfg.K))
+            oracle.tree_draft(topk, ver["last"], ver["bonus"], tp, tr)
+        t_all += time.perf_counter() - t0
+        reps += 1
+    return {"value": round(t_all / reps * 1e6, 1), "unit": "us", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "%d whole steps of the same workload (%d MSA layers + LM head + verify + draft each), %.1f s in all; "
+                      "mean step" % (reps, cfg.n_layers, t_all)}
+
+
+def calibrate_copy(torch, dev):
+    """A plain device-to-device copy of known size (256 MiB read, 256 MiB written per call), so that a
+    rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run of this script has a kernel to scale the counters by."""
+    src = torch.ones(128 * 1024 * 1024, dtype=torch.bfloat16, device=dev)
+    dst = torch.empty_like(src)
+    for _ in range(4):
+        dst.copy_(src)
+    torch.cuda.synchronize()
 
 
 def main():
@@ -103,6 +119,8 @@ def main():
     ap.add_argument("--workload", default="c4", choices=["c2", "c3", "c4", "c5"])
     ap.add_argument("--split-keys", type=int, default=0, help="KV split length of the MSA kernel (0 = automatic)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a 256 MiB device copy (reference kernel for scaling profiler byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus %d is not supported (the path uses no collectives; "
@@ -120,6 +138,8 @@ def main():
     torch.cuda.set_device(0)
     cfg = synth.CONFIGS[args.workload]
     api.load_library()
+    if args.calibrate_copy:
+        calibrate_copy(torch, dev)
     if args.split_keys:
         api.ss_msa_set_split_keys(args.split_keys)
 

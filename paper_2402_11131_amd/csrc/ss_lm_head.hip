@@ -255,7 +255,11 @@ __global__ __launch_bounds__(256, 1) void lm_head_bf16_kernel(LmArgs a) {
     constexpr int NLD = HL + 4;  // global loads of the step: hidden first, then W
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
+#ifdef SS_LM_EXP_NOREAD
+      if (c < 0) {
+#else
       if (c < 3) {
+#endif
 #pragma unroll
         for (int rt = 0; rt < NRT; ++rt)
           hop[(c + 1) & 1][rt] =
@@ -264,12 +268,18 @@ __global__ __launch_bounds__(256, 1) void lm_head_bf16_kernel(LmArgs a) {
       int n_ld = 0, n_st = 0;
 #pragma unroll
       for (int l = (c * NLD) / 4; l < ((c + 1) * NLD) / 4; ++l, ++n_ld) {
+#ifndef SS_LM_EXP_NOLOAD
         if (l < HL) h_new[l] = *reinterpret_cast<const uintx4*>(h_base + h_voff[l]);
         else w_next[l - HL] = *reinterpret_cast<const uintx4*>(w_base + w_voff + 32 * (l - HL));
+#endif
       }
 #pragma unroll
       for (int i = (c * HL) / 4; i < ((c + 1) * HL) / 4; ++i, ++n_st)
+#ifndef SS_LM_EXP_NOSTORE
         *reinterpret_cast<uintx4*>(hst + i * (32 * 128)) = h_old[i];
+#else
+        ;
+#endif
       const bf16x8 wop = __builtin_bit_cast(bf16x8, w_now[c]);
 #pragma unroll
       for (int rt = 0; rt < NRT; ++rt)
