@@ -119,6 +119,9 @@ def main():
     ap.add_argument("--workload", default="c4", choices=["c2", "c3", "c4", "c5"])
     ap.add_argument("--split-keys", type=int, default=0, help="KV split length of the MSA kernel (0 = automatic)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture the step's launches once into a HIP graph and replay it (measured: no faster "
+                         "than launching from the host, the step is bound by the kernels, not by launches)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a 256 MiB device copy (reference kernel for scaling profiler byte counters)")
     args = ap.parse_args()
@@ -205,8 +208,26 @@ def main():
         tok.copy_(torch.from_numpy(tok_np))
         step(0)
         torch.cuda.synchronize()
+    # Optionally the step's launches are captured once into a HIP graph and replayed (only when every
+    # step sees the same input sets; replays are checked against the eager result before anything is timed).
+    use_graph = args.graph and n_sets == cfg.n_layers
+    run_step = step
+    if use_graph:
+        eager = [state["ver"]["out_tokens"].clone(), state["nxt"][0].clone(), idx.clone()] if has_lm else [o.clone() for o in outs]
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step(0)
+        for _ in range(3):
+            graph.replay()
+            torch.cuda.synchronize()
+            now = [state["ver"]["out_tokens"], state["nxt"][0], idx] if has_lm else outs
+            for e_, n_ in zip(eager, now):
+                if not torch.equal(e_, n_):
+                    print("bench.py: a graph replay differs from the eager step", file=sys.stderr)
+                    sys.exit(1)
+        run_step = lambda i: graph.replay()
     t_wall0 = time.perf_counter()
-    us_step = timed(step, args.steps, torch)
+    us_step = timed(run_step, args.steps, torch)
     wall_s = time.perf_counter() - t_wall0
 
     # ---- per-kernel figures (each in its own timed loop, same rotation of inputs)
@@ -254,7 +275,8 @@ def main():
                                    cfg.T, cfg.gamma, cfg.R, cfg.page, cfg.n_layers,
                                    ", LM head %dx%dx%d top-%d" % (cfg.B * cfg.R, cfg.d_model, cfg.vocab, cfg.K)
                                    if has_lm else ""),
-                   "input_sets_rotated": n_sets, "split_keys": args.split_keys or "auto"},
+                   "input_sets_rotated": n_sets, "split_keys": args.split_keys or "auto",
+                   "launch": "hip graph replay" if use_graph else "eager"},
         "roofline": roofline, "kernels": kern, "timed_wall_s": round(wall_s, 3),
     }
     result.update(extra)

@@ -134,14 +134,53 @@ __global__ __launch_bounds__(256) void lm_head_f32_kernel(LmArgs a) {
 // lines with 32 contiguous bytes each.  Four blocks are in flight per wave (the
 // ring is filled three blocks ahead of use): 12 KB per wave against the HBM
 // latency, with one wave per SIMD.  `hidden` is shared by the waves and goes
-// through LDS: three buffers of 64*RT rows x 128 bytes, 16-byte chunks
-// XOR-swizzled ((row >> 1) & 7) so that the operand reads (32 rows x one chunk,
-// 16 lanes per LDS cycle over 64 banks) are conflict free; a block is fetched
-// (from L2) into registers three blocks ahead, written to LDS one block later,
-// and one barrier per block publishes it.  Loads complete in order, so within a
-// step the `hidden` loads are issued before the W loads: waiting for them never
-// waits for younger W blocks.
+// through LDS: three buffers of 64*RT rows x 128 bytes, filled two blocks ahead
+// by direct global->LDS loads (no staging registers and, more important, no
+// ds_write: LDS stores of this size run at a quarter of the read rate).  Such a
+// load writes lane l's 16 bytes to (base + 16*l), so the LDS image is row-major;
+// the chunks of a row are XOR-swizzled on the global side (lane (row r, position
+// q) fetches chunk q ^ ((r >> 1) & 7)), which makes the operand reads (32 rows x
+// one chunk, 16 lanes per LDS cycle over 64 banks) conflict free.  One barrier
+// per block publishes the next buffer.  These loads are inline assembly (the
+// compiler would drain the memory counter before every LDS read if it knew of
+// them), so the wait for them is written by hand: loads complete in order, a step
+// issues its `hidden` loads before its W loads, and at the end of step J
+// everything but the loads of step J and the W loads of step J-1 must have
+// landed.  The compiler's own waits for W registers count only W loads and
+// therefore wait for a little more than they need (W of the block after next).
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
+
+// 16 bytes per lane from (sbase + voff) to LDS address lds_addr + 16*lane.
+SS_DEV void load_to_lds16(const void* sbase, uint32_t voff, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %0" ::"s"(sbase), "v"(voff), "s"(lds_addr) : "memory");
+}
+
+// The KT best (logit, id) pairs of candidates that arrive in increasing id order: an equal logit
+// never displaces an earlier entry, so a strict float compare implements "lower id first".
+template <int KT>
+struct TopAsc {
+  float v[KT];
+  int i[KT];
+  SS_DEV void clear() {
+#pragma unroll
+    for (int j = 0; j < KT; ++j) {
+      v[j] = -INFINITY;
+      i[j] = INT_MAX;
+    }
+  }
+  SS_DEV void insert(float cv, int ci) {
+#pragma unroll
+    for (int j = 0; j < KT; ++j) {
+      const bool up = cv > v[j];
+      const float nv = fmaxf(v[j], cv), ov = fminf(v[j], cv);
+      const int ni = up ? ci : i[j], oi = up ? i[j] : ci;
+      v[j] = nv;
+      i[j] = ni;
+      cv = ov;
+      ci = oi;
+    }
+  }
+};
 
 template <int KT>
 struct TopList {  // the KT best keys seen so far, best first
@@ -179,13 +218,17 @@ __global__ __launch_bounds__(256, 1) void lm_head_bf16_kernel(LmArgs a) {
   // Sources as 32-bit byte offsets from a scalar base that moves with the feature block, so that a
   // load needs no vector arithmetic (the host checks that the matrices are below 2 GiB).  W operand:
   // row v0 + ln, bytes 16*lh.. of each 32-byte piece; ids past the vocabulary are clamped and their
-  // logits dropped later.  hidden staging: thread -> rows tid/8 + 32*i, chunk tid%8; rows past N are
-  // clamped and dropped later.
+  // logits dropped later.  Rows of hidden past N are clamped and dropped later as well.
   const uint32_t w_voff = ((uint32_t)min(v0 + ln, a.V - 1) * (uint32_t)d + 8 * lh) * 2;
+  // hidden: 1 KB load slots of 8 rows; wave w takes slots w, w+4, ...; lane -> (row lane/8 of the slot,
+  // chunk position lane%8)
   uint32_t h_voff[HL];
 #pragma unroll
-  for (int i = 0; i < HL; ++i) h_voff[i] = ((uint32_t)min(row0 + (tid >> 3) + 32 * i, a.N - 1) * (uint32_t)d + (tid & 7) * 8) * 2;
-  const int hdst = (tid >> 3) * 128 + (((tid & 7) ^ ((tid >> 4) & 7)) * 16);
+  for (int i = 0; i < HL; ++i) {
+    const int r = 8 * (w + 4 * i) + (lane >> 3);
+    h_voff[i] = ((uint32_t)min(row0 + r, a.N - 1) * (uint32_t)d + (((lane & 7) ^ ((r >> 1) & 7)) * 8)) * 2;
+  }
+  const uint32_t lds0 = (uint32_t)(uintptr_t)hbuf;
   // hidden operand reads: row 32*rt + ln, logical chunk 2*c + lh
   int hrd[4];
 #pragma unroll
@@ -198,39 +241,40 @@ __global__ __launch_bounds__(256, 1) void lm_head_bf16_kernel(LmArgs a) {
     for (int e = 0; e < 16; ++e) acc[rt][e] = 0.f;
 
   uintx4 wq[4][4];   // ring of W blocks in flight: [block % 4][step]
-  uintx4 hs[2][HL];  // two blocks of `hidden` on their way to LDS
 
   auto load_w = [&](int J, uintx4 (&dst)[4]) {
     const unsigned char* base = (const unsigned char*)a.W + (size_t)J * 128;
 #pragma unroll
     for (int c = 0; c < 4; ++c) dst[c] = *reinterpret_cast<const uintx4*>(base + w_voff + 32 * c);
   };
-  auto load_h = [&](int J, uintx4 (&dst)[HL]) {
+  auto load_h = [&](int J, int buf) {  // block J -> LDS buffer buf
     const unsigned char* base = (const unsigned char*)a.hidden + (size_t)J * 128;
 #pragma unroll
-    for (int i = 0; i < HL; ++i) dst[i] = *reinterpret_cast<const uintx4*>(base + h_voff[i]);
+    for (int i = 0; i < HL; ++i) load_to_lds16(base, h_voff[i], lds0 + buf * HB + (w + 4 * i) * 1024);
   };
-  auto store_h = [&](int buf, const uintx4 (&src)[HL]) {
-#pragma unroll
-    for (int i = 0; i < HL; ++i) *reinterpret_cast<uintx4*>(hbuf + buf * HB + hdst + i * (32 * 128)) = src[i];
-  };
-  // prologue: hidden blocks 0 and 1 in LDS, block 2 and W blocks 0..2 on their way
-  load_h(0, hs[0]);
-  load_h(min(1, n_k - 1), hs[1]);
-  store_h(0, hs[0]);
-  store_h(1, hs[1]);
-  load_h(min(2, n_k - 1), hs[1]);
+
+  // prologue: hidden blocks 0, 1 and W blocks 0..2 on their way; block 0 of hidden has to be there
+  constexpr int WAIT_ALL = 0x0F70;  // s_waitcnt vmcnt(0)
+  // loads that may be in flight at the end of a step: its own HL + 4 and the 4 W loads of the step before
+  constexpr int PENDING = HL + 8;
+  constexpr int WAIT_STEP = 0x0F70 | (PENDING & 15) | ((PENDING >> 4) << 14);  // s_waitcnt vmcnt(PENDING)
+  load_h(0, 0);
+  load_h(min(1, n_k - 1), 1);
   load_w(0, wq[0]);
   load_w(min(1, n_k - 1), wq[1]);
   load_w(min(2, n_k - 1), wq[2]);
+  __builtin_amdgcn_s_waitcnt(WAIT_ALL);
   __syncthreads();
 
-  // Block J: W from ring slot J % 4, hidden from LDS buffer J % 3.  Top of the step: start hidden
-  // block J+3 (register set J % 2) and W block J+3 (the slot block J-1 left); bottom: hidden block
-  // J+2, started a step earlier in the other register set, goes to the buffer block J-1 was read from
-  // (every wave passed the previous barrier since).  Past the end the last block is fetched again
-  // instead, which keeps the steps free of conditions (a condition around the MFMAs would cost a
-  // register copy per accumulator).  The scheduling fences keep the loads at the top of the step.
+  // Block J: W from ring slot J % 4, hidden from LDS buffer J % 3.  A step starts hidden block J+2
+  // (into the buffer block J-1 was read from: every wave passed the previous barrier since) and W
+  // block J+3 (into the slot block J-1 left).  Past the end the last block is fetched again instead,
+  // which keeps the steps free of conditions (a condition around the MFMAs would cost a register copy
+  // per accumulator).
+  // A step is four MFMA rounds (16 features each, 2*RT MFMAs).  The L1 takes a load instruction of a
+  // wave only every ~18 cycles and the four waves share it, so the step's loads are dealt to the
+  // rounds and, inside a round, placed between the MFMAs (scheduling groups) instead of stalling the
+  // wave in a burst.  The operand reads of round c+1 are issued in round c.
   int buf = 0;
 #ifdef SS_LM_TIMING
   long long tacc[4] = {0, 0, 0, 0}, t_last = clock64();
@@ -238,16 +282,12 @@ __global__ __launch_bounds__(256, 1) void lm_head_bf16_kernel(LmArgs a) {
 #else
 #define SS_LT(i)
 #endif
-  // A step is four MFMA rounds (16 features each, 2*RT MFMAs).  The L1 takes a load instruction of a
-  // wave only every ~18 cycles and the four waves share it, so the step's global loads and LDS writes
-  // are dealt to the rounds and, inside a round, placed between the MFMAs (scheduling groups) instead
-  // of stalling the wave in a burst.  The operand reads of round c+1 are issued in round c.
-  auto step = [&](int J, uintx4 (&w_now)[4], uintx4 (&w_next)[4], uintx4 (&h_new)[HL], uintx4 (&h_old)[HL]) {
+  auto step = [&](int J, uintx4 (&w_now)[4], uintx4 (&w_next)[4]) {
     const unsigned char* hb = hbuf + buf * HB;
-    unsigned char* hst = hbuf + (buf == 0 ? 2 : buf - 1) * HB + hdst;  // buffer (J + 2) % 3
-    const int Jn = min(J + 3, n_k - 1);
-    const unsigned char* h_base = (const unsigned char*)a.hidden + (size_t)Jn * 128;
-    const unsigned char* w_base = (const unsigned char*)a.W + (size_t)Jn * 128;
+    const int Jh = min(J + 2, n_k - 1), Jw = min(J + 3, n_k - 1);
+    const unsigned char* h_base = (const unsigned char*)a.hidden + (size_t)Jh * 128;
+    const unsigned char* w_base = (const unsigned char*)a.W + (size_t)Jw * 128;
+    const uint32_t h_dst = lds0 + (buf == 0 ? 2 : buf - 1) * HB + w * 1024;  // buffer (J + 2) % 3
     bf16x8 hop[2][NRT];
 #pragma unroll
     for (int rt = 0; rt < NRT; ++rt)
@@ -255,58 +295,51 @@ __global__ __launch_bounds__(256, 1) void lm_head_bf16_kernel(LmArgs a) {
     constexpr int NLD = HL + 4;  // global loads of the step: hidden first, then W
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-#ifdef SS_LM_EXP_NOREAD
-      if (c < 0) {
-#else
       if (c < 3) {
-#endif
 #pragma unroll
         for (int rt = 0; rt < NRT; ++rt)
           hop[(c + 1) & 1][rt] =
               __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(hb + hrd[c + 1] + rt * (32 * 128)));
       }
-      int n_ld = 0, n_st = 0;
+      int n_w = 0;
 #pragma unroll
-      for (int l = (c * NLD) / 4; l < ((c + 1) * NLD) / 4; ++l, ++n_ld) {
-#ifndef SS_LM_EXP_NOLOAD
-        if (l < HL) h_new[l] = *reinterpret_cast<const uintx4*>(h_base + h_voff[l]);
-        else w_next[l - HL] = *reinterpret_cast<const uintx4*>(w_base + w_voff + 32 * (l - HL));
-#endif
+      for (int l = (c * NLD) / 4; l < ((c + 1) * NLD) / 4; ++l) {
+        if (l < HL) {
+          load_to_lds16(h_base, h_voff[l], h_dst + l * 4096);
+        } else {
+          w_next[l - HL] = *reinterpret_cast<const uintx4*>(w_base + w_voff + 32 * (l - HL));
+          ++n_w;
+        }
       }
-#pragma unroll
-      for (int i = (c * HL) / 4; i < ((c + 1) * HL) / 4; ++i, ++n_st)
-#ifndef SS_LM_EXP_NOSTORE
-        *reinterpret_cast<uintx4*>(hst + i * (32 * 128)) = h_old[i];
-#else
-        ;
-#endif
       const bf16x8 wop = __builtin_bit_cast(bf16x8, w_now[c]);
 #pragma unroll
       for (int rt = 0; rt < NRT; ++rt)
         acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wop, hop[c & 1][rt], acc[rt], 0, 0, 0);
 #pragma unroll
       for (int i = 0; i < NRT; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                 // MFMA
-        if (i < n_ld) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // global load
-        if (i < n_st) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);  // LDS write
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                // MFMA
+        if (i < n_w) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // global load
       }
       __builtin_amdgcn_sched_barrier(0);
     }
     buf = buf == 2 ? 0 : buf + 1;
     SS_LT(1);
+    __builtin_amdgcn_s_waitcnt(WAIT_STEP);  // hidden block J+1 has landed (and W block J+1)
     __syncthreads();
     SS_LT(3);
   };
   int J = 0;
   for (; J + 4 <= n_k; J += 4) {
-    step(J, wq[0], wq[3], hs[0], hs[1]);
-    step(J + 1, wq[1], wq[0], hs[1], hs[0]);
-    step(J + 2, wq[2], wq[1], hs[0], hs[1]);
-    step(J + 3, wq[3], wq[2], hs[1], hs[0]);
+    step(J, wq[0], wq[3]);
+    step(J + 1, wq[1], wq[0]);
+    step(J + 2, wq[2], wq[1]);
+    step(J + 3, wq[3], wq[2]);
   }
-  if (J < n_k) step(J, wq[0], wq[3], hs[0], hs[1]);
-  if (J + 1 < n_k) step(J + 1, wq[1], wq[0], hs[1], hs[0]);
-  if (J + 2 < n_k) step(J + 2, wq[2], wq[1], hs[0], hs[1]);
+  if (J < n_k) step(J, wq[0], wq[3]);
+  if (J + 1 < n_k) step(J + 1, wq[1], wq[0]);
+  if (J + 2 < n_k) step(J + 2, wq[2], wq[1]);
+  __builtin_amdgcn_s_waitcnt(WAIT_ALL);  // the redundant tail loads, before LDS is reused
+  __syncthreads();
 
 #ifdef SS_LM_TIMING
   const long long t_ep0 = clock64();
@@ -318,13 +351,16 @@ __global__ __launch_bounds__(256, 1) void lm_head_bf16_kernel(LmArgs a) {
   uint64_t* lists = reinterpret_cast<uint64_t*>(hbuf);  // [ROWS][4 waves][KT]
 #pragma unroll
   for (int rt = 0; rt < NRT; ++rt) {
-    TopList<KT> top;
-    top.clear();
+    TopAsc<KT> asc;  // this lane's candidates come in increasing id order
+    asc.clear();
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
       const int id = v0 + 8 * (e >> 2) + 4 * lh + (e & 3);
-      top.insert(id < a.V ? cand_key(acc[rt][e], id) : 0);
+      asc.insert(id < a.V ? acc[rt][e] : -INFINITY, id);
     }
+    TopList<KT> top;
+#pragma unroll
+    for (int k = 0; k < KT; ++k) top.k[k] = asc.i[k] == INT_MAX ? 0 : cand_key(asc.v[k], asc.i[k]);  // unused slots rank last
     uint64_t other[KT];
 #pragma unroll
     for (int k = 0; k < KT; ++k) {
@@ -365,12 +401,12 @@ __global__ __launch_bounds__(256, 1) void lm_head_bf16_kernel(LmArgs a) {
 }
 
 // ------------------------------------------------------------------ merge of the parts' candidates
-// One wavefront per row.  Every lane folds its share of the row's candidates into a K-entry list in
+// One wavefront (one workgroup) per row.  Every lane folds its share of the row's candidates into a K-entry list in
 // one pass over memory; then K rounds of a wave-wide arg-max over the heads of the lists, the
 // winning lane popping its head.
-__global__ __launch_bounds__(256) void lm_head_reduce_kernel(LmArgs a) {
-  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int row = blockIdx.x * 4 + w;
+__global__ __launch_bounds__(64) void lm_head_reduce_kernel(LmArgs a) {
+  const int lane = threadIdx.x;
+  const int row = blockIdx.x;
   if (row >= a.N) return;
   const int n = a.n_tiles * a.K;
   const uint64_t* ck = a.cand_key + (size_t)row * n;
@@ -489,7 +525,7 @@ int ss_lm_head_argmax_topk(const void* hidden, const void* W, int N, int d, int 
     if (int rc = launch_lm_bf16(RT, KT, grid, st, a)) return rc;
   }
   if (int rc = check_launch(fn)) return rc;
-  hipLaunchKernelGGL(lm_head_reduce_kernel, dim3(ceil_div(N, 4)), dim3(256), 0, st, a);
+  hipLaunchKernelGGL(lm_head_reduce_kernel, dim3(N), dim3(64), 0, st, a);
   return check_launch(fn);
 }
 
