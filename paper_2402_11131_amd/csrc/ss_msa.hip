@@ -223,11 +223,16 @@ struct MsaPlan {
   size_t part_o_bytes, part_lse_bytes, total_bytes;
 };
 
-// Chooses the split length from the shape alone (sequence lengths live on the device): just enough
-// splits for about 512 workgroups (two resident per compute unit), because every further split costs
-// a workgroup set-up and fp32 partial results that the merge kernel reads back; no split shorter
-// than 256 cached tokens.  When even that leaves the chip short of workgroups the MFMA path runs two
-// wave groups per workgroup (a split inside the workgroup, merged through LDS).
+// Chooses the split length from the shape alone (sequence lengths live on the device).  Every split
+// costs a workgroup set-up and fp32 partial results that the merge kernel reads back, so the plan uses
+// as few as fill the chip; no split is shorter than 256 cached tokens.
+//   fp32 kernel: splits for about 512 workgroups.
+//   MFMA kernel: with 512 or more (sequence, KV head, row chunk) items one workgroup of one wave group
+//   each, two resident per compute unit (measured best when lengths vary: the hardware evens them out);
+//   with fewer, three wave groups per workgroup (the prefix split again inside the workgroup and merged
+//   through LDS: 15 waves on a compute unit) and splits for about 256 workgroups; three wave groups also
+//   when a sequence has several row chunks (long GQA trees: the kernel is then bound by the matrix
+//   cores and more waves hide more latency).
 static MsaPlan make_plan(int B, int R, int H, int Hkv, int D, int max_len, int dtype) {
   MsaPlan p;
   const int g = H / Hkv;
@@ -247,7 +252,16 @@ static MsaPlan make_plan(int B, int R, int H, int Hkv, int D, int max_len, int d
   if (g_split_keys_override > 0) {
     split_keys = g_split_keys_override;
   } else {
-    int n = ceil_div(512, base);
+    int want_wgs = 512;
+    if (dtype == SS_BF16) {
+      if (base < 512) {
+        p.groups = 3;
+        want_wgs = 256;
+      } else if (p.n_qc > 1) {
+        p.groups = 3;
+      }
+    }
+    int n = ceil_div(want_wgs, base);
     const int n_cap = len / 256 < 1 ? 1 : len / 256;
     if (n > n_cap) n = n_cap;
     split_keys = ceil_div(len, n);
@@ -255,7 +269,6 @@ static MsaPlan make_plan(int B, int R, int H, int Hkv, int D, int max_len, int d
   split_keys = (int)align_up((size_t)(split_keys < 64 ? 64 : split_keys), 64);
   p.split_keys = split_keys;
   p.n_splits = ceil_div(len, split_keys);
-  if (dtype == SS_BF16 && (long)base * p.n_splits < 384) p.groups = 2;
   if (p.n_splits > 1) {
     p.part_o_bytes = align_up((size_t)B * H * p.n_splits * R * D * sizeof(float), 256);
     p.part_lse_bytes = align_up((size_t)B * H * p.n_splits * R * sizeof(float), 256);

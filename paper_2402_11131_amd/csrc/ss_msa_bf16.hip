@@ -68,8 +68,15 @@ constexpr int kMaxWaves = 16;  // waves per workgroup: 4 per SIMD leaves each wa
 
 // key (0..31) that row m of score tile X holds inside a 32-key unit
 SS_DEV int block_key(int m, int X) { return 8 * (m >> 2) + (m & 3) + 4 * X; }
-// XOR swizzle of a K row's 16-byte chunks inside an LDS stage
-SS_DEV int k_swz(int row) { return (row & 3) | (((row >> 3) & 1) << 2); }
+// XOR swizzle of a K row's 16-byte chunks inside an LDS stage.  An operand read takes one chunk of
+// each of the 16 rows block_key(0..15, X) per LDS cycle (16 lanes, 64 banks of 4 bytes): the swizzle
+// has to spread those 16 chunks over all 16 bank groups.  Rows of 256 bytes (D = 128) cover the banks
+// once each, so the 16 rows need 16 different 4-bit values; rows of 128 bytes (D = 64) alternate
+// between the two halves of the banks, so rows of equal parity need 8 different 3-bit values.
+template <int D>
+SS_DEV int k_swz(int row) {
+  return D == 128 ? ((row & 3) | (((row >> 3) & 3) << 2)) : (((row >> 1) & 1) | (((row >> 3) & 3) << 1));
+}
 
 SS_DEV bf16x8 as_bf16x8(uintx4 u) { return __builtin_bit_cast(bf16x8, u); }
 SS_DEV uintx4 ld16(const uint16_t* p) { return *reinterpret_cast<const uintx4*>(p); }
@@ -208,7 +215,7 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
 
   // ---- per-lane and per-slot parts of the main loop's addresses (loop invariant).  A unit is moved
   // in 1 KB slots.  K slot sl: rows ROWS_PER_SLOT*sl + lane/CPR, chunk position p = lane%CPR holding
-  // chunk p ^ k_swz(row); the swizzle's bit 2 only depends on the slot.  V slot s2: 8-key chunks
+  // chunk p ^ k_swz(row).  V slot s2: 8-key chunks
   // kc = 2*half + (lane&1) of features dblk*32 + lane/2, half = s2 / V_DBLK, dblk = s2 % V_DBLK.
   // The first LW waves of a group move the data: wave wt takes K slots and V slots wt + LW*j.
   const int ril = lane / CPR, pch = lane % CPR;
@@ -224,17 +231,18 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
     const int sl = (loader ? wt : 0) + LW * j, r0 = ROWS_PER_SLOT * sl;
     k_second[j] = r0 >= 16;
     k_soff[j] = (r0 & 15) * D;
-    k_lsrc[j] = ril * D + ((pch ^ (ril & 3) ^ (((r0 >> 3) & 1) << 2)) * 8);
+    k_lsrc[j] = ril * D + ((pch ^ k_swz<D>(r0 + ril)) * 8);
     k_ldst[j] = sl * 1024 + lane * 16;
     const int half = sl / V_DBLK, dblk = sl % V_DBLK;
     v_second[j] = half != 0;
     v_soff[j] = dblk * 32 * a.page;
     v_ldst[j] = dblk * (32 * VROW) + (half ? v_dst1 : v_dst0);
   }
-  // operand reads: K row of score tile 0 (tile 1 is 4 rows further), even / odd feature step; V row
-  const int rr0 = block_key(lq, 0), k_sh = (lq >> 2) & 1, k_lo = lg ^ (lq & 3);
-  const int k_rd_even = rr0 * (2 * D) + (((k_sh << 2) | k_lo) * 16);
-  const int k_rd_odd = rr0 * (2 * D) + ((((k_sh ^ 1) << 2) | k_lo) * 16);
+  // operand reads: K row of score tile 0 (tile 1 is 4 rows further, same swizzle), chunk 4*ks + lg; V row
+  const int rr0 = block_key(lq, 0);
+  int k_rd[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) k_rd[ks] = rr0 * (2 * D) + (((4 * ks + lg) ^ k_swz<D>(rr0)) * 16);
   const int v_rd = K_BYTES + lq * VROW + ((lg ^ ((lq >> 1) & 3)) * 16);
 
   // Main-loop unit u (a full block of the prefix) -> registers: scalar base per half, 16 bytes per lane.
@@ -280,8 +288,7 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
       floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        const uintx4 kop = *reinterpret_cast<const uintx4*>(st + ((ks & 1) ? k_rd_odd : k_rd_even) +
-                                                            (ks >> 1) * 128 + X * (8 * D));
+        const uintx4 kop = *reinterpret_cast<const uintx4*>(st + k_rd[ks] + X * (8 * D));
         acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kop), Qr[ks], acc, 0, 0, 0);
       }
       S[X] = acc;
@@ -443,7 +450,7 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
           ksrc = k_new + row * D;
           vsrc = v_new + row * D + pch2 * 8;
         }
-        stg[j] = ld16(ksrc + ((pch2 ^ k_swz(rr)) * 8));
+        stg[j] = ld16(ksrc + ((pch2 ^ k_swz<D>(rr)) * 8));
         stg[KJ + j] = ld16(vsrc);
       }
     };
