@@ -315,9 +315,11 @@ __global__ __launch_bounds__(256, 1) void lm_head_bf16_kernel(LmArgs a) {
 #pragma unroll
       for (int rt = 0; rt < NRT; ++rt)
         acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wop, hop[c & 1][rt], acc[rt], 0, 0, 0);
+      if (c == 0) __builtin_amdgcn_sched_group_barrier(0x100, NRT, 0);   // round 0: its own operand reads first
 #pragma unroll
       for (int i = 0; i < NRT; ++i) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                // MFMA
+        if (c < 3) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);    // one operand read of the next round
         if (i < n_w) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // global load
       }
       __builtin_amdgcn_sched_barrier(0);
