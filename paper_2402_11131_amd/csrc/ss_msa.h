@@ -20,7 +20,7 @@ struct MsaArgs {
   float* part_lse;  // [B,H,S,R]    log2-domain log-sum-exp of each split
   int B, T, gamma, R, H, Hkv, g, D;
   int page, page_shift, max_pages, num_pages;
-  int split_keys;  // cached tokens per split (multiple of 64)
+  int split_keys;  // cached tokens per split (multiple of 32; of 64 for the fp32 kernel)
   int n_splits;    // S: upper bound on splits per sequence
   int n_qc;        // query-row chunks per (sequence, KV head) (MFMA path)
   int groups;      // wave groups per workgroup the plan asks for (MFMA path)
@@ -29,9 +29,7 @@ struct MsaArgs {
 };
 
 // A sequence of L cached tokens has active_splits(L) splits; every sequence has at least one (it
-// also scans the step's new keys).  The fp32 kernel gives split s the tokens
-// [s*split_keys, min(L,(s+1)*split_keys)); the MFMA kernel divides the prefix among the same number
-// of splits in 32-token units, with a smaller share for the last one.
+// also scans the step's new keys).  Split s takes the tokens [s*split_keys, min(L,(s+1)*split_keys)).
 SS_DEV int clamp_len(int L, const MsaArgs& a) { return min(max(L, 0), a.max_pages * a.page); }
 SS_DEV int active_splits(int L, const MsaArgs& a) { return max(1, (L + a.split_keys - 1) / a.split_keys); }
 

@@ -265,8 +265,20 @@ static MsaPlan make_plan(int B, int R, int H, int Hkv, int D, int max_len, int d
     const int n_cap = len / 256 < 1 ? 1 : len / 256;
     if (n > n_cap) n = n_cap;
     split_keys = ceil_div(len, n);
+    if (dtype == SS_BF16 && n > 1) {
+      // The last split also scans the step's own rows (about ceil(R/32) + 2 blocks' worth of work), so
+      // the others take a little more than an equal share of the prefix; whole iterations of all wave
+      // groups where that still leaves the last split something.
+      const int nu = ceil_div(len, 32), extra = ceil_div(R, 32) + 2;
+      int per = (nu + extra + n / 2) / n;
+      const int whole = ceil_div(per, p.groups) * p.groups;
+      if ((n - 1) * whole < nu) per = whole;
+      while (per > 1 && (n - 1) * per >= nu) --per;
+      split_keys = per * 32;
+    }
   }
-  split_keys = (int)align_up((size_t)(split_keys < 64 ? 64 : split_keys), 64);
+  const int unit = dtype == SS_BF16 ? 32 : 64;  // the MFMA kernel works in 32-key blocks, the fp32 kernel in 64-key tiles
+  split_keys = (int)align_up((size_t)(split_keys < 64 ? 64 : split_keys), unit);
   p.split_keys = split_keys;
   p.n_splits = ceil_div(len, split_keys);
   if (p.n_splits > 1) {

@@ -114,7 +114,7 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
   float* ml = reinterpret_cast<float*>(anc + SS_MAX_T);  // [n_groups][NW][2][16]: max, sum per query
 
 #ifdef SS_MSA_TIMING
-  const long long t_entry = clock64();
+  const long long t_entry = clock64(), r_entry = wall_clock64();
 #endif
   // ---- which piece of work: XCD-aware order.  Workgroup ids go round-robin over
   // the 8 XCDs, so ids that are equal mod 8 share an L2: the query chunks of one
@@ -134,21 +134,11 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int grp = w / NW, wt = w % NW;  // wave group, query tile of this wave
   const int R = a.R, T = a.T, F = a.g * R;
-  const int L = clamp_len(a.seq_lens[b], a);
-  const int n_active = active_splits(L, a);
-  if (s >= n_active) return;
-  const bool is_last = (s == n_active - 1);
-  // Key range of this split, in 32-key units.  The last active split also takes the step's own rows
-  // (and the tree work that goes with them), so it is given that much less of the prefix.
-  int k0, k1;
-  {
-    const int nu = (L + 31) >> 5, extra = ((R + 31) >> 5) + 2;
-    int per = (nu + extra + n_active / 2) / n_active;
-    if (per < 1) per = 1;
-    while (per > 1 && (n_active - 1) * per >= nu) --per;
-    k0 = min(s * per * 32, L);
-    k1 = is_last ? L : min((s + 1) * per * 32, L);
-  }
+  // Cached tokens [k0, k0 + split_keys) clipped to the sequence; the plan made the splits a little
+  // longer than an equal share, so that the last one, which also scans the step's own rows, has less
+  // of the prefix.  Nothing up to the first loads depends on the sequence length (it is fetched in
+  // parallel with them): page ids and the first block are fetched from clamped, always valid positions.
+  const int k0 = s * a.split_keys;
   const float c = a.scale_log2;
 
   const uint16_t* q = (const uint16_t*)a.q;
@@ -160,37 +150,21 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
   const uint16_t* v_head = (const uint16_t*)a.v_cache + (size_t)hk * a.page * D;
   const int pmask = a.page - 1;
 
-  // ---- units of this split: full 32-key blocks of the prefix, its ragged last block, blocks of
-  // the step's own rows (last split only).  The first n_main * n_groups full blocks go through the
-  // pipelined main loop, n_main per group; whatever is left is handled one by one afterwards.
-  const int n_full = (k1 - k0) >> 5;
-  const int tail = (k1 - k0) & 31;
-  const int n_prefix_units = n_full + (tail ? 1 : 0);
-  const int n_units = n_prefix_units + (is_last ? (R + 31) >> 5 : 0);
-  const int n_main = n_full / n_groups;
   unsigned char* my_stages = stages + (size_t)grp * 2 * STAGE_BYTES;
 
   // Physical pages of the two 16-key halves of this group's main-loop units (equal for pages of 32
-  // or 64 tokens).  Lane i of every wave keeps the pair for loop iteration jbase + i; one gather
+  // or 64 tokens; positions past the table are clamped, such units are never used).  Lane i of every wave keeps the pair for loop iteration jbase + i; one gather
   // serves 64 iterations and a page id reaches the scalar unit through a lane read, so that no
   // memory wait sits between issuing a unit's loads and computing on the previous unit.
   int tab_a = 0, tab_b = 0;
+  const int key_cap = max(a.max_pages * a.page - 32, 0) & ~31;  // last 32-key block the table covers
   auto refill_pages = [&](int jbase) {
-    if (n_main > 0) {
-      const int uu = grp + min(jbase + lane, n_main - 1) * n_groups;
-      const int kb = k0 + 32 * uu;
-      tab_a = min(max(my_table[kb >> a.page_shift], 0), a.num_pages - 1);
-      tab_b = min(max(my_table[(kb + 16) >> a.page_shift], 0), a.num_pages - 1);
-    }
+    const int kb = min(k0 + 32 * (grp + (jbase + lane) * n_groups), key_cap);
+    tab_a = min(max(my_table[kb >> a.page_shift], 0), a.num_pages - 1);
+    tab_b = min(max(my_table[(kb + 16) >> a.page_shift], 0), a.num_pages - 1);
   };
   refill_pages(0);
-  // The tree's ancestor sets go to LDS now, while the first loads are in flight; only the split that
-  // scans the step's own rows needs them.
-  if (is_last) {
-    if (tid < T) par[tid] = clamp_parent(a.parent[(size_t)b * T + tid], tid);
-    __syncthreads();
-    compute_anc(par, T, anc, tid);
-  }
+  const int par_v = tid < T ? clamp_parent(a.parent[(size_t)b * T + tid], tid) : 0;
 
   // ---- this wave's query tile: MFMA B operands (lane (lq, lg) holds features 8*(4*ks+lg).. of
   // folded query row f)
@@ -267,6 +241,31 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
     for (int j = 0; j < KJ; ++j) *reinterpret_cast<uintx4*>(st + v_ldst[j]) = stg[KJ + j];
   };
 
+  // ---- main loop over full blocks of the prefix: while a group computes on one LDS stage, its waves
+  // hold the next unit in registers (loads issued at the top), write it to the other stage after the
+  // compute, and one barrier per unit publishes it.
+  const RowVis no_vis = RowVis{0, 0, 0};
+  // ---- prologue.  First block of this group on its way (harmless if it turns out not to exist);
+  // the tree's ancestor sets into LDS meanwhile; then the sequence length decides what there is to do.
+  if (loader) load_main(grp, __builtin_amdgcn_readlane(tab_a, 0), __builtin_amdgcn_readlane(tab_b, 0));
+  if (tid < T) par[tid] = par_v;
+  __syncthreads();
+  compute_anc(par, T, anc, tid);
+
+  const int L = clamp_len(a.seq_lens[b], a);
+  const int n_active = active_splits(L, a);
+  if (s >= n_active) return;
+  const bool is_last = (s == n_active - 1);
+  const int k1 = max(k0, min(L, k0 + a.split_keys));
+  // Units of this split: full 32-key blocks of the prefix, its ragged last block, blocks of the step's
+  // own rows (last split only).  The full blocks go through the pipelined main loop, n_main iterations
+  // with one block per group (in the last iteration some groups may have none); the ragged block and
+  // the step's own rows are handled afterwards.
+  const int n_full = (k1 - k0) >> 5;
+  const int tail = (k1 - k0) & 31;
+  const int n_prefix_units = n_full + (tail ? 1 : 0);
+  const int n_units = n_prefix_units + (is_last ? (R + 31) >> 5 : 0);
+  const int n_main = (n_full + n_groups - 1) / n_groups;
 #ifdef SS_MSA_TIMING
   long long tacc[8] = {0, 0, 0, 0, 0, 0, 0, 0}, t_last = 0;
 #endif
@@ -370,14 +369,7 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
     }
   };
 
-  // ---- main loop over full blocks of the prefix: while a group computes on one LDS stage, its waves
-  // hold the next unit in registers (loads issued at the top), write it to the other stage after the
-  // compute, and one barrier per unit publishes it.
-  const RowVis no_vis = RowVis{0, 0, 0};
-  if (n_main > 0 && loader) {
-    load_main(grp, __builtin_amdgcn_readlane(tab_a, 0), __builtin_amdgcn_readlane(tab_b, 0));
-    store_main(my_stages);
-  }
+  if (n_main > 0 && loader) store_main(my_stages);
   __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): nothing from the prologue (Q, page ids) is pending inside the loop
   __syncthreads();
 #ifdef SS_MSA_TIMING
@@ -400,10 +392,7 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
     __syncthreads();  // the next stage is complete, this one may be overwritten after the next barrier
     SS_T(5);
   }
-  if (n_main > 0) {
-    compute(std::true_type{}, grp + (n_main - 1) * n_groups, my_stages + ((n_main - 1) & 1) * STAGE_BYTES, no_vis);
-    __syncthreads();  // the stages are free for what follows
-  }
+  // (the last main-loop unit is computed below, with the first of the remaining units already in flight)
 #ifdef SS_MSA_TIMING
   if (lane == 0 && blockIdx.x < 1024) {
     long long* dbg = (long long*)a.part_lse + 1000000 + (blockIdx.x * 16 + w) * 16;
@@ -417,14 +406,13 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
   }
 #endif
 
-  // ---- the remaining units (leftover full blocks, the ragged block, the step's own rows), pipelined
+  // ---- the remaining units (the ragged block, the step's own rows), pipelined
   // the same way.  Addresses are per lane here, clamped to existing keys / rows; what is read in
   // excess is masked.  The lane id is laundered wherever addresses are formed, so that none of this
   // arithmetic is kept in registers across the loops.
-  const int u_odd0 = n_main * n_groups;
+  const int u_odd0 = n_full;
   const int n_odd_iter = (n_units - u_odd0 + n_groups - 1) / n_groups;
-  if (n_odd_iter > 0) {
-    const RowVis vis = is_last ? make_row_vis(q_r, T, a.gamma, anc, (a.flags & SS_STREAM_EXCLUDE_SELF) != 0) : no_vis;
+  {
     auto load_odd = [&](int u) {
       int lane2 = lane;
       asm volatile("" : "+v"(lane2));
@@ -473,17 +461,24 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
         }
       }
     };
-    if (loader && u_odd0 + grp < n_units) {
-      load_odd(u_odd0 + grp);
-      store_odd(u_odd0 + grp, my_stages);
+    const bool odd_first = loader && u_odd0 + grp < n_units;
+    if (odd_first) load_odd(u_odd0 + grp);  // in flight while the last main-loop unit is computed
+    if (n_main > 0) {
+      const int u_last = grp + (n_main - 1) * n_groups;
+      if (u_last < n_full) compute(std::true_type{}, u_last, my_stages + ((n_main - 1) & 1) * STAGE_BYTES, no_vis);
+      __syncthreads();  // the stages are free for what follows
     }
-    __syncthreads();
-    for (int jo = 0; jo < n_odd_iter; ++jo) {
-      const int u = u_odd0 + jo * n_groups + grp, un = u + n_groups;
-      if (loader && un < n_units) load_odd(un);
-      if (u < n_units) compute(std::false_type{}, u, my_stages + (jo & 1) * STAGE_BYTES, vis);
-      if (loader && un < n_units) store_odd(un, my_stages + ((jo + 1) & 1) * STAGE_BYTES);
+    if (n_odd_iter > 0) {
+      const RowVis vis = is_last ? make_row_vis(q_r, T, a.gamma, anc, (a.flags & SS_STREAM_EXCLUDE_SELF) != 0) : no_vis;
+      if (odd_first) store_odd(u_odd0 + grp, my_stages);
       __syncthreads();
+      for (int jo = 0; jo < n_odd_iter; ++jo) {
+        const int u = u_odd0 + jo * n_groups + grp, un = u + n_groups;
+        if (loader && un < n_units) load_odd(un);
+        if (u < n_units) compute(std::false_type{}, u, my_stages + (jo & 1) * STAGE_BYTES, vis);
+        if (loader && un < n_units) store_odd(un, my_stages + ((jo + 1) & 1) * STAGE_BYTES);
+        __syncthreads();
+      }
     }
   }
 
@@ -545,6 +540,7 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
     long long* dbg = (long long*)a.part_lse + 1000000 + (blockIdx.x * 16 + w) * 16;
     dbg[12] = clock64();
     dbg[13] = t_odd;
+    dbg[14] = wall_clock64() - r_entry;
   }
 #endif
 }
