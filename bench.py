@@ -33,9 +33,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, vendor figure
 
 # HBM traffic of one launch of the MSA kernel, from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE; KiB
 # per dispatch), each scaled by what the same counter reads for the 256 MiB device copy of --calibrate-copy
-# (FETCH_SIZE reads half of the bytes the copy fetches: factor 2.0; WRITE_SIZE factor 1.0).  c4: 139727 KiB
-# x 2.0 fetched + 23680 KiB written (the fp32 split partials).  Summaries are under profiles/.
-MSA_TRAFFIC_BYTES = {"c4": int((139727.2 * 2.0 + 23680.0) * 1024), "c2": None, "c3": None, "c5": None}
+# (FETCH_SIZE reads half of the bytes the copy fetches: factor 2.0; WRITE_SIZE factor 1.0).  c4: 136309 KiB
+# x 2.0 fetched + 12720 KiB written (the fp32 partials of the two splits).  Summaries are under profiles/.
+MSA_TRAFFIC_BYTES = {"c4": int((136309.0 * 2.0 + 12720.0) * 1024), "c2": None, "c3": None, "c5": None}
 
 
 def msa_bytes(cfg, seq_lens):
@@ -237,11 +237,19 @@ def main():
     kern = {"msa_call_us": round(us_msa_call, 2), "msa_kernel_us": round(us_msa_kernel, 2)}
     b_msa = msa_bytes(cfg, seq_lens)
     f_msa = msa_flops(cfg, seq_lens)
-    achieved = b_msa / (us_msa_kernel * 1e-6) / 1e9
-    roofline = {"kernel": "msa_bf16_kernel", "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                "traffic": MSA_TRAFFIC_BYTES.get(args.workload), "algorithmic_bytes": b_msa,
-                "mfma_tflops": round(f_msa / (us_msa_kernel * 1e-6) / 1e12, 1)}
+    gbps = b_msa / (us_msa_kernel * 1e-6) / 1e9
+    tflops = f_msa / (us_msa_kernel * 1e-6) / 1e12
+    # Which roofline binds the kernel on this workload: the matrix cores if its FLOP per byte exceed the
+    # machine's ridge (long GQA trees: c5), HBM otherwise.  Both figures are reported either way.
+    if f_msa / b_msa > MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBPS * 1e9):
+        roofline = {"kernel": "msa_bf16_kernel", "bound": "mfma", "achieved": round(tflops, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
+                    "unit": "TFLOP/s", "frac": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4),
+                    "traffic": MSA_TRAFFIC_BYTES.get(args.workload), "algorithmic_flops": f_msa, "hbm_gbps": round(gbps, 1)}
+    else:
+        roofline = {"kernel": "msa_bf16_kernel", "bound": "hbm", "achieved": round(gbps, 1), "peak": HBM_PEAK_GBPS,
+                    "unit": "GB/s", "frac": round(gbps / HBM_PEAK_GBPS, 4),
+                    "traffic": MSA_TRAFFIC_BYTES.get(args.workload), "algorithmic_bytes": b_msa,
+                    "mfma_tflops": round(tflops, 1)}
     extra = {}
     if has_lm:
         hidden = outs[-1].view(N, cfg.d_model)

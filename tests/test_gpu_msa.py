@@ -96,7 +96,7 @@ def test_bf16_ragged_lengths(lens):
 
 
 @pytest.mark.parametrize("page", [16, 32, 64])
-@pytest.mark.parametrize("split", [0, 128, 384, 8192])
+@pytest.mark.parametrize("split", [0, 96, 128, 384, 736, 8192])
 def test_bf16_pages_and_splits(page, split):
     cfg = synth.scaled(synth.CONFIGS["c2"], B=3, H=4, Hkv=4, L_min=500, L_max=1500, page=page)
     _check(cfg, 6, split=split)
