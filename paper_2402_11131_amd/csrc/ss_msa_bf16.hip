@@ -541,6 +541,7 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
     dbg[12] = clock64();
     dbg[13] = t_odd;
     dbg[14] = wall_clock64() - r_entry;
+    dbg[15] = r_entry;
   }
 #endif
 }
