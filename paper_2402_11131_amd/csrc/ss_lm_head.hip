@@ -134,7 +134,7 @@ __global__ __launch_bounds__(256) void lm_head_f32_kernel(LmArgs a) {
 // lines with 32 contiguous bytes each.  Four blocks are in flight per wave (the
 // ring is filled three blocks ahead of use): 12 KB per wave against the HBM
 // latency, with one wave per SIMD.  `hidden` is shared by the waves and goes
-// through LDS: three buffers of 64*RT rows x 128 bytes, filled two blocks ahead
+// through LDS: four buffers of 64*RT rows x 128 bytes, filled three blocks ahead
 // by direct global->LDS loads (no staging registers and, more important, no
 // ds_write: LDS stores of this size run at a quarter of the read rate).  Such a
 // load writes lane l's 16 bytes to (base + 16*l), so the LDS image is row-major;
@@ -205,7 +205,7 @@ __global__ __launch_bounds__(256, 1) void lm_head_bf16_kernel(LmArgs a) {
   constexpr int NRT = 2 * RT;    // 32-row accumulator tiles per wave
   constexpr int HB = ROWS * 128; // bytes of one block of `hidden` in LDS
   constexpr int HL = 2 * RT;     // 16-byte chunks of it per thread
-  extern __shared__ __attribute__((aligned(16))) unsigned char hbuf[];  // [3][HB], reused by the epilogue
+  extern __shared__ __attribute__((aligned(16))) unsigned char hbuf[];  // [4][HB], reused by the epilogue
 #ifdef SS_LM_TIMING
   const long long t_entry = clock64();
 #endif
@@ -253,28 +253,32 @@ __global__ __launch_bounds__(256, 1) void lm_head_bf16_kernel(LmArgs a) {
     for (int i = 0; i < HL; ++i) load_to_lds16(base, h_voff[i], lds0 + buf * HB + (w + 4 * i) * 1024);
   };
 
-  // prologue: hidden blocks 0, 1 and W blocks 0..2 on their way; block 0 of hidden has to be there
+  // prologue: hidden blocks 0..2 in LDS, W blocks 0..2 on their way
   constexpr int WAIT_ALL = 0x0F70;  // s_waitcnt vmcnt(0)
   // loads that may be in flight at the end of a step: its own HL + 4 and the 4 W loads of the step before
   constexpr int PENDING = HL + 8;
   constexpr int WAIT_STEP = 0x0F70 | (PENDING & 15) | ((PENDING >> 4) << 14);  // s_waitcnt vmcnt(PENDING)
   load_h(0, 0);
   load_h(min(1, n_k - 1), 1);
+  load_h(min(2, n_k - 1), 2);
   load_w(0, wq[0]);
   load_w(min(1, n_k - 1), wq[1]);
   load_w(min(2, n_k - 1), wq[2]);
   __builtin_amdgcn_s_waitcnt(WAIT_ALL);
   __syncthreads();
 
-  // Block J: W from ring slot J % 4, hidden from LDS buffer J % 3.  A step starts hidden block J+2
-  // (into the buffer block J-1 was read from: every wave passed the previous barrier since) and W
-  // block J+3 (into the slot block J-1 left).  Past the end the last block is fetched again instead,
-  // which keeps the steps free of conditions (a condition around the MFMAs would cost a register copy
-  // per accumulator).
+  // Block J: W from ring slot J % 4, hidden from LDS buffer J % 4.  At the start of step J the buffers
+  // of blocks J and J+1 are complete (published by the previous barrier): the operand reads of a step's
+  // first MFMA round are issued during the last round of the step before, so that no LDS latency is
+  // exposed after the barrier.  A step starts hidden block J+3 (into the buffer block J-1 was read
+  // from: every wave passed the previous barrier since) and W block J+3 (into the slot block J-1
+  // left), and ends when hidden block J+2 has landed.  Past the end the last block is fetched again
+  // instead, which keeps the steps free of conditions (a condition around the MFMAs would cost a
+  // register copy per accumulator).
   // A step is four MFMA rounds (16 features each, 2*RT MFMAs).  The L1 takes a load instruction of a
   // wave only every ~18 cycles and the four waves share it, so the step's loads are dealt to the
   // rounds and, inside a round, placed between the MFMAs (scheduling groups) instead of stalling the
-  // wave in a burst.  The operand reads of round c+1 are issued in round c.
+  // wave in a burst.  The operand reads of a round are issued in the round before.
   int buf = 0;
 #ifdef SS_LM_TIMING
   long long tacc[4] = {0, 0, 0, 0}, t_last = clock64();
@@ -282,25 +286,24 @@ __global__ __launch_bounds__(256, 1) void lm_head_bf16_kernel(LmArgs a) {
 #else
 #define SS_LT(i)
 #endif
+  bf16x8 hop[2][NRT];  // hidden operands of the current and of the next round
+#pragma unroll
+  for (int rt = 0; rt < NRT; ++rt)
+    hop[0][rt] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(hbuf + hrd[0] + rt * (32 * 128)));
   auto step = [&](int J, uintx4 (&w_now)[4], uintx4 (&w_next)[4]) {
     const unsigned char* hb = hbuf + buf * HB;
-    const int Jh = min(J + 2, n_k - 1), Jw = min(J + 3, n_k - 1);
-    const unsigned char* h_base = (const unsigned char*)a.hidden + (size_t)Jh * 128;
-    const unsigned char* w_base = (const unsigned char*)a.W + (size_t)Jw * 128;
-    const uint32_t h_dst = lds0 + (buf == 0 ? 2 : buf - 1) * HB + w * 1024;  // buffer (J + 2) % 3
-    bf16x8 hop[2][NRT];
-#pragma unroll
-    for (int rt = 0; rt < NRT; ++rt)
-      hop[0][rt] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(hb + hrd[0] + rt * (32 * 128)));
+    const unsigned char* hb_next = hbuf + ((buf + 1) & 3) * HB;
+    const int Jn = min(J + 3, n_k - 1);
+    const unsigned char* h_base = (const unsigned char*)a.hidden + (size_t)Jn * 128;
+    const unsigned char* w_base = (const unsigned char*)a.W + (size_t)Jn * 128;
+    const uint32_t h_dst = lds0 + ((buf + 3) & 3) * HB + w * 1024;  // buffer (J + 3) % 4
     constexpr int NLD = HL + 4;  // global loads of the step: hidden first, then W
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-      if (c < 3) {
+      const unsigned char* src = c < 3 ? hb + hrd[c + 1] : hb_next + hrd[0];
 #pragma unroll
-        for (int rt = 0; rt < NRT; ++rt)
-          hop[(c + 1) & 1][rt] =
-              __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(hb + hrd[c + 1] + rt * (32 * 128)));
-      }
+      for (int rt = 0; rt < NRT; ++rt)
+        hop[(c + 1) & 1][rt] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(src + rt * (32 * 128)));
       int n_w = 0;
 #pragma unroll
       for (int l = (c * NLD) / 4; l < ((c + 1) * NLD) / 4; ++l) {
@@ -315,18 +318,17 @@ __global__ __launch_bounds__(256, 1) void lm_head_bf16_kernel(LmArgs a) {
 #pragma unroll
       for (int rt = 0; rt < NRT; ++rt)
         acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wop, hop[c & 1][rt], acc[rt], 0, 0, 0);
-      if (c == 0) __builtin_amdgcn_sched_group_barrier(0x100, NRT, 0);   // round 0: its own operand reads first
 #pragma unroll
       for (int i = 0; i < NRT; ++i) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                // MFMA
-        if (c < 3) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);    // one operand read of the next round
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                // one operand read of the next round
         if (i < n_w) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // global load
       }
       __builtin_amdgcn_sched_barrier(0);
     }
-    buf = buf == 2 ? 0 : buf + 1;
+    buf = (buf + 1) & 3;
     SS_LT(1);
-    __builtin_amdgcn_s_waitcnt(WAIT_STEP);  // hidden block J+1 has landed (and W block J+1)
+    __builtin_amdgcn_s_waitcnt(WAIT_STEP);  // hidden block J+2 has landed (and W block J+1)
     __syncthreads();
     SS_LT(3);
   };
@@ -443,7 +445,7 @@ __global__ __launch_bounds__(64) void lm_head_reduce_kernel(LmArgs a) {
 template <int RT, int KT>
 static int launch_lm_bf16_rk(dim3 grid, hipStream_t st, const LmArgs& a) {
   auto kern = lm_head_bf16_kernel<RT, KT>;
-  const size_t lds = 3 * (size_t)(64 * RT) * 128;
+  const size_t lds = 4 * (size_t)(64 * RT) * 128;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
