@@ -163,3 +163,19 @@ def tree_draft(stream_topk, last, bonus, tmpl_parent, tmpl_rank):
     _load().ora_tree_draft(_p(tk), ctypes.c_long(T * gamma * K), K, _p(last), _p(bonus), _p(tp),
                            _p(tr), B, T, gamma, T2, _p(next_tok), _p(next_parent))
     return next_tok, next_parent
+
+
+def kv_commit(k_new, v_new, k_cache, v_cache, block_table, seq_lens, path, n_accept):
+    """n3.  Appends the main-row keys/values of the accepted path (path [B,max_depth+1], n_accept [B]
+    as verification returns them) to copies of the caches.  Returns (k_cache, v_cache, new_seq_lens)."""
+    k_new, v_new = _f32(k_new), _f32(v_new)
+    kc, vc = _f32(k_cache).copy(), _f32(v_cache).copy()
+    bt, sl, path, na = _i32(block_table), _i32(seq_lens), _i32(path), _i32(n_accept)
+    B, R, Hkv, D = k_new.shape
+    P, _, page, _ = kc.shape
+    assert v_new.shape == k_new.shape and vc.shape == (P, Hkv, D, page)
+    assert bt.shape[0] == B and sl.shape == (B,) and na.shape == (B,) and path.shape[0] == B
+    new_lens = np.zeros(B, np.int32)
+    _load().ora_kv_commit(_p(k_new), _p(v_new), _p(kc), _p(vc), _p(bt), bt.shape[1], _p(sl), _p(path), _p(na),
+                          B, R, Hkv, D, page, path.shape[1] - 1, _p(new_lens))
+    return kc, vc, new_lens

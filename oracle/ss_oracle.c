@@ -337,3 +337,36 @@ void ora_tree_draft(const int32_t* stream_topk, long batch_stride, int K, const 
   if (next_parent)
     for (int i = 0; i < T2; i++) next_parent[i] = (i == 0) ? -1 : ora_parent(tmpl_parent, i);
 }
+
+/*
+ * n3: KV-cache commit.  Main-stream keys/values are cached, those of the speculative streams never
+ * are (Sec. 3.2.1), and the cache is trimmed back to what was accepted after each generation step
+ * (Appendix A.1): of the step's own rows only the main rows of the accepted path stay, appended in
+ * path order behind the L cached tokens.  Caches are updated in place; new_len = L + n_accept + 1.
+ * Layouts as in a2: k_cache [P][Hkv][page][D], v_cache [P][Hkv][D][page], k_new/v_new [B][R][Hkv][D].
+ * A position past the block table's capacity is dropped.
+ */
+void ora_kv_commit(const float* k_new, const float* v_new, float* k_cache, float* v_cache,
+                   const int32_t* block_table, int max_pages, const int32_t* seq_lens, const int32_t* path,
+                   const int32_t* n_accept, int B, int R, int Hkv, int D, int page, int max_depth,
+                   int32_t* new_lens) {
+  for (int b = 0; b < B; b++) {
+    int L = seq_lens[b];
+    int kept = 0;
+    for (int j = 0; j <= n_accept[b] && j <= max_depth; j++) {
+      int node = path[(size_t)b * (max_depth + 1) + j];
+      int pos = L + j;
+      if (pos >= max_pages * page) break;
+      int pg = block_table[(size_t)b * max_pages + pos / page], slot = pos % page;
+      for (int h = 0; h < Hkv; h++)
+        for (int d = 0; d < D; d++) {
+          size_t src = (((size_t)b * R + node) * Hkv + h) * D + d;
+          k_cache[(((size_t)pg * Hkv + h) * page + slot) * D + d] = k_new[src];
+          v_cache[(((size_t)pg * Hkv + h) * D + d) * page + slot] = v_new[src];
+        }
+      kept++;
+    }
+    if (new_lens) new_lens[b] = L + kept;
+  }
+}
+
