@@ -261,7 +261,15 @@ def main():
         us_draft = timed(lambda i: api.ss_tree_draft(idx, cfg.K, ver["last"], ver["bonus"], cfg.T, cfg.gamma,
                                                      branching=cfg.draft_branching, batch_stride=cfg.R * cfg.K,
                                                      offset=cfg.T * cfg.K), it, torch)
-        kern.update({"lm_head_call_us": round(us_lm, 2), "verify_us": round(us_ver, 2), "draft_us": round(us_draft, 2)})
+        # KV-cache commit of the accepted path (the row after the hot path: not part of `value`), all layers
+        cap = layers[0]["block_table"].shape[1] * cfg.page
+        short = torch.clamp(layers[0]["seq_lens"], max=cap - cfg.max_depth - 1)
+        new_lens = torch.empty_like(short)
+        us_commit = timed(lambda i: [api.ss_kv_commit(l["k_new"], l["v_new"], l["k_cache"], l["v_cache"], l["block_table"], short,
+                                                       ver["path"], ver["n_accept"], cfg.gamma, new_seq_lens=new_lens)
+                                     for l in layers[:cfg.n_layers]], it, torch)
+        kern.update({"lm_head_call_us": round(us_lm, 2), "verify_us": round(us_ver, 2), "draft_us": round(us_draft, 2),
+                     "kv_commit_all_layers_us": round(us_commit, 2)})
         f_lm = 2.0 * N * cfg.vocab * cfg.d_model
         tf = f_lm / (us_lm * 1e-6) / 1e12
         extra["roofline_lm_head"] = {"kernel": "lm_head_bf16_kernel + reduce", "bound": "mfma", "achieved": round(tf, 1),

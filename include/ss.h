@@ -227,6 +227,34 @@ int ss_tree_draft(const int32_t* stream_topk, long topk_batch_stride, int K, con
 int ss_full_tree_template_host(const int32_t* branching, int gamma, int capacity,
                                int32_t* parent_out, int32_t* rank_out, int32_t* depth_out);
 
+/*
+ * n3. KV-cache commit after verification (Sec. 3.2.1: main-stream keys/values
+ * are cached, those of the speculative streams never are; Appendix A.1: the
+ * cache is backtracked lazily after each generation step).  Of the step's own
+ * rows only the main rows of the accepted path stay: the key/value row of node
+ * path[b][j], j = 0..n_accept[b], is appended at position seq_lens[b] + j of
+ * sequence b's paged cache; everything else of k_new/v_new is dropped.  One call
+ * per layer (each layer has its own caches and its own k_new/v_new).
+ *
+ *  k_new, v_new [B,R,Hkv,D] in (row order as above, R = T*(1+gamma)).
+ *  k_cache [num_pages,Hkv,page_size,D], v_cache [num_pages,Hkv,D,page_size]
+ *          in/out, layouts as in a2.
+ *  block_table [B,max_pages_per_seq], seq_lens [B] in.  The table must map the
+ *          positions that are written; a position at or past
+ *          max_pages_per_seq*page_size is dropped (with all that follow it).
+ *  path [B,max_depth+1], n_accept [B] in: as ss_tree_verify returns them.
+ *  new_seq_lens [B] int32 out, or NULL: seq_lens[b] + number of rows appended
+ *          (n_accept[b] + 1 unless the table's capacity cut it).  Must not be
+ *          the seq_lens array itself.
+ * Node ids outside [0,T), page ids outside [0,num_pages) and n_accept outside
+ * [0,max_depth] are clamped into range.
+ */
+int ss_kv_commit(const void* k_new, const void* v_new, void* k_cache, void* v_cache,
+                 const int32_t* block_table, int max_pages_per_seq, int num_pages,
+                 const int32_t* seq_lens, const int32_t* path, const int32_t* n_accept, int B, int T,
+                 int gamma, int Hkv, int D, int page_size, int max_depth, int dtype,
+                 int32_t* new_seq_lens, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

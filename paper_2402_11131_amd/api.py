@@ -27,7 +27,7 @@ SS_MAX_T, SS_MAX_GAMMA, SS_MAX_K = 64, 8, 8
 EXPORTS = (
     "ss_version", "ss_last_error", "ss_check_tree_host", "ss_build_mask", "ss_msa_workspace_bytes",
     "ss_msa_attention", "ss_msa_set_split_keys", "ss_lm_head_workspace_bytes", "ss_lm_head_argmax_topk",
-    "ss_tree_verify", "ss_tree_draft", "ss_full_tree_template_host",
+    "ss_tree_verify", "ss_tree_draft", "ss_full_tree_template_host", "ss_kv_commit",
 )
 
 _lib = None
@@ -66,6 +66,7 @@ def load_library() -> ctypes.CDLL:
     lib.ss_tree_verify.argtypes = [vp, vp, vp, lng, lng, i32, i32, i32, vp, vp, vp, vp, vp, vp]
     lib.ss_tree_draft.argtypes = [vp, lng, i32, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, vp]
     lib.ss_full_tree_template_host.argtypes = [vp, i32, i32, vp, vp, vp]
+    lib.ss_kv_commit.argtypes = [vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp, vp]
     for name in EXPORTS:
         getattr(lib, name)
     _lib = lib
@@ -267,3 +268,32 @@ def ss_tree_draft(stream_topk, K: int, last, bonus, T: int, gamma: int, tmpl_par
                              None if tmpl_rank is None else _dev(tmpl_rank, i32, "tmpl_rank"), br_ptr, B, T, gamma,
                              T2, next_tok.data_ptr(), next_parent.data_ptr(), _stream()))
     return next_tok, next_parent
+
+
+def ss_kv_commit(k_new, v_new, k_cache, v_cache, block_table, seq_lens, path, n_accept, gamma: int,
+                 new_seq_lens: Optional[torch.Tensor] = None, want_lens: bool = True):
+    """n3.  Appends the main-row keys/values of the accepted path (path [B,max_depth+1], n_accept [B] from
+    ss_tree_verify) to the paged caches IN PLACE.  Returns new_seq_lens [B] int32 (None if want_lens is False
+    and no tensor was given)."""
+    lib = load_library()
+    code = _dtype_code(k_new)
+    dt = k_new.dtype
+    B, R, Hkv, D = k_new.shape
+    P, _, page, _ = k_cache.shape
+    if R % (1 + gamma):
+        raise ValueError("k_new has %d rows, not a multiple of 1+gamma" % R)
+    T = R // (1 + gamma)
+    if tuple(v_new.shape) != (B, R, Hkv, D) or tuple(k_cache.shape) != (P, Hkv, page, D) or tuple(v_cache.shape) != (P, Hkv, D, page):
+        raise ValueError("k_new/v_new must be [B,R,Hkv,D], k_cache [P,Hkv,page,D], v_cache [P,Hkv,D,page]")
+    if block_table.shape[0] != B or tuple(seq_lens.shape) != (B,) or path.shape[0] != B or tuple(n_accept.shape) != (B,):
+        raise ValueError("block_table / seq_lens / path / n_accept batch size mismatch")
+    i32 = torch.int32
+    if new_seq_lens is None and want_lens:
+        new_seq_lens = torch.empty(B, dtype=i32, device=k_new.device)
+    _check(lib.ss_kv_commit(_dev(k_new, dt, "k_new"), _dev(v_new, dt, "v_new"), _dev(k_cache, dt, "k_cache"),
+                            _dev(v_cache, dt, "v_cache"), _dev(block_table, i32, "block_table"), block_table.shape[1], P,
+                            _dev(seq_lens, i32, "seq_lens"), _dev(path, i32, "path"), _dev(n_accept, i32, "n_accept"),
+                            B, T, gamma, Hkv, D, page, path.shape[1] - 1, code,
+                            None if new_seq_lens is None else _dev(new_seq_lens, i32, "new_seq_lens"), _stream()))
+    return new_seq_lens
+

@@ -1,0 +1,85 @@
+// n3: KV-cache commit after verification (Sec. 3.2.1, Appendix A.1).  Of the step's own rows only the
+// main rows of the accepted path are appended to the paged cache; stream rows and rejected nodes are
+// dropped.  A few KB per sequence: one workgroup per (sequence, path position), pure copies.
+#include "ss_common.h"
+
+namespace ss {
+
+struct KvArgs {
+  const void* k_new;
+  const void* v_new;
+  void* k_cache;
+  void* v_cache;
+  const int32_t* block_table;
+  const int32_t* seq_lens;
+  const int32_t* path;
+  const int32_t* n_accept;
+  int32_t* new_seq_lens;
+  int B, T, R, Hkv, D, page, page_shift, max_pages, num_pages, max_depth;
+};
+
+// E = element type of the tensors as an unsigned integer of the same size (the copy is bit-exact).
+template <typename E>
+__global__ __launch_bounds__(256) void kv_commit_kernel(KvArgs a) {
+  const int b = blockIdx.x / (a.max_depth + 1), j = blockIdx.x % (a.max_depth + 1);
+  const int cap = a.max_pages * a.page;
+  const int L = min(max(a.seq_lens[b], 0), cap);
+  const int n_acc = min(max(a.n_accept[b], 0), a.max_depth);
+  if (j == 0 && threadIdx.x == 0 && a.new_seq_lens) a.new_seq_lens[b] = min(L + n_acc + 1, cap);
+  const int pos = L + j;
+  if (j > n_acc || pos >= cap) return;
+  const int node = min(max(a.path[(size_t)b * (a.max_depth + 1) + j], 0), a.T - 1);
+  const int pg = min(max(a.block_table[(size_t)b * a.max_pages + (pos >> a.page_shift)], 0), a.num_pages - 1);
+  const int slot = pos & (a.page - 1);
+  const E* ks = (const E*)a.k_new + ((size_t)b * a.R + node) * a.Hkv * a.D;
+  const E* vs = (const E*)a.v_new + ((size_t)b * a.R + node) * a.Hkv * a.D;
+  E* kd = (E*)a.k_cache + (size_t)pg * a.Hkv * a.page * a.D + (size_t)slot * a.D;  // + h*page*D + d
+  E* vd = (E*)a.v_cache + (size_t)pg * a.Hkv * a.D * a.page + slot;                // + (h*D + d)*page
+  for (int e = threadIdx.x; e < a.Hkv * a.D; e += 256) {
+    const int h = e / a.D, d = e % a.D;
+    kd[(size_t)h * a.page * a.D + d] = ks[e];
+    vd[(size_t)e * a.page] = vs[e];
+  }
+}
+
+}  // namespace ss
+
+extern "C" int ss_kv_commit(const void* k_new, const void* v_new, void* k_cache, void* v_cache,
+                            const int32_t* block_table, int max_pages_per_seq, int num_pages,
+                            const int32_t* seq_lens, const int32_t* path, const int32_t* n_accept, int B, int T,
+                            int gamma, int Hkv, int D, int page_size, int max_depth, int dtype,
+                            int32_t* new_seq_lens, void* stream) {
+  using namespace ss;
+  clear_error();
+  const char* fn = "ss_kv_commit";
+  SS_REQUIRE(B >= 0, SS_ERR_INVALID_ARG, "%s: B=%d", fn, B);
+  SS_REQUIRE(T >= 1 && T <= SS_MAX_T, SS_ERR_UNSUPPORTED, "%s: T=%d outside [1,%d]", fn, T, SS_MAX_T);
+  SS_REQUIRE(gamma >= 0 && gamma <= SS_MAX_GAMMA, SS_ERR_UNSUPPORTED, "%s: gamma=%d outside [0,%d]", fn, gamma,
+             SS_MAX_GAMMA);
+  SS_REQUIRE(Hkv >= 1 && D >= 1, SS_ERR_INVALID_ARG, "%s: Hkv=%d D=%d", fn, Hkv, D);
+  SS_REQUIRE(dtype == SS_F32 || dtype == SS_BF16, SS_ERR_UNSUPPORTED, "%s: dtype %d", fn, dtype);
+  SS_REQUIRE(page_size == 16 || page_size == 32 || page_size == 64, SS_ERR_UNSUPPORTED,
+             "%s: page_size %d not in {16,32,64}", fn, page_size);
+  SS_REQUIRE(max_pages_per_seq >= 1 && num_pages >= 1, SS_ERR_INVALID_ARG, "%s: max_pages_per_seq=%d num_pages=%d", fn,
+             max_pages_per_seq, num_pages);
+  SS_REQUIRE((long)max_pages_per_seq * page_size <= (1L << 30), SS_ERR_UNSUPPORTED, "%s: sequence capacity too large",
+             fn);
+  SS_REQUIRE(max_depth >= 0 && max_depth < SS_MAX_T, SS_ERR_INVALID_ARG, "%s: max_depth=%d", fn, max_depth);
+  SS_REQUIRE(B == 0 || (k_new && v_new && k_cache && v_cache && block_table && seq_lens && path && n_accept),
+             SS_ERR_INVALID_ARG, "%s: NULL tensor argument", fn);
+  SS_REQUIRE(new_seq_lens == nullptr || new_seq_lens != seq_lens, SS_ERR_INVALID_ARG,
+             "%s: new_seq_lens must not be the seq_lens array", fn);
+  SS_REQUIRE((long)B * (max_depth + 1) <= 0x7fffffffL, SS_ERR_UNSUPPORTED, "%s: grid too large", fn);
+  if (B == 0) return SS_OK;
+  KvArgs a;
+  a.k_new = k_new; a.v_new = v_new; a.k_cache = k_cache; a.v_cache = v_cache;
+  a.block_table = block_table; a.seq_lens = seq_lens; a.path = path; a.n_accept = n_accept;
+  a.new_seq_lens = new_seq_lens;
+  a.B = B; a.T = T; a.R = T * (1 + gamma); a.Hkv = Hkv; a.D = D; a.page = page_size;
+  a.page_shift = page_size == 16 ? 4 : (page_size == 32 ? 5 : 6);
+  a.max_pages = max_pages_per_seq; a.num_pages = num_pages; a.max_depth = max_depth;
+  const dim3 grid((unsigned)(B * (max_depth + 1)));
+  if (dtype == SS_F32) hipLaunchKernelGGL(kv_commit_kernel<uint32_t>, grid, dim3(256), 0, (hipStream_t)stream, a);
+  else hipLaunchKernelGGL(kv_commit_kernel<uint16_t>, grid, dim3(256), 0, (hipStream_t)stream, a);
+  return check_launch(fn);
+}
