@@ -123,6 +123,17 @@ def lm_head_topk(hidden, W, K: int, want_logits: bool = False):
     return (idx, val, logits) if want_logits else (idx, val)
 
 
+def linear_rows(x, W):
+    """n1.  y [N,V] (float64) = x [N,d] . W[V,d]^T."""
+    x, W = _f32(x), _f32(W)
+    N, d = x.shape
+    V = W.shape[0]
+    assert W.shape == (V, d)
+    y = np.zeros((N, V), np.float64)
+    _load().ora_linear_rows(_p(x), _p(W), N, d, V, _p(y))
+    return y
+
+
 def tree_verify(tok, parent, main_argmax, max_depth: int):
     """a4.  tok, parent, main_argmax [B,T] -> dict(n_accept, last, bonus, path, out_tokens)."""
     tok, parent, a = _i32(tok), _i32(parent), _i32(main_argmax)

@@ -241,6 +241,23 @@ void ora_lm_head_topk(const float* hidden, const float* W, int N, int d, int V, 
   }
 }
 
+/*
+ * n1: the dense projections around multi-stream attention (Sec. 3.1: queries,
+ * keys and values are H.W^Q, H.W^K, H.W^V of the hidden states H, for main and
+ * stream rows alike; the feed-forward maps are of the same form).  With the
+ * weight stored one output feature per row, y[n,v] = sum_e x[n,e] * W[v,e],
+ * accumulated in double in the order of e.
+ */
+void ora_linear_rows(const float* x, const float* W, int N, int d, int V, double* y) {
+#pragma omp parallel for schedule(static)
+  for (int n = 0; n < N; n++)
+    for (int v = 0; v < V; v++) {
+      double acc = 0.0;
+      for (int e = 0; e < d; e++) acc += (double)x[(size_t)n * d + e] * (double)W[(size_t)v * d + e];
+      y[(size_t)n * V + v] = acc;
+    }
+}
+
 /* ------------------------------------------------------------------ verify */
 
 /*
