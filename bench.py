@@ -278,6 +278,27 @@ def main():
                                      "hbm_gbps": round((cfg.vocab * cfg.d_model * 2 + N * cfg.d_model * 2) /
                                                        (us_lm * 1e-6) / 1e9, 1)}
         extra["accepted_per_sequence"] = state["ver"]["n_accept"].tolist()
+        if args.workload == "c4":
+            # Dense projections of one MSA layer on the step's N rows (the row after the hot path: not part of
+            # `value`): fused QKV, attention output, fused gate+up and down of a 4096/11008 feed-forward block.
+            dm, dff = cfg.d_model, 11008
+            dense = {}
+            total = 0.0
+            for name, (din, dout) in (("qkv", (dm, 3 * cfg.H * cfg.D)), ("attn_out", (cfg.H * cfg.D, dm)),
+                                      ("gate_up", (dm, 2 * dff)), ("down", (dff, dm))):
+                xs = [synth.make_lm_head_inputs(synth.scaled(cfg, vocab=dout, d_model=din), 50 + j, device=dev, N=N)
+                      for j in range(2)]
+                y = torch.empty(N, dout, dtype=xs[0]["hidden"].dtype, device=dev)
+                for j in range(2):
+                    api.ss_linear_rows(xs[j]["hidden"], xs[j]["W"], y)
+                us = timed(lambda i: api.ss_linear_rows(xs[i % 2]["hidden"], xs[i % 2]["W"], y), it, torch)
+                total += us
+                dense[name] = {"d_in": din, "d_out": dout, "us": round(us, 2),
+                               "tflops": round(2.0 * N * din * dout / (us * 1e-6) / 1e12, 1),
+                               "hbm_gbps": round((din * dout + N * din + N * dout) * 2 / (us * 1e-6) / 1e9, 1)}
+                del xs, y
+            dense["layer_total_us"] = round(total, 2)
+            extra["linear_rows"] = dense
 
     result = {
         "metric": "verify+speculate step time (MSA layers + LM-head argmax/top-k + verify + draft)",

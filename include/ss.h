@@ -167,6 +167,22 @@ int ss_lm_head_argmax_topk(const void* hidden, const void* W, int N, int d, int 
                            void* stream);
 
 /*
+ * n1. Dense projection of the step's rows (Sec. 3.1: queries, keys and values
+ * are H.W^Q, H.W^K, H.W^V of the hidden states H of main and stream rows; the
+ * output projection and the feed-forward maps of a layer have the same form):
+ *    y[n,v] = sum_e x[n,e] * W[v,e]
+ *  x [N,d], W [V,d] (one output feature per row), y [N,V]; all device memory of
+ *  type dtype (SS_F32 or SS_BF16), row-major, contiguous.  Products are
+ *  accumulated in fp32; a bf16 result is rounded to nearest even once.
+ *  It runs the main loop of a3 with a store in place of the search, so the same
+ *  limits hold: d % 64 == 0 for SS_BF16, x and W below 2^30 elements; rows of y
+ *  leave in 16-byte pieces when V % 8 == 0 (any V is accepted).
+ * y must not overlap x or W.  N == 0 is a no-op.  No workspace.
+ */
+int ss_linear_rows(const void* x, const void* W, int N, int d, int V, int dtype, void* y,
+                   void* stream);
+
+/*
  * a4. Greedy ("hard matching") tree verification (Sec. 3.2.2, Appendix A.1):
  * the root is always accepted; node i is accepted iff its parent is accepted
  * and tok[i] equals the main-stream argmax token at its parent.  `last` is the

@@ -27,7 +27,7 @@ SS_MAX_T, SS_MAX_GAMMA, SS_MAX_K = 64, 8, 8
 EXPORTS = (
     "ss_version", "ss_last_error", "ss_check_tree_host", "ss_build_mask", "ss_msa_workspace_bytes",
     "ss_msa_attention", "ss_msa_set_split_keys", "ss_lm_head_workspace_bytes", "ss_lm_head_argmax_topk",
-    "ss_tree_verify", "ss_tree_draft", "ss_full_tree_template_host", "ss_kv_commit",
+    "ss_tree_verify", "ss_tree_draft", "ss_full_tree_template_host", "ss_kv_commit", "ss_linear_rows",
 )
 
 _lib = None
@@ -67,6 +67,7 @@ def load_library() -> ctypes.CDLL:
     lib.ss_tree_draft.argtypes = [vp, lng, i32, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, vp]
     lib.ss_full_tree_template_host.argtypes = [vp, i32, i32, vp, vp, vp]
     lib.ss_kv_commit.argtypes = [vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp, vp]
+    lib.ss_linear_rows.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp]
     for name in EXPORTS:
         getattr(lib, name)
     _lib = lib
@@ -297,3 +298,20 @@ def ss_kv_commit(k_new, v_new, k_cache, v_cache, block_table, seq_lens, path, n_
                             None if new_seq_lens is None else _dev(new_seq_lens, i32, "new_seq_lens"), _stream()))
     return new_seq_lens
 
+
+
+def ss_linear_rows(x: torch.Tensor, W: torch.Tensor, y: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """n1.  y [N,V] = x [N,d] . W[V,d]^T in the inputs' dtype (fp32 or bf16)."""
+    lib = load_library()
+    code = _dtype_code(x)
+    dt = x.dtype
+    N, d = x.shape
+    V = W.shape[0]
+    if tuple(W.shape) != (V, d):
+        raise ValueError("W must be [V,%d]" % d)
+    if y is None:
+        y = torch.empty(N, V, dtype=dt, device=x.device)
+    elif tuple(y.shape) != (N, V):
+        raise ValueError("y must be [%d,%d]" % (N, V))
+    _check(lib.ss_linear_rows(_dev(x, dt, "x"), _dev(W, dt, "W"), N, d, V, code, _dev(y, dt, "y"), _stream()))
+    return y

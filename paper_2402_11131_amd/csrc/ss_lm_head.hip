@@ -6,6 +6,7 @@
 // Order everywhere: larger logit first, equal logits -> lower token id first.
 #include <limits.h>
 #include <math.h>
+#include <stdlib.h>
 
 #include "ss_common.h"
 
@@ -16,9 +17,11 @@ struct LmArgs {
   const void* W;       // [V,d]
   int N, d, V, K;
   int n_tiles;         // vocabulary tiles
+  int n_chunks;        // row chunks (bf16 kernel)
   uint64_t* cand_key;  // [N, n_tiles, K] candidates as ordered keys
   int32_t* idx;        // [N,K]
   float* val;          // [N,K]
+  void* y;             // [N,V], plain-projection flavour only (same type as the inputs)
 };
 
 SS_DEV bool cand_better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
@@ -44,6 +47,9 @@ SS_DEV int key_id(uint64_t k) { return k == 0 ? INT_MAX : (int)(0xffffffffu - (u
 //
 // Workgroup tile 32 rows x 64 vocabulary columns, feature chunks of 32 through
 // LDS; thread (wave w, lane c) accumulates rows w, w+4, ... of column c.
+//
+// STORE = true is the plain projection: the tile is written to y instead of being searched.
+template <bool STORE>
 __global__ __launch_bounds__(256) void lm_head_f32_kernel(LmArgs a) {
   constexpr int BM = 32, BN = 64, BK = 32;
   __shared__ float As[BM][BK + 1];
@@ -73,6 +79,14 @@ __global__ __launch_bounds__(256) void lm_head_f32_kernel(LmArgs a) {
 #pragma unroll
       for (int i = 0; i < BM / 4; ++i) acc[i] = fmaf(As[w + 4 * i][kk], wv, acc[i]);
     }
+  }
+  if constexpr (STORE) {
+#pragma unroll
+    for (int i = 0; i < BM / 4; ++i) {
+      const int row = r0 + w + 4 * i, col = v0 + lane;
+      if (row < a.N && col < a.V) ((float*)a.y)[(size_t)row * a.V + col] = acc[i];
+    }
+    return;
   }
 #pragma unroll
   for (int i = 0; i < BM / 4; ++i) Z[w + 4 * i][lane] = acc[i];
@@ -119,9 +133,9 @@ __global__ __launch_bounds__(256) void lm_head_f32_kernel(LmArgs a) {
 // over the vocabulary is mostly a per-lane affair: no logit is ever exchanged
 // between lanes, only K-entry candidate lists.
 //
-// Workgroup = 4 waves; tile = 128 token ids x 64*RT rows; wave w owns ids
-// [32*w, 32*w+32) and all rows: 2*RT accumulator tiles (160 accumulation registers
-// for RT = 5).  With N <= 320 one workgroup column covers all rows, so W is read
+// Workgroup = 4 waves; tile = 128 token ids x 32*NRT rows; wave w owns ids
+// [32*w, 32*w+32) and all rows: NRT accumulator tiles (160 accumulation registers
+// for NRT = 10).  With N <= 320 one workgroup column covers all rows, so W is read
 // from HBM exactly once, and the 250 workgroups of a 32000-token vocabulary fill
 // the chip once.  Each workgroup has to pull all of `hidden` through its L1, which
 // makes L2 -> compute-unit traffic (hidden once per workgroup, W once) the
@@ -134,7 +148,7 @@ __global__ __launch_bounds__(256) void lm_head_f32_kernel(LmArgs a) {
 // lines with 32 contiguous bytes each.  Four blocks are in flight per wave (the
 // ring is filled three blocks ahead of use): 12 KB per wave against the HBM
 // latency, with one wave per SIMD.  `hidden` is shared by the waves and goes
-// through LDS: four buffers of 64*RT rows x 128 bytes, filled three blocks ahead
+// through LDS: four buffers of 32*NRT rows x 128 bytes, filled three blocks ahead
 // by direct global->LDS loads (no staging registers and, more important, no
 // ds_write: LDS stores of this size run at a quarter of the read rate).  Such a
 // load writes lane l's 16 bytes to (base + 16*l), so the LDS image is row-major;
@@ -199,20 +213,25 @@ struct TopList {  // the KT best keys seen so far, best first
   }
 };
 
-template <int RT, int KT>
+template <int NRT, int KT>  // NRT: 32-row accumulator tiles per wave
 __global__ __launch_bounds__(256, 1) void lm_head_bf16_kernel(LmArgs a) {
-  constexpr int ROWS = 64 * RT;  // rows of `hidden` per workgroup
-  constexpr int NRT = 2 * RT;    // 32-row accumulator tiles per wave
+  constexpr int ROWS = 32 * NRT; // rows of `hidden` per workgroup
   constexpr int HB = ROWS * 128; // bytes of one block of `hidden` in LDS
-  constexpr int HL = 2 * RT;     // 16-byte chunks of it per thread
+  constexpr int HL = NRT;        // 16-byte chunks of it per thread
   extern __shared__ __attribute__((aligned(16))) unsigned char hbuf[];  // [4][HB], reused by the epilogue
 #ifdef SS_LM_TIMING
   const long long t_entry = clock64();
 #endif
   const int tid = threadIdx.x, lane = tid & 63, ln = lane & 31, lh = lane >> 5;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int v0 = blockIdx.x * 128 + 32 * w;  // first token id of this wave
-  const int row0 = blockIdx.y * ROWS;        // first row of this workgroup
+  // Workgroup -> (vocabulary tile, row chunk).  Workgroups are dealt to the eight XCDs in turn; the row
+  // chunks of one vocabulary tile take consecutive turns of ONE XCD, so that they run together and
+  // share that tile of W in its L2.
+  const int xcd = blockIdx.x & 7, turn = blockIdx.x >> 3;
+  const int tile = (turn / a.n_chunks) * 8 + xcd;
+  if (tile >= a.n_tiles) return;
+  const int v0 = tile * 128 + 32 * w;             // first token id of this wave
+  const int row0 = (turn % a.n_chunks) * ROWS;    // first row of this workgroup
   const int d = a.d, n_k = d / 64;
 
   // Sources as 32-bit byte offsets from a scalar base that moves with the feature block, so that a
@@ -275,7 +294,7 @@ __global__ __launch_bounds__(256, 1) void lm_head_bf16_kernel(LmArgs a) {
   // left), and ends when hidden block J+2 has landed.  Past the end the last block is fetched again
   // instead, which keeps the steps free of conditions (a condition around the MFMAs would cost a
   // register copy per accumulator).
-  // A step is four MFMA rounds (16 features each, 2*RT MFMAs).  The L1 takes a load instruction of a
+  // A step is four MFMA rounds (16 features each, NRT MFMAs).  The L1 takes a load instruction of a
   // wave only every ~18 cycles and the four waves share it, so the step's loads are dealt to the
   // rounds and, inside a round, placed between the MFMAs (scheduling groups) instead of stalling the
   // wave in a burst.  The operand reads of a round are issued in the round before.
@@ -349,9 +368,44 @@ __global__ __launch_bounds__(256, 1) void lm_head_bf16_kernel(LmArgs a) {
   const long long t_ep0 = clock64();
 #endif
   // ---- epilogue.  acc[rt][e] on lane (ln, lh) is the logit of row row0 + 32*rt + ln and token id
-  // v0 + 8*(e/4) + 4*lh + e%4.  Per row: this lane's 16 candidates go into a K-entry list, the two
-  // lanes of a row merge theirs, the four waves' lists meet in LDS (free by now: the last step ended
-  // with a barrier), and one thread per row leaves the workgroup's K best as part blockIdx.x.
+  // v0 + 8*(e/4) + 4*lh + e%4.  LDS is free by now: the last step ended with a barrier.
+  if constexpr (KT == 0) {
+    // Plain projection: the tile is rounded to bf16 and turned round through LDS ([ROWS] rows of 128
+    // outputs, padded to 272 bytes so that the 8-byte writes of 32 rows spread over the banks), then
+    // leaves in 16-byte pieces, 256 contiguous bytes per row.
+    constexpr int YS = 272;
+    static_assert(ROWS * YS <= 4 * HB, "output tile must fit the hidden buffers");
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt)
+#pragma unroll
+      for (int eg = 0; eg < 4; ++eg) {
+        uintx2 pk;
+        pk[0] = pack_bf16x2(acc[rt][4 * eg], acc[rt][4 * eg + 1]);
+        pk[1] = pack_bf16x2(acc[rt][4 * eg + 2], acc[rt][4 * eg + 3]);
+        *reinterpret_cast<uintx2*>(hbuf + (32 * rt + ln) * YS + (32 * w + 8 * eg + 4 * lh) * 2) = pk;
+      }
+    __syncthreads();
+    const bool vec_ok = (a.V % 8) == 0 && ((uintptr_t)a.y & 15) == 0;  // rows of y are 16-byte aligned
+    uint16_t* y = (uint16_t*)a.y;
+    for (int p = tid; p < ROWS * 16; p += 256) {
+      const int r = p >> 4, ch = p & 15;
+      const int row = row0 + r, id0 = tile * 128 + 8 * ch;
+      if (row >= a.N || id0 >= a.V) continue;
+      const uintx4 piece = *reinterpret_cast<const uintx4*>(hbuf + r * YS + ch * 16);
+      uint16_t* dst = y + (size_t)row * a.V + id0;
+      if (vec_ok) {
+        *reinterpret_cast<uintx4*>(dst) = piece;  // V % 8 == 0 and id0 < V: the whole piece is inside
+      } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+          if (id0 + j < a.V) dst[j] = (uint16_t)(piece[j >> 1] >> (16 * (j & 1)));
+      }
+    }
+    return;
+  } else {
+  // Per row: this lane's 16 candidates go into a K-entry list, the two lanes of a row merge theirs,
+  // the four waves' lists meet in LDS, and one thread per row leaves the workgroup's K best as part
+  // blockIdx.x.
   uint64_t* lists = reinterpret_cast<uint64_t*>(hbuf);  // [ROWS][4 waves][KT]
 #pragma unroll
   for (int rt = 0; rt < NRT; ++rt) {
@@ -386,11 +440,12 @@ __global__ __launch_bounds__(256, 1) void lm_head_bf16_kernel(LmArgs a) {
     for (int j = 0; j < 4 * KT; ++j) top.insert(lists[r * 4 * KT + j]);
     const int row = row0 + r;
     if (row < a.N) {
-      const size_t o = ((size_t)row * a.n_tiles + blockIdx.x) * a.K;
+      const size_t o = ((size_t)row * a.n_tiles + tile) * a.K;
 #pragma unroll
       for (int k = 0; k < KT; ++k)
         if (k < a.K) a.cand_key[o + k] = top.k[k];
     }
+  }
   }
 #ifdef SS_LM_TIMING
   if (lane == 0) {
@@ -442,45 +497,78 @@ __global__ __launch_bounds__(64) void lm_head_reduce_kernel(LmArgs a) {
   }
 }
 
-template <int RT, int KT>
-static int launch_lm_bf16_rk(dim3 grid, hipStream_t st, const LmArgs& a) {
-  auto kern = lm_head_bf16_kernel<RT, KT>;
-  const size_t lds = 4 * (size_t)(64 * RT) * 128;
+template <int NRT, int KT>
+static int launch_lm_bf16_rk(hipStream_t st, const LmArgs& a) {
+  auto kern = lm_head_bf16_kernel<NRT, KT>;
+  const size_t lds = 4 * (size_t)(32 * NRT) * 128;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)lds);
-    if (e != hipSuccess) SS_FAIL(SS_ERR_HIP, "ss_lm_head_argmax_topk: hipFuncSetAttribute: %s", hipGetErrorString(e));
+    if (e != hipSuccess) SS_FAIL(SS_ERR_HIP, "lm_head_bf16_kernel: hipFuncSetAttribute: %s", hipGetErrorString(e));
     attr_set = true;
   }
+  const dim3 grid(8 * a.n_chunks * ceil_div(a.n_tiles, 8));
   hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, a);
   return SS_OK;
 }
-template <int RT>
-static int launch_lm_bf16_r(int KT, dim3 grid, hipStream_t st, const LmArgs& a) {
+template <int NRT>
+static int launch_lm_bf16_r(int KT, hipStream_t st, const LmArgs& a) {
   switch (KT) {
-    case 1: return launch_lm_bf16_rk<RT, 1>(grid, st, a);
-    case 4: return launch_lm_bf16_rk<RT, 4>(grid, st, a);
-    default: return launch_lm_bf16_rk<RT, 8>(grid, st, a);
+    case 0: return launch_lm_bf16_rk<NRT, 0>(st, a);
+    case 1: return launch_lm_bf16_rk<NRT, 1>(st, a);
+    case 4: return launch_lm_bf16_rk<NRT, 4>(st, a);
+    default: return launch_lm_bf16_rk<NRT, 8>(st, a);
   }
 }
-static int launch_lm_bf16(int RT, int KT, dim3 grid, hipStream_t st, const LmArgs& a) {
-  switch (RT) {
-    case 1: return launch_lm_bf16_r<1>(KT, grid, st, a);
-    case 2: return launch_lm_bf16_r<2>(KT, grid, st, a);
-    case 3: return launch_lm_bf16_r<3>(KT, grid, st, a);
-    case 4: return launch_lm_bf16_r<4>(KT, grid, st, a);
-    default: return launch_lm_bf16_r<5>(KT, grid, st, a);
+// Rows go to the workgroups in n_chunks chunks of 32*NRT rows; a.n_chunks must be set.
+static int launch_lm_bf16(int NRT, int KT, hipStream_t st, const LmArgs& a) {
+  switch (NRT) {
+    case 1: return launch_lm_bf16_r<1>(KT, st, a);
+    case 2: return launch_lm_bf16_r<2>(KT, st, a);
+    case 3: return launch_lm_bf16_r<3>(KT, st, a);
+    case 4: return launch_lm_bf16_r<4>(KT, st, a);
+    case 5: return launch_lm_bf16_r<5>(KT, st, a);
+    case 6: return launch_lm_bf16_r<6>(KT, st, a);
+    case 7: return launch_lm_bf16_r<7>(KT, st, a);
+    case 8: return launch_lm_bf16_r<8>(KT, st, a);
+    case 9: return launch_lm_bf16_r<9>(KT, st, a);
+    default: return launch_lm_bf16_r<10>(KT, st, a);
   }
+}
+
+// Rows per workgroup, in 32-row tiles, for the search flavour: as many as fit (W is then read once per
+// chunk), chunks of equal size.
+static int lm_row_tiles(int N, int* n_chunks) {
+  const int n32 = ceil_div(N, 32);
+  *n_chunks = ceil_div(n32, 10);
+  return ceil_div(n32, *n_chunks);
+}
+
+// The same for the plain projection, whose output dimension is often too small to give every compute
+// unit a workgroup: rows are cut into more chunks while the workgroups still fit the chip in one round
+// (256 compute units, one workgroup each).  The chunks of a vocabulary tile share its part of W in L2.
+static int linear_row_tiles(int N, int n_tiles, int* n_chunks) {
+  const int n32 = ceil_div(N, 32);
+  int c = 256 / n_tiles;
+  c = c < 1 ? 1 : (c > n32 ? n32 : c);
+  int nrt = ceil_div(n32, c);
+  if (nrt > 10) nrt = 10;
+  *n_chunks = ceil_div(n32, nrt);
+  return nrt;
 }
 
 // Candidate parts per row: one per vocabulary tile (64 ids in the fp32 kernel, 128 in the MFMA kernel).
 static int lm_tiles(int V, int dtype) { return ceil_div(V, dtype == SS_BF16 ? 128 : 64); }
 
+static int gemm_check(const char* fn, int N, int d, int V, int dtype);
 static int lm_check(const char* fn, int N, int d, int V, int K, int dtype) {
-  SS_REQUIRE(N >= 0 && d >= 1 && V >= 1, SS_ERR_INVALID_ARG, "%s: N=%d d=%d V=%d", fn, N, d, V);
   SS_REQUIRE(K >= 1 && K <= SS_MAX_K, SS_ERR_UNSUPPORTED, "%s: K=%d outside [1,%d]", fn, K, SS_MAX_K);
-  SS_REQUIRE(K <= V, SS_ERR_INVALID_ARG, "%s: K=%d exceeds V=%d", fn, K, V);
+  SS_REQUIRE(K <= V || V < 1, SS_ERR_INVALID_ARG, "%s: K=%d exceeds V=%d", fn, K, V);
+  return gemm_check(fn, N, d, V, dtype);
+}
+static int gemm_check(const char* fn, int N, int d, int V, int dtype) {
+  SS_REQUIRE(N >= 0 && d >= 1 && V >= 1, SS_ERR_INVALID_ARG, "%s: N=%d d=%d V=%d", fn, N, d, V);
   SS_REQUIRE(dtype == SS_F32 || dtype == SS_BF16, SS_ERR_UNSUPPORTED, "%s: dtype %d", fn, dtype);
   SS_REQUIRE(dtype != SS_BF16 || d % 64 == 0, SS_ERR_UNSUPPORTED, "%s: bf16 path needs d %% 64 == 0 (d=%d)", fn, d);
   SS_REQUIRE(dtype != SS_BF16 || ((long)(N < 1 ? 1 : N) * d < (1L << 30) && (long)V * d < (1L << 30)), SS_ERR_UNSUPPORTED,
@@ -512,24 +600,58 @@ int ss_lm_head_argmax_topk(const void* hidden, const void* W, int N, int d, int 
   LmArgs a;
   a.hidden = hidden; a.W = W; a.N = N; a.d = d; a.V = V; a.K = K;
   a.n_tiles = lm_tiles(V, dtype);
+  a.n_chunks = 1;
   char* ws = (char*)(((uintptr_t)workspace + 255) & ~(uintptr_t)255);
   a.cand_key = (uint64_t*)ws;
   a.idx = idx; a.val = val;
+  a.y = nullptr;
   hipStream_t st = (hipStream_t)stream;
   if (dtype == SS_F32) {
     dim3 grid(a.n_tiles, ceil_div(N, 32));
     SS_REQUIRE(grid.y <= 65535, SS_ERR_UNSUPPORTED, "%s: N too large", fn);
-    hipLaunchKernelGGL(lm_head_f32_kernel, grid, dim3(256), 0, st, a);
+    hipLaunchKernelGGL(lm_head_f32_kernel<false>, grid, dim3(256), 0, st, a);
   } else {
-    int RT = ceil_div(N, 64);
-    if (RT > 5) RT = 5;
-    dim3 grid(ceil_div(V, 128), ceil_div(N, 64 * RT));
-    SS_REQUIRE(grid.y <= 65535, SS_ERR_UNSUPPORTED, "%s: N too large", fn);
+    const int NRT = lm_row_tiles(N, &a.n_chunks);
+    SS_REQUIRE((long)a.n_chunks * (a.n_tiles + 7) < (1L << 27), SS_ERR_UNSUPPORTED, "%s: N x V too large", fn);
     const int KT = K == 1 ? 1 : (K <= 4 ? 4 : 8);
-    if (int rc = launch_lm_bf16(RT, KT, grid, st, a)) return rc;
+    if (int rc = launch_lm_bf16(NRT, KT, st, a)) return rc;
   }
   if (int rc = check_launch(fn)) return rc;
   hipLaunchKernelGGL(lm_head_reduce_kernel, dim3(N), dim3(64), 0, st, a);
+  return check_launch(fn);
+}
+
+int ss_linear_rows(const void* x, const void* W, int N, int d, int V, int dtype, void* y, void* stream) {
+  using namespace ss;
+  clear_error();
+  const char* fn = "ss_linear_rows";
+  if (int rc = gemm_check(fn, N, d, V, dtype)) return rc;
+  SS_REQUIRE(N == 0 || (x && W && y), SS_ERR_INVALID_ARG, "%s: NULL tensor argument", fn);
+  SS_REQUIRE((long)(N < 1 ? 1 : N) * V < (1L << 31), SS_ERR_UNSUPPORTED, "%s: y (%d x %d) has 2^31 elements or more", fn, N, V);
+  if (N == 0) return SS_OK;
+  LmArgs a;
+  a.hidden = x; a.W = W; a.N = N; a.d = d; a.V = V; a.K = 0;
+  a.n_tiles = lm_tiles(V, dtype);
+  a.n_chunks = 1;
+  a.cand_key = nullptr; a.idx = nullptr; a.val = nullptr;
+  a.y = y;
+  hipStream_t st = (hipStream_t)stream;
+  if (dtype == SS_F32) {
+    dim3 grid(a.n_tiles, ceil_div(N, 32));
+    SS_REQUIRE(grid.y <= 65535, SS_ERR_UNSUPPORTED, "%s: N too large", fn);
+    hipLaunchKernelGGL(lm_head_f32_kernel<true>, grid, dim3(256), 0, st, a);
+  } else {
+    int NRT = linear_row_tiles(N, a.n_tiles, &a.n_chunks);
+    if (const char* e = getenv("SS_LINEAR_ROW_TILES")) {  // tuning aid: rows per workgroup / 32
+      const int want = atoi(e);
+      if (want >= 1 && want <= 10) {
+        a.n_chunks = ceil_div(ceil_div(N, 32), want);
+        NRT = ceil_div(ceil_div(N, 32), a.n_chunks);
+      }
+    }
+    SS_REQUIRE((long)a.n_chunks * (a.n_tiles + 7) < (1L << 27), SS_ERR_UNSUPPORTED, "%s: N x V too large", fn);
+    if (int rc = launch_lm_bf16(NRT, 0, st, a)) return rc;
+  }
   return check_launch(fn);
 }
 
