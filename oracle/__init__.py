@@ -134,6 +134,21 @@ def linear_rows(x, W):
     return y
 
 
+def stream_insert(M, P, fM=None):
+    """n4 (Eq. 3).  M [B,T,d] main-stream hidden states of the tree nodes, P [gamma,d] stream embeddings,
+    fM = f(M) or None for the identity.  Returns X [B,R,d] float64."""
+    M, P = _f32(M), _f32(P)
+    B, T, d = M.shape
+    gamma = P.shape[0]
+    assert P.shape == (gamma, d)
+    if fM is not None:
+        fM = _f32(fM)
+        assert fM.shape == M.shape
+    X = np.zeros((B, T * (1 + gamma), d), np.float64)
+    _load().ora_stream_insert(_p(M), _p(fM), _p(P), B, T, gamma, d, _p(X))
+    return X
+
+
 def tree_verify(tok, parent, main_argmax, max_depth: int):
     """a4.  tok, parent, main_argmax [B,T] -> dict(n_accept, last, bonus, path, out_tokens)."""
     tok, parent, a = _i32(tok), _i32(parent), _i32(main_argmax)

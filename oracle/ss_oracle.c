@@ -258,6 +258,31 @@ void ora_linear_rows(const float* x, const float* W, int N, int d, int V, double
     }
 }
 
+/*
+ * n4: stream insertion (Eq. 3).  At the first multi-stream layer the rows of a
+ * step are formed from the main-stream hidden states M [B,T,d] of the tree
+ * nodes: the main row of node i is M_i itself, stream j of node i starts as
+ * f(M_i) + P_j with P [gamma,d] the stream identifier embeddings.  fM holds
+ * f(M) [B,T,d]; NULL means the identity, which the paper's experiments use
+ * (Appendix, experimental setup).  X [B,R,d] in the row order stated above.
+ */
+void ora_stream_insert(const float* M, const float* fM, const float* P, int B, int T, int gamma,
+                       int d, double* X) {
+  const int R = T * (1 + gamma);
+  const float* src = fM ? fM : M;
+  for (int b = 0; b < B; b++)
+    for (int i = 0; i < T; i++) {
+      for (int e = 0; e < d; e++)
+        X[((size_t)b * R + i) * d + e] = (double)M[((size_t)b * T + i) * d + e];
+      for (int j = 1; j <= gamma; j++) {
+        const int r = T + i * gamma + (j - 1);
+        for (int e = 0; e < d; e++)
+          X[((size_t)b * R + r) * d + e] =
+              (double)src[((size_t)b * T + i) * d + e] + (double)P[(size_t)(j - 1) * d + e];
+      }
+    }
+}
+
 /* ------------------------------------------------------------------ verify */
 
 /*
