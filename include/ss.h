@@ -183,6 +183,21 @@ int ss_linear_rows(const void* x, const void* W, int N, int d, int V, int dtype,
                    void* stream);
 
 /*
+ * n4. Stream insertion (Eq. 3): the rows of a step as they enter the first
+ * multi-stream layer, from the main-stream hidden states of the tree nodes.
+ *    X[b, i]                 = M[b,i]                 main row of node i
+ *    X[b, T + i*gamma + j-1] = f(M)[b,i] + P[j-1]     stream j = 1..gamma of node i
+ *  M [B,T,d]; fM [B,T,d] = f(M), or NULL for the identity (the paper's
+ *  experiments; a rank-eta f is two ss_linear_rows calls); P [gamma,d] stream
+ *  identifier embeddings; X [B,R,d] with R = T*(1+gamma) in the row order of this
+ *  header.  All device memory of type dtype, contiguous.  Sums are formed in
+ *  fp32 and rounded once.  X must not overlap the inputs.  B == 0 is a no-op;
+ *  with gamma == 0 P may be NULL.
+ */
+int ss_stream_insert(const void* M, const void* fM, const void* P, int B, int T, int gamma, int d,
+                     int dtype, void* X, void* stream);
+
+/*
  * a4. Greedy ("hard matching") tree verification (Sec. 3.2.2, Appendix A.1):
  * the root is always accepted; node i is accepted iff its parent is accepted
  * and tok[i] equals the main-stream argmax token at its parent.  `last` is the

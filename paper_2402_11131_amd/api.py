@@ -27,7 +27,7 @@ SS_MAX_T, SS_MAX_GAMMA, SS_MAX_K = 64, 8, 8
 EXPORTS = (
     "ss_version", "ss_last_error", "ss_check_tree_host", "ss_build_mask", "ss_msa_workspace_bytes",
     "ss_msa_attention", "ss_msa_set_split_keys", "ss_lm_head_workspace_bytes", "ss_lm_head_argmax_topk",
-    "ss_tree_verify", "ss_tree_draft", "ss_full_tree_template_host", "ss_kv_commit", "ss_linear_rows",
+    "ss_tree_verify", "ss_tree_draft", "ss_full_tree_template_host", "ss_kv_commit", "ss_linear_rows", "ss_stream_insert",
 )
 
 _lib = None
@@ -68,6 +68,7 @@ def load_library() -> ctypes.CDLL:
     lib.ss_full_tree_template_host.argtypes = [vp, i32, i32, vp, vp, vp]
     lib.ss_kv_commit.argtypes = [vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp, vp]
     lib.ss_linear_rows.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp]
+    lib.ss_stream_insert.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp, vp]
     for name in EXPORTS:
         getattr(lib, name)
     _lib = lib
@@ -315,3 +316,25 @@ def ss_linear_rows(x: torch.Tensor, W: torch.Tensor, y: Optional[torch.Tensor] =
         raise ValueError("y must be [%d,%d]" % (N, V))
     _check(lib.ss_linear_rows(_dev(x, dt, "x"), _dev(W, dt, "W"), N, d, V, code, _dev(y, dt, "y"), _stream()))
     return y
+
+
+def ss_stream_insert(M: torch.Tensor, P: torch.Tensor, fM: Optional[torch.Tensor] = None,
+                     X: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """n4 (Eq. 3).  M [B,T,d], P [gamma,d], fM = f(M) or None (identity) -> X [B, T*(1+gamma), d]."""
+    lib = load_library()
+    code = _dtype_code(M)
+    dt = M.dtype
+    B, T, d = M.shape
+    gamma = P.shape[0]
+    if tuple(P.shape) != (gamma, d):
+        raise ValueError("P must be [gamma,%d]" % d)
+    if fM is not None and tuple(fM.shape) != (B, T, d):
+        raise ValueError("fM must have M's shape")
+    R = T * (1 + gamma)
+    if X is None:
+        X = torch.empty(B, R, d, dtype=dt, device=M.device)
+    elif tuple(X.shape) != (B, R, d):
+        raise ValueError("X must be [%d,%d,%d]" % (B, R, d))
+    _check(lib.ss_stream_insert(_dev(M, dt, "M"), None if fM is None else _dev(fM, dt, "fM"), _dev(P, dt, "P"),
+                                B, T, gamma, d, code, _dev(X, dt, "X"), _stream()))
+    return X

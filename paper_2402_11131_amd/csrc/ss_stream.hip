@@ -1,0 +1,83 @@
+// n4: stream insertion (Eq. 3).  The rows of a step enter the first multi-stream layer as: main row of
+// node i = M_i, stream j of node i = f(M_i) + P_j.  Elementwise and tiny (B*R*d elements): one workgroup
+// per output row, 16-byte pieces where the row length allows.  Sums are formed in fp32 and rounded once.
+#include "ss_common.h"
+
+namespace ss {
+
+struct StreamArgs {
+  const void* M;   // [B,T,d]
+  const void* fM;  // [B,T,d] or NULL (identity)
+  const void* P;   // [gamma,d]
+  void* X;         // [B,R,d]
+  int B, T, gamma, d;
+};
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void stream_insert_kernel(StreamArgs a) {
+  constexpr int ES = BF16 ? 2 : 4;   // bytes per element
+  constexpr int PER = 16 / ES;       // elements per 16-byte piece
+  const int R = a.T * (1 + a.gamma);
+  const int b = blockIdx.x / R, r = blockIdx.x % R;
+  int node, strm;
+  row_split(r, a.T, a.gamma, node, strm);
+  const size_t src_row = ((size_t)b * a.T + node) * a.d;
+  const unsigned char* m = (const unsigned char*)(strm == 0 || a.fM == nullptr ? a.M : a.fM) + src_row * ES;
+  const unsigned char* p = (const unsigned char*)a.P + (size_t)(strm > 0 ? strm - 1 : 0) * a.d * ES;
+  unsigned char* x = (unsigned char*)a.X + ((size_t)b * R + r) * a.d * ES;
+  const bool vec = (a.d % PER) == 0 && ((((uintptr_t)a.M | (uintptr_t)a.fM | (uintptr_t)a.P | (uintptr_t)a.X) & 15) == 0);
+  if (vec) {
+    for (int c = threadIdx.x; c < a.d / PER; c += 256) {
+      uintx4 mv = *reinterpret_cast<const uintx4*>(m + (size_t)c * 16);
+      if (strm > 0) {
+        const uintx4 pv = *reinterpret_cast<const uintx4*>(p + (size_t)c * 16);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          if constexpr (BF16) {
+            const float lo = bf16_bits_to_f32(mv[q] & 0xffffu) + bf16_bits_to_f32(pv[q] & 0xffffu);
+            const float hi = bf16_bits_to_f32(mv[q] >> 16) + bf16_bits_to_f32(pv[q] >> 16);
+            mv[q] = pack_bf16x2(lo, hi);
+          } else {
+            mv[q] = __float_as_uint(__uint_as_float(mv[q]) + __uint_as_float(pv[q]));
+          }
+        }
+      }
+      *reinterpret_cast<uintx4*>(x + (size_t)c * 16) = mv;
+    }
+  } else {
+    for (int e = threadIdx.x; e < a.d; e += 256) {
+      if constexpr (BF16) {
+        const uint16_t mb = ((const uint16_t*)m)[e];
+        ((uint16_t*)x)[e] = strm == 0 ? mb
+                                      : (uint16_t)f32_to_bf16_bits(bf16_bits_to_f32(mb) + bf16_bits_to_f32(((const uint16_t*)p)[e]));
+      } else {
+        const float mf = ((const float*)m)[e];
+        ((float*)x)[e] = strm == 0 ? mf : mf + ((const float*)p)[e];
+      }
+    }
+  }
+}
+
+}  // namespace ss
+
+extern "C" int ss_stream_insert(const void* M, const void* fM, const void* P, int B, int T, int gamma, int d,
+                                int dtype, void* X, void* stream) {
+  using namespace ss;
+  clear_error();
+  const char* fn = "ss_stream_insert";
+  SS_REQUIRE(B >= 0 && d >= 1, SS_ERR_INVALID_ARG, "%s: B=%d d=%d", fn, B, d);
+  SS_REQUIRE(T >= 1 && T <= SS_MAX_T, SS_ERR_UNSUPPORTED, "%s: T=%d outside [1,%d]", fn, T, SS_MAX_T);
+  SS_REQUIRE(gamma >= 0 && gamma <= SS_MAX_GAMMA, SS_ERR_UNSUPPORTED, "%s: gamma=%d outside [0,%d]", fn, gamma,
+             SS_MAX_GAMMA);
+  SS_REQUIRE(dtype == SS_F32 || dtype == SS_BF16, SS_ERR_UNSUPPORTED, "%s: dtype %d", fn, dtype);
+  SS_REQUIRE(B == 0 || (M && X && (P || gamma == 0)), SS_ERR_INVALID_ARG, "%s: NULL tensor argument", fn);
+  SS_REQUIRE((long)B * T * (1 + gamma) <= 0x7fffffffL, SS_ERR_UNSUPPORTED, "%s: grid too large", fn);
+  if (B == 0) return SS_OK;
+  StreamArgs a;
+  a.M = M; a.fM = fM; a.P = P ? P : M; a.X = X;  // P is never read when gamma == 0
+  a.B = B; a.T = T; a.gamma = gamma; a.d = d;
+  const dim3 grid((unsigned)(B * T * (1 + gamma)));
+  if (dtype == SS_F32) hipLaunchKernelGGL(stream_insert_kernel<false>, grid, dim3(256), 0, (hipStream_t)stream, a);
+  else hipLaunchKernelGGL(stream_insert_kernel<true>, grid, dim3(256), 0, (hipStream_t)stream, a);
+  return check_launch(fn);
+}

@@ -1,0 +1,92 @@
+"""GPU parity of stream insertion (n4, Eq. 3) against the oracle.
+
+fp32: the kernel's single fp32 addition is the correctly rounded sum, i.e. the oracle's double sum rounded
+to fp32: bit-exact.  bf16: main rows are copies (bit-exact); a stream row is the fp32 sum of two bf16
+values rounded to bf16, within one rounding of the oracle's double sum: |x - ref| <= 2^-8 |ref|.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from helpers import to_np_f32
+from paper_2402_11131_amd import api, synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _normal(g, shape, std):
+    return torch.from_numpy((std * g.standard_normal(shape)).astype(np.float32))
+
+
+def _inputs(B, T, gamma, d, dtype, seed, with_f=False):
+    g = synth.rng_for(seed)
+    M = _normal(g, (B, T, d), 1.0).to(dtype)
+    P = _normal(g, (gamma, d), 0.1).to(dtype)
+    fM = _normal(g, (B, T, d), 0.5).to(dtype) if with_f else None
+    return M, P, fM
+
+
+def _check(B, T, gamma, d, dtype, seed, with_f=False):
+    M, P, fM = _inputs(B, T, gamma, d, dtype, seed, with_f)
+    X = api.ss_stream_insert(M.to(DEV), P.to(DEV), None if fM is None else fM.to(DEV))
+    torch.cuda.synchronize()
+    assert X.dtype == dtype and tuple(X.shape) == (B, T * (1 + gamma), d)
+    got = to_np_f32(X.cpu())
+    ref = oracle.stream_insert(to_np_f32(M), to_np_f32(P), None if fM is None else to_np_f32(fM))
+    np.testing.assert_array_equal(got[:, :T], to_np_f32(M))        # main rows: copies
+    if dtype == torch.float32:
+        np.testing.assert_array_equal(got, ref.astype(np.float32))
+    else:
+        assert (np.abs(got - ref) <= 2.0 ** -8 * np.abs(ref)).all()
+
+
+def test_c4_shape_bf16():
+    cfg = synth.CONFIGS["c4"]
+    _check(cfg.B, cfg.T, cfg.gamma, cfg.d_model, torch.bfloat16, 1)
+
+
+def test_c1_shape_fp32():
+    cfg = synth.CONFIGS["c1"]
+    _check(cfg.B, cfg.T, cfg.gamma, cfg.d_model, torch.float32, 2)
+
+
+@pytest.mark.parametrize("B,T,gamma,d", [(1, 1, 1, 8), (3, 7, 2, 100), (2, 64, 8, 72), (5, 11, 3, 36), (2, 5, 0, 64),
+                                          (1, 9, 4, 1000)])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_shapes(B, T, gamma, d, dtype):
+    _check(B, T, gamma, d, dtype, 3)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_given_transformed_states(dtype):
+    _check(2, 6, 3, 256, dtype, 4, with_f=True)
+
+
+def test_rank_eta_transform_through_the_projection_then_insert():
+    # f of rank 64 as two ss_linear_rows calls, then insertion; against the oracle's chain fed the GPU's
+    # intermediate values (each stage is compared on its own inputs)
+    g = synth.rng_for(5)
+    B, T, gamma, d, eta = 2, 5, 2, 128, 64
+    M = _normal(g, (B, T, d), 1.0).to(torch.bfloat16).to(DEV)
+    P = _normal(g, (gamma, d), 0.1).to(torch.bfloat16).to(DEV)
+    A = _normal(g, (eta, d), 0.1).to(torch.bfloat16).to(DEV)
+    Bm = _normal(g, (d, eta), 0.1).to(torch.bfloat16).to(DEV)
+    low = api.ss_linear_rows(M.view(B * T, d), A)
+    fM = api.ss_linear_rows(low, Bm).view(B, T, d)
+    X = api.ss_stream_insert(M, P, fM)
+    torch.cuda.synchronize()
+    ref = oracle.stream_insert(to_np_f32(M), to_np_f32(P), to_np_f32(fM))
+    assert (np.abs(to_np_f32(X) - ref) <= 2.0 ** -8 * np.abs(ref)).all()
+    ref_f = oracle.linear_rows(to_np_f32(low), to_np_f32(Bm))
+    np.testing.assert_allclose(to_np_f32(fM).reshape(B * T, d), ref_f, rtol=2.0 ** -7, atol=1e-3)
+
+
+def test_empty_batch_and_bad_shapes():
+    X = api.ss_stream_insert(torch.zeros(0, 4, 16, device=DEV), torch.zeros(2, 16, device=DEV))
+    assert tuple(X.shape) == (0, 12, 16)
+    with pytest.raises(ValueError):
+        api.ss_stream_insert(torch.zeros(1, 4, 16, device=DEV), torch.zeros(2, 8, device=DEV))
+    with pytest.raises(api.SSError):      # T above the tree limit
+        api.ss_stream_insert(torch.zeros(1, 65, 16, device=DEV), torch.zeros(2, 16, device=DEV))
