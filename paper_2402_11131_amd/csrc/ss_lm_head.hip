@@ -213,6 +213,94 @@ struct TopList {  // the KT best keys seen so far, best first
   }
 };
 
+// The epilogue of both MFMA kernels.  acc[rt][e] on lane (ln, lh) is the logit of row row0 + 32*rt + ln
+// and token id v0 + 8*(e/4) + 4*lh + e%4.  `lds` (at least 512 bytes per row of the tile) must be free:
+// the callers end their loops with a barrier.
+template <int NRT, int KT>
+SS_DEV void lm_epilogue(const LmArgs& a, floatx16 (&acc)[NRT], unsigned char* hbuf, int tile, int row0, int v0, int w,
+                        int tid) {
+  constexpr int ROWS = 32 * NRT;
+  const int lane = tid & 63, ln = lane & 31, lh = lane >> 5;
+  if constexpr (KT == 0) {
+    // Plain projection: the tile is rounded to bf16 and turned round through LDS ([ROWS] rows of 128
+    // outputs, padded to 272 bytes so that the 8-byte writes of 32 rows spread over the banks), then
+    // leaves in 16-byte pieces, 256 contiguous bytes per row.
+    constexpr int YS = 272;
+    static_assert(YS <= 512, "output tile must fit 512 bytes per row");
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt)
+#pragma unroll
+      for (int eg = 0; eg < 4; ++eg) {
+        uintx2 pk;
+        pk[0] = pack_bf16x2(acc[rt][4 * eg], acc[rt][4 * eg + 1]);
+        pk[1] = pack_bf16x2(acc[rt][4 * eg + 2], acc[rt][4 * eg + 3]);
+        *reinterpret_cast<uintx2*>(hbuf + (32 * rt + ln) * YS + (32 * w + 8 * eg + 4 * lh) * 2) = pk;
+      }
+    __syncthreads();
+    const bool vec_ok = (a.V % 8) == 0 && ((uintptr_t)a.y & 15) == 0;  // rows of y are 16-byte aligned
+    uint16_t* y = (uint16_t*)a.y;
+    for (int p = tid; p < ROWS * 16; p += 256) {
+      const int r = p >> 4, ch = p & 15;
+      const int row = row0 + r, id0 = tile * 128 + 8 * ch;
+      if (row >= a.N || id0 >= a.V) continue;
+      const uintx4 piece = *reinterpret_cast<const uintx4*>(hbuf + r * YS + ch * 16);
+      uint16_t* dst = y + (size_t)row * a.V + id0;
+      if (vec_ok) {
+        *reinterpret_cast<uintx4*>(dst) = piece;  // V % 8 == 0 and id0 < V: the whole piece is inside
+      } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+          if (id0 + j < a.V) dst[j] = (uint16_t)(piece[j >> 1] >> (16 * (j & 1)));
+      }
+    }
+    return;
+  } else {
+  // Per row: this lane's 16 candidates go into a K-entry list, the two lanes of a row merge theirs,
+  // the four waves' lists meet in LDS, and one thread per row leaves the workgroup's K best as the
+  // part of this vocabulary tile.
+  uint64_t* lists = reinterpret_cast<uint64_t*>(hbuf);  // [ROWS][4 waves][KT]
+#pragma unroll
+  for (int rt = 0; rt < NRT; ++rt) {
+    TopAsc<KT> asc;  // this lane's candidates come in increasing id order
+    asc.clear();
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      const int id = v0 + 8 * (e >> 2) + 4 * lh + (e & 3);
+      asc.insert(id < a.V ? acc[rt][e] : -INFINITY, id);
+    }
+    TopList<KT> top;
+#pragma unroll
+    for (int k = 0; k < KT; ++k) top.k[k] = asc.i[k] == INT_MAX ? 0 : cand_key(asc.v[k], asc.i[k]);  // unused slots rank last
+    uint64_t other[KT];
+#pragma unroll
+    for (int k = 0; k < KT; ++k) {
+      const uint32_t lo = __shfl_xor((uint32_t)top.k[k], 32, 64), hi = __shfl_xor((uint32_t)(top.k[k] >> 32), 32, 64);
+      other[k] = ((uint64_t)hi << 32) | lo;
+    }
+#pragma unroll
+    for (int k = 0; k < KT; ++k) top.insert(other[k]);
+    if (lh == 0) {
+#pragma unroll
+      for (int k = 0; k < KT; ++k) lists[((32 * rt + ln) * 4 + w) * KT + k] = top.k[k];
+    }
+  }
+  __syncthreads();
+  for (int r = tid; r < ROWS; r += 256) {
+    TopList<KT> top;
+    top.clear();
+#pragma unroll
+    for (int j = 0; j < 4 * KT; ++j) top.insert(lists[r * 4 * KT + j]);
+    const int row = row0 + r;
+    if (row < a.N) {
+      const size_t o = ((size_t)row * a.n_tiles + tile) * a.K;
+#pragma unroll
+      for (int k = 0; k < KT; ++k)
+        if (k < a.K) a.cand_key[o + k] = top.k[k];
+    }
+  }
+  }
+}
+
 template <int NRT, int KT>  // NRT: 32-row accumulator tiles per wave
 __global__ __launch_bounds__(256, 1) void lm_head_bf16_kernel(LmArgs a) {
   constexpr int ROWS = 32 * NRT; // rows of `hidden` per workgroup
@@ -367,86 +455,7 @@ __global__ __launch_bounds__(256, 1) void lm_head_bf16_kernel(LmArgs a) {
 #ifdef SS_LM_TIMING
   const long long t_ep0 = clock64();
 #endif
-  // ---- epilogue.  acc[rt][e] on lane (ln, lh) is the logit of row row0 + 32*rt + ln and token id
-  // v0 + 8*(e/4) + 4*lh + e%4.  LDS is free by now: the last step ended with a barrier.
-  if constexpr (KT == 0) {
-    // Plain projection: the tile is rounded to bf16 and turned round through LDS ([ROWS] rows of 128
-    // outputs, padded to 272 bytes so that the 8-byte writes of 32 rows spread over the banks), then
-    // leaves in 16-byte pieces, 256 contiguous bytes per row.
-    constexpr int YS = 272;
-    static_assert(ROWS * YS <= 4 * HB, "output tile must fit the hidden buffers");
-#pragma unroll
-    for (int rt = 0; rt < NRT; ++rt)
-#pragma unroll
-      for (int eg = 0; eg < 4; ++eg) {
-        uintx2 pk;
-        pk[0] = pack_bf16x2(acc[rt][4 * eg], acc[rt][4 * eg + 1]);
-        pk[1] = pack_bf16x2(acc[rt][4 * eg + 2], acc[rt][4 * eg + 3]);
-        *reinterpret_cast<uintx2*>(hbuf + (32 * rt + ln) * YS + (32 * w + 8 * eg + 4 * lh) * 2) = pk;
-      }
-    __syncthreads();
-    const bool vec_ok = (a.V % 8) == 0 && ((uintptr_t)a.y & 15) == 0;  // rows of y are 16-byte aligned
-    uint16_t* y = (uint16_t*)a.y;
-    for (int p = tid; p < ROWS * 16; p += 256) {
-      const int r = p >> 4, ch = p & 15;
-      const int row = row0 + r, id0 = tile * 128 + 8 * ch;
-      if (row >= a.N || id0 >= a.V) continue;
-      const uintx4 piece = *reinterpret_cast<const uintx4*>(hbuf + r * YS + ch * 16);
-      uint16_t* dst = y + (size_t)row * a.V + id0;
-      if (vec_ok) {
-        *reinterpret_cast<uintx4*>(dst) = piece;  // V % 8 == 0 and id0 < V: the whole piece is inside
-      } else {
-#pragma unroll
-        for (int j = 0; j < 8; ++j)
-          if (id0 + j < a.V) dst[j] = (uint16_t)(piece[j >> 1] >> (16 * (j & 1)));
-      }
-    }
-    return;
-  } else {
-  // Per row: this lane's 16 candidates go into a K-entry list, the two lanes of a row merge theirs,
-  // the four waves' lists meet in LDS, and one thread per row leaves the workgroup's K best as part
-  // blockIdx.x.
-  uint64_t* lists = reinterpret_cast<uint64_t*>(hbuf);  // [ROWS][4 waves][KT]
-#pragma unroll
-  for (int rt = 0; rt < NRT; ++rt) {
-    TopAsc<KT> asc;  // this lane's candidates come in increasing id order
-    asc.clear();
-#pragma unroll
-    for (int e = 0; e < 16; ++e) {
-      const int id = v0 + 8 * (e >> 2) + 4 * lh + (e & 3);
-      asc.insert(id < a.V ? acc[rt][e] : -INFINITY, id);
-    }
-    TopList<KT> top;
-#pragma unroll
-    for (int k = 0; k < KT; ++k) top.k[k] = asc.i[k] == INT_MAX ? 0 : cand_key(asc.v[k], asc.i[k]);  // unused slots rank last
-    uint64_t other[KT];
-#pragma unroll
-    for (int k = 0; k < KT; ++k) {
-      const uint32_t lo = __shfl_xor((uint32_t)top.k[k], 32, 64), hi = __shfl_xor((uint32_t)(top.k[k] >> 32), 32, 64);
-      other[k] = ((uint64_t)hi << 32) | lo;
-    }
-#pragma unroll
-    for (int k = 0; k < KT; ++k) top.insert(other[k]);
-    if (lh == 0) {
-#pragma unroll
-      for (int k = 0; k < KT; ++k) lists[((32 * rt + ln) * 4 + w) * KT + k] = top.k[k];
-    }
-  }
-  __syncthreads();
-  for (int r = tid; r < ROWS; r += 256) {
-    TopList<KT> top;
-    top.clear();
-#pragma unroll
-    for (int j = 0; j < 4 * KT; ++j) top.insert(lists[r * 4 * KT + j]);
-    const int row = row0 + r;
-    if (row < a.N) {
-      const size_t o = ((size_t)row * a.n_tiles + tile) * a.K;
-#pragma unroll
-      for (int k = 0; k < KT; ++k)
-        if (k < a.K) a.cand_key[o + k] = top.k[k];
-    }
-  }
-  }
+  lm_epilogue<NRT, KT>(a, acc, hbuf, tile, row0, v0, w, tid);
 #ifdef SS_LM_TIMING
   if (lane == 0) {
     long long* dbg = (long long*)(a.cand_key + (size_t)a.N * a.n_tiles * a.K) + 64 + (blockIdx.x * 4 + w) * 8;
@@ -457,6 +466,116 @@ __global__ __launch_bounds__(256, 1) void lm_head_bf16_kernel(LmArgs a) {
     dbg[7] = (long long)__builtin_amdgcn_s_getreg(4 | (31 << 11)) | ((long long)(__builtin_amdgcn_s_getreg(20 | (31 << 11)) & 0xf) << 32);
   }
 #endif
+}
+
+// ------------------------------------------------------------------ bf16 MFMA kernel, W through LDS
+//
+// The flavour for at most 192 rows per workgroup (NRT <= 6).  With few rows the loop above is bound by
+// its W loads, not by the matrix cores: a register load gives every lane 16 bytes of its own row, so one
+// instruction touches 32 lines for 32 bytes each and the L1 spends its tag lookups on them.  Here W
+// takes the road `hidden` takes: direct global->LDS loads of whole 128-byte lines (8 rows per
+// instruction, the same XOR swizzle), each wave loading the 32 rows it owns, and one extra operand read
+// per MFMA round.  A block is hidden (32*NRT rows) followed by W (128 rows), four buffers, filled three
+// blocks ahead; every global load of the loop is hand-written, so the only wait is the one at the end
+// of a step: all loads but the step's own must have landed.
+template <int NRT, int KT>
+__global__ __launch_bounds__(256, 1) void lm_head_bf16_wlds_kernel(LmArgs a) {
+  static_assert(NRT <= 6, "four buffers of hidden and W must fit 160 KB");
+  constexpr int ROWS = 32 * NRT;
+  constexpr int HB = ROWS * 128;   // bytes of one block of `hidden`
+  constexpr int BB = HB + 128 * 128;  // ... and of W behind it
+  constexpr int NLD = NRT + 4;     // global loads per wave and step
+  extern __shared__ __attribute__((aligned(16))) unsigned char hbuf[];  // [4][BB], reused by the epilogue
+  const int tid = threadIdx.x, lane = tid & 63, ln = lane & 31, lh = lane >> 5;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int xcd = blockIdx.x & 7, turn = blockIdx.x >> 3;  // as in the kernel above
+  const int tile = (turn / a.n_chunks) * 8 + xcd;
+  if (tile >= a.n_tiles) return;
+  const int v0 = tile * 128 + 32 * w;
+  const int row0 = (turn % a.n_chunks) * ROWS;
+  const int d = a.d, n_k = d / 64;
+
+  // load slots of 8 rows x 128 bytes; lane -> (row lane/8 of the slot, chunk position lane%8, which
+  // receives chunk (lane%8) ^ swizzle(row)).  hidden: wave w takes slots w, w+4, ...; W: its own rows.
+  uint32_t h_voff[NRT], w_voff[4];
+#pragma unroll
+  for (int i = 0; i < NRT; ++i) {
+    const int r = 8 * (w + 4 * i) + (lane >> 3);
+    h_voff[i] = ((uint32_t)min(row0 + r, a.N - 1) * (uint32_t)d + (((lane & 7) ^ ((r >> 1) & 7)) * 8)) * 2;
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int r = 8 * i + (lane >> 3);  // row of this wave's 32
+    w_voff[i] = ((uint32_t)min(v0 + r, a.V - 1) * (uint32_t)d + (((lane & 7) ^ ((r >> 1) & 7)) * 8)) * 2;
+  }
+  const uint32_t lds0 = (uint32_t)(uintptr_t)hbuf;
+  // operand reads: row 32*rt + ln of hidden (row ln of this wave's W), logical chunk 2*c + lh
+  int hrd[4];
+#pragma unroll
+  for (int c = 0; c < 4; ++c) hrd[c] = ln * 128 + (((2 * c + lh) ^ ((ln >> 1) & 7)) * 16);
+  const int w_rd = HB + w * (32 * 128);
+
+  floatx16 acc[NRT];
+#pragma unroll
+  for (int rt = 0; rt < NRT; ++rt)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[rt][e] = 0.f;
+
+  auto load_block = [&](int J, int buf) {
+    const unsigned char* hb = (const unsigned char*)a.hidden + (size_t)J * 128;
+    const unsigned char* wb = (const unsigned char*)a.W + (size_t)J * 128;
+#pragma unroll
+    for (int i = 0; i < NRT; ++i) load_to_lds16(hb, h_voff[i], lds0 + buf * BB + (w + 4 * i) * 1024);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) load_to_lds16(wb, w_voff[i], lds0 + buf * BB + HB + (4 * w + i) * 1024);
+  };
+  constexpr int WAIT_ALL = 0x0F70;                                           // s_waitcnt vmcnt(0)
+  constexpr int WAIT_STEP = 0x0F70 | (NLD & 15) | ((NLD >> 4) << 14);        // s_waitcnt vmcnt(NLD)
+  load_block(0, 0);
+  load_block(min(1, n_k - 1), 1);
+  load_block(min(2, n_k - 1), 2);
+  __builtin_amdgcn_s_waitcnt(WAIT_ALL);
+  __syncthreads();
+
+  bf16x8 hop[2][NRT], wop[2];  // operands of the current and of the next round
+#pragma unroll
+  for (int rt = 0; rt < NRT; ++rt)
+    hop[0][rt] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(hbuf + hrd[0] + rt * (32 * 128)));
+  wop[0] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(hbuf + w_rd + hrd[0]));
+  // Step J reads buffer J % 4 (and, for the first round of step J+1, buffer (J+1) % 4: both complete
+  // since the barrier of the step before), and fills buffer (J+3) % 4, which every wave has left at
+  // that barrier.  Past the end the last block is fetched again: no condition in the loop.
+  for (int J = 0; J < n_k; ++J) {
+    const int buf = J & 3;
+    const unsigned char* cur = hbuf + buf * BB;
+    const unsigned char* nxt = hbuf + ((buf + 1) & 3) * BB;
+    const int Jn = min(J + 3, n_k - 1);
+    const unsigned char* h_base = (const unsigned char*)a.hidden + (size_t)Jn * 128;
+    const unsigned char* w_base = (const unsigned char*)a.W + (size_t)Jn * 128;
+    const uint32_t dst = lds0 + ((buf + 3) & 3) * BB;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const unsigned char* src = c < 3 ? cur + hrd[c + 1] : nxt + hrd[0];
+#pragma unroll
+      for (int rt = 0; rt < NRT; ++rt)
+        hop[(c + 1) & 1][rt] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(src + rt * (32 * 128)));
+      wop[(c + 1) & 1] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(src + w_rd));
+#pragma unroll
+      for (int l = (c * NLD) / 4; l < ((c + 1) * NLD) / 4; ++l) {
+        if (l < NRT) load_to_lds16(h_base, h_voff[l], dst + (w + 4 * l) * 1024);
+        else load_to_lds16(w_base, w_voff[l - NRT], dst + HB + (4 * w + (l - NRT)) * 1024);
+      }
+#pragma unroll
+      for (int rt = 0; rt < NRT; ++rt)
+        acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wop[c & 1], hop[c & 1][rt], acc[rt], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    __builtin_amdgcn_s_waitcnt(WAIT_STEP);  // block J+2 has landed
+    __syncthreads();
+  }
+  __builtin_amdgcn_s_waitcnt(WAIT_ALL);  // the redundant tail loads, before LDS is reused
+  __syncthreads();
+  lm_epilogue<NRT, KT>(a, acc, hbuf, tile, row0, v0, w, tid);
 }
 
 // ------------------------------------------------------------------ merge of the parts' candidates
@@ -499,8 +618,15 @@ __global__ __launch_bounds__(64) void lm_head_reduce_kernel(LmArgs a) {
 
 template <int NRT, int KT>
 static int launch_lm_bf16_rk(hipStream_t st, const LmArgs& a) {
-  auto kern = lm_head_bf16_kernel<NRT, KT>;
-  const size_t lds = 4 * (size_t)(32 * NRT) * 128;
+  void (*kern)(LmArgs);
+  size_t lds;
+  if constexpr (NRT <= 6) {
+    kern = lm_head_bf16_wlds_kernel<NRT, KT>;
+    lds = 4 * ((size_t)(32 * NRT) * 128 + 128 * 128);
+  } else {
+    kern = lm_head_bf16_kernel<NRT, KT>;
+    lds = 4 * (size_t)(32 * NRT) * 128;
+  }
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
