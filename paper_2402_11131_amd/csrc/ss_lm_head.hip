@@ -214,19 +214,19 @@ struct TopList {  // the KT best keys seen so far, best first
 };
 
 // The epilogue of both MFMA kernels.  acc[rt][e] on lane (ln, lh) is the logit of row row0 + 32*rt + ln
-// and token id v0 + 8*(e/4) + 4*lh + e%4.  `lds` (at least 512 bytes per row of the tile) must be free:
+// and token id v0 + 8*(e/4) + 4*lh + e%4.  `hbuf` (64*NW + 16 bytes per row of the tile) must be free:
 // the callers end their loops with a barrier.
-template <int NRT, int KT>
+template <int NRT, int KT, int NW>  // NW waves of 32 ids each
 SS_DEV void lm_epilogue(const LmArgs& a, floatx16 (&acc)[NRT], unsigned char* hbuf, int tile, int row0, int v0, int w,
                         int tid) {
   constexpr int ROWS = 32 * NRT;
+  constexpr int TI = 32 * NW;  // ids per tile
   const int lane = tid & 63, ln = lane & 31, lh = lane >> 5;
   if constexpr (KT == 0) {
-    // Plain projection: the tile is rounded to bf16 and turned round through LDS ([ROWS] rows of 128
-    // outputs, padded to 272 bytes so that the 8-byte writes of 32 rows spread over the banks), then
-    // leaves in 16-byte pieces, 256 contiguous bytes per row.
-    constexpr int YS = 272;
-    static_assert(YS <= 512, "output tile must fit 512 bytes per row");
+    // Plain projection: the tile is rounded to bf16 and turned round through LDS ([ROWS] rows of TI
+    // outputs, padded by 16 bytes so that the 8-byte writes of 32 rows spread over the banks), then
+    // leaves in 16-byte pieces, 2*TI contiguous bytes per row.
+    constexpr int YS = 2 * TI + 16;
 #pragma unroll
     for (int rt = 0; rt < NRT; ++rt)
 #pragma unroll
@@ -239,9 +239,9 @@ SS_DEV void lm_epilogue(const LmArgs& a, floatx16 (&acc)[NRT], unsigned char* hb
     __syncthreads();
     const bool vec_ok = (a.V % 8) == 0 && ((uintptr_t)a.y & 15) == 0;  // rows of y are 16-byte aligned
     uint16_t* y = (uint16_t*)a.y;
-    for (int p = tid; p < ROWS * 16; p += 256) {
-      const int r = p >> 4, ch = p & 15;
-      const int row = row0 + r, id0 = tile * 128 + 8 * ch;
+    for (int p = tid; p < ROWS * (TI / 8); p += 64 * NW) {
+      const int r = p / (TI / 8), ch = p % (TI / 8);
+      const int row = row0 + r, id0 = tile * TI + 8 * ch;
       if (row >= a.N || id0 >= a.V) continue;
       const uintx4 piece = *reinterpret_cast<const uintx4*>(hbuf + r * YS + ch * 16);
       uint16_t* dst = y + (size_t)row * a.V + id0;
@@ -258,7 +258,7 @@ SS_DEV void lm_epilogue(const LmArgs& a, floatx16 (&acc)[NRT], unsigned char* hb
   // Per row: this lane's 16 candidates go into a K-entry list, the two lanes of a row merge theirs,
   // the four waves' lists meet in LDS, and one thread per row leaves the workgroup's K best as the
   // part of this vocabulary tile.
-  uint64_t* lists = reinterpret_cast<uint64_t*>(hbuf);  // [ROWS][4 waves][KT]
+  uint64_t* lists = reinterpret_cast<uint64_t*>(hbuf);  // [ROWS][NW waves][KT]
 #pragma unroll
   for (int rt = 0; rt < NRT; ++rt) {
     TopAsc<KT> asc;  // this lane's candidates come in increasing id order
@@ -281,15 +281,15 @@ SS_DEV void lm_epilogue(const LmArgs& a, floatx16 (&acc)[NRT], unsigned char* hb
     for (int k = 0; k < KT; ++k) top.insert(other[k]);
     if (lh == 0) {
 #pragma unroll
-      for (int k = 0; k < KT; ++k) lists[((32 * rt + ln) * 4 + w) * KT + k] = top.k[k];
+      for (int k = 0; k < KT; ++k) lists[((32 * rt + ln) * NW + w) * KT + k] = top.k[k];
     }
   }
   __syncthreads();
-  for (int r = tid; r < ROWS; r += 256) {
+  for (int r = tid; r < ROWS; r += 64 * NW) {
     TopList<KT> top;
     top.clear();
-#pragma unroll
-    for (int j = 0; j < 4 * KT; ++j) top.insert(lists[r * 4 * KT + j]);
+#pragma unroll 16
+    for (int j = 0; j < NW * KT; ++j) top.insert(lists[r * NW * KT + j]);
     const int row = row0 + r;
     if (row < a.N) {
       const size_t o = ((size_t)row * a.n_tiles + tile) * a.K;
@@ -455,7 +455,7 @@ __global__ __launch_bounds__(256, 1) void lm_head_bf16_kernel(LmArgs a) {
 #ifdef SS_LM_TIMING
   const long long t_ep0 = clock64();
 #endif
-  lm_epilogue<NRT, KT>(a, acc, hbuf, tile, row0, v0, w, tid);
+  lm_epilogue<NRT, KT, 4>(a, acc, hbuf, tile, row0, v0, w, tid);
 #ifdef SS_LM_TIMING
   if (lane == 0) {
     long long* dbg = (long long*)(a.cand_key + (size_t)a.N * a.n_tiles * a.K) + 64 + (blockIdx.x * 4 + w) * 8;
@@ -470,37 +470,44 @@ __global__ __launch_bounds__(256, 1) void lm_head_bf16_kernel(LmArgs a) {
 
 // ------------------------------------------------------------------ bf16 MFMA kernel, W through LDS
 //
-// The flavour for at most 192 rows per workgroup (NRT <= 6).  With few rows the loop above is bound by
-// its W loads, not by the matrix cores: a register load gives every lane 16 bytes of its own row, so one
-// instruction touches 32 lines for 32 bytes each and the L1 spends its tag lookups on them.  Here W
-// takes the road `hidden` takes: direct global->LDS loads of whole 128-byte lines (8 rows per
-// instruction, the same XOR swizzle), each wave loading the 32 rows it owns, and one extra operand read
-// per MFMA round.  A block is hidden (32*NRT rows) followed by W (128 rows), four buffers, filled three
-// blocks ahead; every global load of the loop is hand-written, so the only wait is the one at the end
-// of a step: all loads but the step's own must have landed.
-template <int NRT, int KT>
-__global__ __launch_bounds__(256, 1) void lm_head_bf16_wlds_kernel(LmArgs a) {
-  static_assert(NRT <= 6, "four buffers of hidden and W must fit 160 KB");
+// With few rows per workgroup the loop above is bound by its W loads, not by the matrix cores: a
+// register load gives every lane 16 bytes of its own row, so one instruction touches 32 lines for 32
+// bytes each and the L1 spends its tag lookups on them.  Here W takes the road `hidden` takes: direct
+// global->LDS loads of whole 128-byte lines (8 rows per instruction, the same XOR swizzle), each wave
+// loading the 32 rows it owns, and one extra operand read per MFMA round.  A block is hidden (32*NRT
+// rows) followed by W (32*NW rows); NBUF buffers, filled NBUF-1 blocks ahead; every global load of the
+// loop is hand-written, so the only wait is the one at the end of a step: all loads but the step's own
+// must have landed.  NW = 4 waves (tile of 128 ids) or 8 (256 ids, two waves per SIMD).  The 4*NRT
+// hidden load slots are dealt to the waves in rounds; in a last, incomplete round the spare waves load
+// a slot a second time (same bytes to the same place), which keeps the load count equal for all.
+template <int NRT, int KT, int NW, int NBUF>
+__global__ __launch_bounds__(64 * NW, 1) void lm_head_bf16_wlds_kernel(LmArgs a) {
   constexpr int ROWS = 32 * NRT;
-  constexpr int HB = ROWS * 128;   // bytes of one block of `hidden`
-  constexpr int BB = HB + 128 * 128;  // ... and of W behind it
-  constexpr int NLD = NRT + 4;     // global loads per wave and step
-  extern __shared__ __attribute__((aligned(16))) unsigned char hbuf[];  // [4][BB], reused by the epilogue
+  constexpr int TI = 32 * NW;
+  constexpr int HB = ROWS * 128;     // bytes of one block of `hidden`
+  constexpr int BB = HB + TI * 128;  // ... and of W behind it
+  static_assert(NBUF * BB <= 160 * 1024, "buffers must fit 160 KB");
+  static_assert(NBUF * BB >= ROWS * (2 * TI + 16) && NBUF * BB >= ROWS * NW * 64, "epilogue must fit the buffers");
+  constexpr int NH = (4 * NRT + NW - 1) / NW;  // hidden loads per wave and step
+  constexpr int NLD = NH + 4;                  // global loads per wave and step
+  extern __shared__ __attribute__((aligned(16))) unsigned char hbuf[];  // [NBUF][BB], reused by the epilogue
   const int tid = threadIdx.x, lane = tid & 63, ln = lane & 31, lh = lane >> 5;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int xcd = blockIdx.x & 7, turn = blockIdx.x >> 3;  // as in the kernel above
   const int tile = (turn / a.n_chunks) * 8 + xcd;
   if (tile >= a.n_tiles) return;
-  const int v0 = tile * 128 + 32 * w;
+  const int v0 = tile * TI + 32 * w;
   const int row0 = (turn % a.n_chunks) * ROWS;
   const int d = a.d, n_k = d / 64;
 
   // load slots of 8 rows x 128 bytes; lane -> (row lane/8 of the slot, chunk position lane%8, which
-  // receives chunk (lane%8) ^ swizzle(row)).  hidden: wave w takes slots w, w+4, ...; W: its own rows.
-  uint32_t h_voff[NRT], w_voff[4];
+  // receives chunk (lane%8) ^ swizzle(row)).  hidden: wave w takes slots w, w+NW, ...; W: its own rows.
+  uint32_t h_voff[NH], w_voff[4];
+  int h_slot[NH];
 #pragma unroll
-  for (int i = 0; i < NRT; ++i) {
-    const int r = 8 * (w + 4 * i) + (lane >> 3);
+  for (int i = 0; i < NH; ++i) {
+    h_slot[i] = (w + NW * i) % (4 * NRT);
+    const int r = 8 * h_slot[i] + (lane >> 3);
     h_voff[i] = ((uint32_t)min(row0 + r, a.N - 1) * (uint32_t)d + (((lane & 7) ^ ((r >> 1) & 7)) * 8)) * 2;
   }
 #pragma unroll
@@ -525,15 +532,14 @@ __global__ __launch_bounds__(256, 1) void lm_head_bf16_wlds_kernel(LmArgs a) {
     const unsigned char* hb = (const unsigned char*)a.hidden + (size_t)J * 128;
     const unsigned char* wb = (const unsigned char*)a.W + (size_t)J * 128;
 #pragma unroll
-    for (int i = 0; i < NRT; ++i) load_to_lds16(hb, h_voff[i], lds0 + buf * BB + (w + 4 * i) * 1024);
+    for (int i = 0; i < NH; ++i) load_to_lds16(hb, h_voff[i], lds0 + buf * BB + h_slot[i] * 1024);
 #pragma unroll
     for (int i = 0; i < 4; ++i) load_to_lds16(wb, w_voff[i], lds0 + buf * BB + HB + (4 * w + i) * 1024);
   };
-  constexpr int WAIT_ALL = 0x0F70;                                           // s_waitcnt vmcnt(0)
-  constexpr int WAIT_STEP = 0x0F70 | (NLD & 15) | ((NLD >> 4) << 14);        // s_waitcnt vmcnt(NLD)
-  load_block(0, 0);
-  load_block(min(1, n_k - 1), 1);
-  load_block(min(2, n_k - 1), 2);
+  constexpr int WAIT_ALL = 0x0F70;                                     // s_waitcnt vmcnt(0)
+  constexpr int WAIT_STEP = 0x0F70 | (NLD & 15) | ((NLD >> 4) << 14);  // s_waitcnt vmcnt(NLD)
+#pragma unroll
+  for (int j = 0; j < NBUF - 1; ++j) load_block(min(j, n_k - 1), j);
   __builtin_amdgcn_s_waitcnt(WAIT_ALL);
   __syncthreads();
 
@@ -542,40 +548,54 @@ __global__ __launch_bounds__(256, 1) void lm_head_bf16_wlds_kernel(LmArgs a) {
   for (int rt = 0; rt < NRT; ++rt)
     hop[0][rt] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(hbuf + hrd[0] + rt * (32 * 128)));
   wop[0] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(hbuf + w_rd + hrd[0]));
-  // Step J reads buffer J % 4 (and, for the first round of step J+1, buffer (J+1) % 4: both complete
-  // since the barrier of the step before), and fills buffer (J+3) % 4, which every wave has left at
-  // that barrier.  Past the end the last block is fetched again: no condition in the loop.
+  // Step J reads buffer J % NBUF and fills the buffer before it, which every wave has left at the
+  // barrier of the step before; that barrier published every block up to J + NBUF - 3.  With four
+  // buffers this includes block J+1, so the operands of step J+1's first round are read during the last
+  // round of step J (no LDS latency after the barrier); with three they are read after the barrier.
+  // Past the end the last block is fetched again: no condition in the loop.
+  constexpr bool EARLY = NBUF >= 4;
+  int buf = 0;
   for (int J = 0; J < n_k; ++J) {
-    const int buf = J & 3;
+    const int buf_next = buf + 1 == NBUF ? 0 : buf + 1;
+    const int buf_fill = buf == 0 ? NBUF - 1 : buf - 1;
     const unsigned char* cur = hbuf + buf * BB;
-    const unsigned char* nxt = hbuf + ((buf + 1) & 3) * BB;
-    const int Jn = min(J + 3, n_k - 1);
+    const unsigned char* nxt = hbuf + buf_next * BB;
+    const int Jn = min(J + NBUF - 1, n_k - 1);
     const unsigned char* h_base = (const unsigned char*)a.hidden + (size_t)Jn * 128;
     const unsigned char* w_base = (const unsigned char*)a.W + (size_t)Jn * 128;
-    const uint32_t dst = lds0 + ((buf + 3) & 3) * BB;
+    const uint32_t dst = lds0 + buf_fill * BB;
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-      const unsigned char* src = c < 3 ? cur + hrd[c + 1] : nxt + hrd[0];
+      if (c < 3 || EARLY) {
+        const unsigned char* src = c < 3 ? cur + hrd[c + 1] : nxt + hrd[0];
 #pragma unroll
-      for (int rt = 0; rt < NRT; ++rt)
-        hop[(c + 1) & 1][rt] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(src + rt * (32 * 128)));
-      wop[(c + 1) & 1] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(src + w_rd));
+        for (int rt = 0; rt < NRT; ++rt)
+          hop[(c + 1) & 1][rt] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(src + rt * (32 * 128)));
+        wop[(c + 1) & 1] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(src + w_rd));
+      }
 #pragma unroll
       for (int l = (c * NLD) / 4; l < ((c + 1) * NLD) / 4; ++l) {
-        if (l < NRT) load_to_lds16(h_base, h_voff[l], dst + (w + 4 * l) * 1024);
-        else load_to_lds16(w_base, w_voff[l - NRT], dst + HB + (4 * w + (l - NRT)) * 1024);
+        if (l < NH) load_to_lds16(h_base, h_voff[l], dst + h_slot[l] * 1024);
+        else load_to_lds16(w_base, w_voff[l - NH], dst + HB + (4 * w + (l - NH)) * 1024);
       }
 #pragma unroll
       for (int rt = 0; rt < NRT; ++rt)
         acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wop[c & 1], hop[c & 1][rt], acc[rt], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
     }
-    __builtin_amdgcn_s_waitcnt(WAIT_STEP);  // block J+2 has landed
+    buf = buf_next;
+    __builtin_amdgcn_s_waitcnt(WAIT_STEP);  // all blocks but the one this step asked for have landed
     __syncthreads();
+    if (!EARLY) {
+#pragma unroll
+      for (int rt = 0; rt < NRT; ++rt)
+        hop[0][rt] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(nxt + hrd[0] + rt * (32 * 128)));
+      wop[0] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(nxt + hrd[0] + w_rd));
+    }
   }
   __builtin_amdgcn_s_waitcnt(WAIT_ALL);  // the redundant tail loads, before LDS is reused
   __syncthreads();
-  lm_epilogue<NRT, KT>(a, acc, hbuf, tile, row0, v0, w, tid);
+  lm_epilogue<NRT, KT, NW>(a, acc, hbuf, tile, row0, v0, w, tid);
 }
 
 // ------------------------------------------------------------------ merge of the parts' candidates
@@ -616,12 +636,22 @@ __global__ __launch_bounds__(64) void lm_head_reduce_kernel(LmArgs a) {
   }
 }
 
-template <int NRT, int KT>
+struct LmFlavour {
+  int nrt;   // 32-row tiles per workgroup
+  int wide;  // 0: 4 waves, tile of 128 ids; 1: 8 waves, tile of 256 ids (NRT <= 5, W through LDS)
+};
+
+template <int NRT, int KT, int WIDE>
 static int launch_lm_bf16_rk(hipStream_t st, const LmArgs& a) {
   void (*kern)(LmArgs);
   size_t lds;
-  if constexpr (NRT <= 6) {
-    kern = lm_head_bf16_wlds_kernel<NRT, KT>;
+  int threads = 256;
+  if constexpr (WIDE == 1) {
+    kern = lm_head_bf16_wlds_kernel<NRT, KT, 8, 3>;
+    lds = 3 * ((size_t)(32 * NRT) * 128 + 256 * 128);
+    threads = 512;
+  } else if constexpr (NRT <= 6) {
+    kern = lm_head_bf16_wlds_kernel<NRT, KT, 4, 4>;
     lds = 4 * ((size_t)(32 * NRT) * 128 + 128 * 128);
   } else {
     kern = lm_head_bf16_kernel<NRT, KT>;
@@ -635,53 +665,87 @@ static int launch_lm_bf16_rk(hipStream_t st, const LmArgs& a) {
     attr_set = true;
   }
   const dim3 grid(8 * a.n_chunks * ceil_div(a.n_tiles, 8));
-  hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, a);
+  hipLaunchKernelGGL(kern, grid, dim3(threads), lds, st, a);
   return SS_OK;
 }
-template <int NRT>
+template <int NRT, int WIDE>
 static int launch_lm_bf16_r(int KT, hipStream_t st, const LmArgs& a) {
   switch (KT) {
-    case 0: return launch_lm_bf16_rk<NRT, 0>(st, a);
-    case 1: return launch_lm_bf16_rk<NRT, 1>(st, a);
-    case 4: return launch_lm_bf16_rk<NRT, 4>(st, a);
-    default: return launch_lm_bf16_rk<NRT, 8>(st, a);
+    case 0: return launch_lm_bf16_rk<NRT, 0, WIDE>(st, a);
+    case 1: return launch_lm_bf16_rk<NRT, 1, WIDE>(st, a);
+    case 4: return launch_lm_bf16_rk<NRT, 4, WIDE>(st, a);
+    default: return launch_lm_bf16_rk<NRT, 8, WIDE>(st, a);
   }
 }
-// Rows go to the workgroups in n_chunks chunks of 32*NRT rows; a.n_chunks must be set.
-static int launch_lm_bf16(int NRT, int KT, hipStream_t st, const LmArgs& a) {
-  switch (NRT) {
-    case 1: return launch_lm_bf16_r<1>(KT, st, a);
-    case 2: return launch_lm_bf16_r<2>(KT, st, a);
-    case 3: return launch_lm_bf16_r<3>(KT, st, a);
-    case 4: return launch_lm_bf16_r<4>(KT, st, a);
-    case 5: return launch_lm_bf16_r<5>(KT, st, a);
-    case 6: return launch_lm_bf16_r<6>(KT, st, a);
-    case 7: return launch_lm_bf16_r<7>(KT, st, a);
-    case 8: return launch_lm_bf16_r<8>(KT, st, a);
-    case 9: return launch_lm_bf16_r<9>(KT, st, a);
-    default: return launch_lm_bf16_r<10>(KT, st, a);
+// Rows go to the workgroups in n_chunks chunks of 32*NRT rows; a.n_chunks and a.n_tiles must be set
+// for the flavour (tiles of 256 ids if f.wide).
+static int launch_lm_bf16(LmFlavour f, int KT, hipStream_t st, const LmArgs& a) {
+  if (f.wide) {
+    switch (f.nrt) {
+      case 1: return launch_lm_bf16_r<1, 1>(KT, st, a);
+      case 2: return launch_lm_bf16_r<2, 1>(KT, st, a);
+      case 3: return launch_lm_bf16_r<3, 1>(KT, st, a);
+      case 4: return launch_lm_bf16_r<4, 1>(KT, st, a);
+      default: return launch_lm_bf16_r<5, 1>(KT, st, a);
+    }
+  }
+  switch (f.nrt) {
+    case 1: return launch_lm_bf16_r<1, 0>(KT, st, a);
+    case 2: return launch_lm_bf16_r<2, 0>(KT, st, a);
+    case 3: return launch_lm_bf16_r<3, 0>(KT, st, a);
+    case 4: return launch_lm_bf16_r<4, 0>(KT, st, a);
+    case 5: return launch_lm_bf16_r<5, 0>(KT, st, a);
+    case 6: return launch_lm_bf16_r<6, 0>(KT, st, a);
+    case 7: return launch_lm_bf16_r<7, 0>(KT, st, a);
+    case 8: return launch_lm_bf16_r<8, 0>(KT, st, a);
+    case 9: return launch_lm_bf16_r<9, 0>(KT, st, a);
+    default: return launch_lm_bf16_r<10, 0>(KT, st, a);
   }
 }
 
-// Rows per workgroup, in 32-row tiles, for the search flavour: as many as fit (W is then read once per
-// chunk), chunks of equal size.
-static int lm_row_tiles(int N, int* n_chunks) {
+// Which MFMA kernel, how many rows per workgroup and how many row chunks.  A compute unit holds one
+// workgroup (LDS), so the aim is one round of at most 256 workgroups with as many rows each as that
+// allows: rows are cut into more chunks while the workgroups still fit the chip (the chunks of a
+// vocabulary tile share its part of W in L2).  Up to 192 rows, or few outputs (V <= 8192): 4 waves,
+// tiles of 128 ids.  Otherwise 8 waves, tiles of 256 ids, at most 160 rows: measured faster than both
+// the 4-wave tile with 160 rows and the 320-row tile of the register-fed kernel (LM head of
+// 320 x 4096 x 32000: 92 against 112 us; projection to 22016 outputs: 66 against 76 us).
+static LmFlavour lm_choose(int N, int V, LmArgs* a) {
   const int n32 = ceil_div(N, 32);
-  *n_chunks = ceil_div(n32, 10);
-  return ceil_div(n32, *n_chunks);
+  const int tiles128 = ceil_div(V, 128), tiles256 = ceil_div(V, 256);
+  LmFlavour f;
+  int c, cap;
+  if (n32 <= 6 || tiles128 <= 64) {
+    f.wide = 0;
+    cap = 6;
+    c = 256 / tiles128;
+    a->n_tiles = tiles128;
+  } else {
+    f.wide = 1;
+    cap = 5;
+    c = 256 / tiles256;
+    a->n_tiles = tiles256;
+  }
+  const int c_min = ceil_div(n32, cap);
+  c = c < c_min ? c_min : (c > n32 ? n32 : c);
+  f.nrt = ceil_div(n32, c);
+  a->n_chunks = ceil_div(n32, f.nrt);
+  return f;
 }
 
-// The same for the plain projection, whose output dimension is often too small to give every compute
-// unit a workgroup: rows are cut into more chunks while the workgroups still fit the chip in one round
-// (256 compute units, one workgroup each).  The chunks of a vocabulary tile share its part of W in L2.
-static int linear_row_tiles(int N, int n_tiles, int* n_chunks) {
+// Tuning aid: "<row tiles>" or "<row tiles>w" in the environment variable replaces the chosen flavour.
+static void lm_flavour_override(const char* var, int N, int V, LmFlavour* f, LmArgs* a) {
+  const char* e = getenv(var);
+  if (!e) return;
+  char* end = nullptr;
+  const long want = strtol(e, &end, 10);
+  const int wide = end && *end == 'w';
+  if (want < 1 || want > (wide ? 5 : 10)) return;
   const int n32 = ceil_div(N, 32);
-  int c = 256 / n_tiles;
-  c = c < 1 ? 1 : (c > n32 ? n32 : c);
-  int nrt = ceil_div(n32, c);
-  if (nrt > 10) nrt = 10;
-  *n_chunks = ceil_div(n32, nrt);
-  return nrt;
+  a->n_chunks = ceil_div(n32, (int)want);
+  f->nrt = ceil_div(n32, a->n_chunks);
+  f->wide = wide;
+  a->n_tiles = ceil_div(V, wide ? 256 : 128);
 }
 
 // Candidate parts per row: one per vocabulary tile (64 ids in the fp32 kernel, 128 in the MFMA kernel).
@@ -737,10 +801,11 @@ int ss_lm_head_argmax_topk(const void* hidden, const void* W, int N, int d, int 
     SS_REQUIRE(grid.y <= 65535, SS_ERR_UNSUPPORTED, "%s: N too large", fn);
     hipLaunchKernelGGL(lm_head_f32_kernel<false>, grid, dim3(256), 0, st, a);
   } else {
-    const int NRT = lm_row_tiles(N, &a.n_chunks);
+    LmFlavour f = lm_choose(N, V, &a);
+    lm_flavour_override("SS_LM_FLAVOUR", N, V, &f, &a);
     SS_REQUIRE((long)a.n_chunks * (a.n_tiles + 7) < (1L << 27), SS_ERR_UNSUPPORTED, "%s: N x V too large", fn);
     const int KT = K == 1 ? 1 : (K <= 4 ? 4 : 8);
-    if (int rc = launch_lm_bf16(NRT, KT, st, a)) return rc;
+    if (int rc = launch_lm_bf16(f, KT, st, a)) return rc;
   }
   if (int rc = check_launch(fn)) return rc;
   hipLaunchKernelGGL(lm_head_reduce_kernel, dim3(N), dim3(64), 0, st, a);
@@ -767,16 +832,10 @@ int ss_linear_rows(const void* x, const void* W, int N, int d, int V, int dtype,
     SS_REQUIRE(grid.y <= 65535, SS_ERR_UNSUPPORTED, "%s: N too large", fn);
     hipLaunchKernelGGL(lm_head_f32_kernel<true>, grid, dim3(256), 0, st, a);
   } else {
-    int NRT = linear_row_tiles(N, a.n_tiles, &a.n_chunks);
-    if (const char* e = getenv("SS_LINEAR_ROW_TILES")) {  // tuning aid: rows per workgroup / 32
-      const int want = atoi(e);
-      if (want >= 1 && want <= 10) {
-        a.n_chunks = ceil_div(ceil_div(N, 32), want);
-        NRT = ceil_div(ceil_div(N, 32), a.n_chunks);
-      }
-    }
+    LmFlavour f = lm_choose(N, V, &a);
+    lm_flavour_override("SS_LINEAR_FLAVOUR", N, V, &f, &a);
     SS_REQUIRE((long)a.n_chunks * (a.n_tiles + 7) < (1L << 27), SS_ERR_UNSUPPORTED, "%s: N x V too large", fn);
-    if (int rc = launch_lm_bf16(NRT, 0, st, a)) return rc;
+    if (int rc = launch_lm_bf16(f, 0, st, a)) return rc;
   }
   return check_launch(fn);
 }
