@@ -133,35 +133,26 @@ __global__ __launch_bounds__(256) void lm_head_f32_kernel(LmArgs a) {
 // over the vocabulary is mostly a per-lane affair: no logit is ever exchanged
 // between lanes, only K-entry candidate lists.
 //
-// Workgroup = 4 waves; tile = 128 token ids x 32*NRT rows; wave w owns ids
-// [32*w, 32*w+32) and all rows: NRT accumulator tiles (160 accumulation registers
-// for NRT = 10).  With N <= 320 one workgroup column covers all rows, so W is read
-// from HBM exactly once, and the 250 workgroups of a 32000-token vocabulary fill
-// the chip once.  Each workgroup has to pull all of `hidden` through its L1, which
-// makes L2 -> compute-unit traffic (hidden once per workgroup, W once) the
-// resource to watch: requests are full 128-byte lines throughout.
-//
-// Feeding the matrix cores.  Features go in blocks of 64 (one line per row).
-// W rows belong to one wave only, so they are loaded straight into operand
-// registers: lane (m, h) takes bytes [32*c + 16*h, +16) of row m for step c, i.e.
-// step c covers features 64*J + 16*c .. +15 and a load instruction touches 32
-// lines with 32 contiguous bytes each.  Four blocks are in flight per wave (the
-// ring is filled three blocks ahead of use): 12 KB per wave against the HBM
-// latency, with one wave per SIMD.  `hidden` is shared by the waves and goes
-// through LDS: four buffers of 32*NRT rows x 128 bytes, filled three blocks ahead
-// by direct global->LDS loads (no staging registers and, more important, no
-// ds_write: LDS stores of this size run at a quarter of the read rate).  Such a
-// load writes lane l's 16 bytes to (base + 16*l), so the LDS image is row-major;
-// the chunks of a row are XOR-swizzled on the global side (lane (row r, position
-// q) fetches chunk q ^ ((r >> 1) & 7)), which makes the operand reads (32 rows x
-// one chunk, 16 lanes per LDS cycle over 64 banks) conflict free.  One barrier
-// per block publishes the next buffer.  These loads are inline assembly (the
+// Workgroup = NW waves (4 or 8); tile = 32*NW token ids x 32*NRT rows; wave w owns
+// ids [32*w, 32*w+32) and all rows of the tile: NRT accumulator tiles.  Rows beyond
+// one tile go in equal chunks; the grid is one-dimensional and XCD-aware (below).
+// Features go in blocks of 64 (one 128-byte line per row).  Both operands reach LDS
+// by direct global->LDS loads (no staging registers and no ds_write: LDS stores of
+// this size run at a quarter of the read rate).  Such a load writes lane l's 16
+// bytes to (base + 16*l), so the LDS image is row-major; the chunks of a row are
+// XOR-swizzled on the global side (lane (row r, position q) fetches chunk
+// q ^ ((r >> 1) & 7)), which makes the operand reads (32 rows x one chunk, 16 lanes
+// per LDS cycle over 64 banks) conflict free.  These loads are inline assembly (the
 // compiler would drain the memory counter before every LDS read if it knew of
-// them), so the wait for them is written by hand: loads complete in order, a step
-// issues its `hidden` loads before its W loads, and at the end of step J
-// everything but the loads of step J and the W loads of step J-1 must have
-// landed.  The compiler's own waits for W registers count only W loads and
-// therefore wait for a little more than they need (W of the block after next).
+// them), so the wait for them is written by hand; loads complete in order.
+//
+// An earlier version fed W straight into operand registers (every lane 16 bytes of
+// its own row: one instruction touches 32 lines for 32 bytes each) and kept all 320
+// rows of the headline workload in one workgroup.  Taking loads out one kind at a
+// time showed it bound by exactly those W loads (the L1 spends its tag lookups on
+// them), most of all with few rows per workgroup; W through LDS with whole lines
+// took the projection 4096 -> 4096 on 320 rows from 42 to 23 us and, as the
+// 8-wave tile of 256 ids x 160 rows, the 320 x 4096 x 32000 LM head from 112 to 92 us.
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 
 // 16 bytes per lane from (sbase + voff) to LDS address lds_addr + 16*lane.
@@ -301,187 +292,14 @@ SS_DEV void lm_epilogue(const LmArgs& a, floatx16 (&acc)[NRT], unsigned char* hb
   }
 }
 
-template <int NRT, int KT>  // NRT: 32-row accumulator tiles per wave
-__global__ __launch_bounds__(256, 1) void lm_head_bf16_kernel(LmArgs a) {
-  constexpr int ROWS = 32 * NRT; // rows of `hidden` per workgroup
-  constexpr int HB = ROWS * 128; // bytes of one block of `hidden` in LDS
-  constexpr int HL = NRT;        // 16-byte chunks of it per thread
-  extern __shared__ __attribute__((aligned(16))) unsigned char hbuf[];  // [4][HB], reused by the epilogue
-#ifdef SS_LM_TIMING
-  const long long t_entry = clock64();
-#endif
-  const int tid = threadIdx.x, lane = tid & 63, ln = lane & 31, lh = lane >> 5;
-  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-  // Workgroup -> (vocabulary tile, row chunk).  Workgroups are dealt to the eight XCDs in turn; the row
-  // chunks of one vocabulary tile take consecutive turns of ONE XCD, so that they run together and
-  // share that tile of W in its L2.
-  const int xcd = blockIdx.x & 7, turn = blockIdx.x >> 3;
-  const int tile = (turn / a.n_chunks) * 8 + xcd;
-  if (tile >= a.n_tiles) return;
-  const int v0 = tile * 128 + 32 * w;             // first token id of this wave
-  const int row0 = (turn % a.n_chunks) * ROWS;    // first row of this workgroup
-  const int d = a.d, n_k = d / 64;
-
-  // Sources as 32-bit byte offsets from a scalar base that moves with the feature block, so that a
-  // load needs no vector arithmetic (the host checks that the matrices are below 2 GiB).  W operand:
-  // row v0 + ln, bytes 16*lh.. of each 32-byte piece; ids past the vocabulary are clamped and their
-  // logits dropped later.  Rows of hidden past N are clamped and dropped later as well.
-  const uint32_t w_voff = ((uint32_t)min(v0 + ln, a.V - 1) * (uint32_t)d + 8 * lh) * 2;
-  // hidden: 1 KB load slots of 8 rows; wave w takes slots w, w+4, ...; lane -> (row lane/8 of the slot,
-  // chunk position lane%8)
-  uint32_t h_voff[HL];
-#pragma unroll
-  for (int i = 0; i < HL; ++i) {
-    const int r = 8 * (w + 4 * i) + (lane >> 3);
-    h_voff[i] = ((uint32_t)min(row0 + r, a.N - 1) * (uint32_t)d + (((lane & 7) ^ ((r >> 1) & 7)) * 8)) * 2;
-  }
-  const uint32_t lds0 = (uint32_t)(uintptr_t)hbuf;
-  // hidden operand reads: row 32*rt + ln, logical chunk 2*c + lh
-  int hrd[4];
-#pragma unroll
-  for (int c = 0; c < 4; ++c) hrd[c] = ln * 128 + (((2 * c + lh) ^ ((ln >> 1) & 7)) * 16);
-
-  floatx16 acc[NRT];
-#pragma unroll
-  for (int rt = 0; rt < NRT; ++rt)
-#pragma unroll
-    for (int e = 0; e < 16; ++e) acc[rt][e] = 0.f;
-
-  uintx4 wq[4][4];   // ring of W blocks in flight: [block % 4][step]
-
-  auto load_w = [&](int J, uintx4 (&dst)[4]) {
-    const unsigned char* base = (const unsigned char*)a.W + (size_t)J * 128;
-#pragma unroll
-    for (int c = 0; c < 4; ++c) dst[c] = *reinterpret_cast<const uintx4*>(base + w_voff + 32 * c);
-  };
-  auto load_h = [&](int J, int buf) {  // block J -> LDS buffer buf
-    const unsigned char* base = (const unsigned char*)a.hidden + (size_t)J * 128;
-#pragma unroll
-    for (int i = 0; i < HL; ++i) load_to_lds16(base, h_voff[i], lds0 + buf * HB + (w + 4 * i) * 1024);
-  };
-
-  // prologue: hidden blocks 0..2 in LDS, W blocks 0..2 on their way
-  constexpr int WAIT_ALL = 0x0F70;  // s_waitcnt vmcnt(0)
-  // loads that may be in flight at the end of a step: its own HL + 4 and the 4 W loads of the step before
-  constexpr int PENDING = HL + 8;
-  constexpr int WAIT_STEP = 0x0F70 | (PENDING & 15) | ((PENDING >> 4) << 14);  // s_waitcnt vmcnt(PENDING)
-  load_h(0, 0);
-  load_h(min(1, n_k - 1), 1);
-  load_h(min(2, n_k - 1), 2);
-  load_w(0, wq[0]);
-  load_w(min(1, n_k - 1), wq[1]);
-  load_w(min(2, n_k - 1), wq[2]);
-  __builtin_amdgcn_s_waitcnt(WAIT_ALL);
-  __syncthreads();
-
-  // Block J: W from ring slot J % 4, hidden from LDS buffer J % 4.  At the start of step J the buffers
-  // of blocks J and J+1 are complete (published by the previous barrier): the operand reads of a step's
-  // first MFMA round are issued during the last round of the step before, so that no LDS latency is
-  // exposed after the barrier.  A step starts hidden block J+3 (into the buffer block J-1 was read
-  // from: every wave passed the previous barrier since) and W block J+3 (into the slot block J-1
-  // left), and ends when hidden block J+2 has landed.  Past the end the last block is fetched again
-  // instead, which keeps the steps free of conditions (a condition around the MFMAs would cost a
-  // register copy per accumulator).
-  // A step is four MFMA rounds (16 features each, NRT MFMAs).  The L1 takes a load instruction of a
-  // wave only every ~18 cycles and the four waves share it, so the step's loads are dealt to the
-  // rounds and, inside a round, placed between the MFMAs (scheduling groups) instead of stalling the
-  // wave in a burst.  The operand reads of a round are issued in the round before.
-  int buf = 0;
-#ifdef SS_LM_TIMING
-  long long tacc[4] = {0, 0, 0, 0}, t_last = clock64();
-#define SS_LT(i) { __builtin_amdgcn_sched_barrier(0); const long long t_now_ = clock64(); tacc[i] += t_now_ - t_last; t_last = t_now_; __builtin_amdgcn_sched_barrier(0); }
-#else
-#define SS_LT(i)
-#endif
-  bf16x8 hop[2][NRT];  // hidden operands of the current and of the next round
-#pragma unroll
-  for (int rt = 0; rt < NRT; ++rt)
-    hop[0][rt] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(hbuf + hrd[0] + rt * (32 * 128)));
-  auto step = [&](int J, uintx4 (&w_now)[4], uintx4 (&w_next)[4]) {
-    const unsigned char* hb = hbuf + buf * HB;
-    const unsigned char* hb_next = hbuf + ((buf + 1) & 3) * HB;
-    const int Jn = min(J + 3, n_k - 1);
-    const unsigned char* h_base = (const unsigned char*)a.hidden + (size_t)Jn * 128;
-    const unsigned char* w_base = (const unsigned char*)a.W + (size_t)Jn * 128;
-    const uint32_t h_dst = lds0 + ((buf + 3) & 3) * HB + w * 1024;  // buffer (J + 3) % 4
-    constexpr int NLD = HL + 4;  // global loads of the step: hidden first, then W
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      const unsigned char* src = c < 3 ? hb + hrd[c + 1] : hb_next + hrd[0];
-#pragma unroll
-      for (int rt = 0; rt < NRT; ++rt)
-        hop[(c + 1) & 1][rt] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(src + rt * (32 * 128)));
-      int n_w = 0;
-#pragma unroll
-      for (int l = (c * NLD) / 4; l < ((c + 1) * NLD) / 4; ++l) {
-        if (l < HL) {
-          load_to_lds16(h_base, h_voff[l], h_dst + l * 4096);
-        } else {
-          w_next[l - HL] = *reinterpret_cast<const uintx4*>(w_base + w_voff + 32 * (l - HL));
-          ++n_w;
-        }
-      }
-      const bf16x8 wop = __builtin_bit_cast(bf16x8, w_now[c]);
-#pragma unroll
-      for (int rt = 0; rt < NRT; ++rt)
-        acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wop, hop[c & 1][rt], acc[rt], 0, 0, 0);
-#pragma unroll
-      for (int i = 0; i < NRT; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                // MFMA
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                // one operand read of the next round
-        if (i < n_w) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // global load
-      }
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    buf = (buf + 1) & 3;
-    SS_LT(1);
-    __builtin_amdgcn_s_waitcnt(WAIT_STEP);  // hidden block J+2 has landed (and W block J+1)
-    __syncthreads();
-    SS_LT(3);
-  };
-  int J = 0;
-  for (; J + 4 <= n_k; J += 4) {
-    step(J, wq[0], wq[3]);
-    step(J + 1, wq[1], wq[0]);
-    step(J + 2, wq[2], wq[1]);
-    step(J + 3, wq[3], wq[2]);
-  }
-  if (J < n_k) step(J, wq[0], wq[3]);
-  if (J + 1 < n_k) step(J + 1, wq[1], wq[0]);
-  if (J + 2 < n_k) step(J + 2, wq[2], wq[1]);
-  __builtin_amdgcn_s_waitcnt(WAIT_ALL);  // the redundant tail loads, before LDS is reused
-  __syncthreads();
-
-#ifdef SS_LM_TIMING
-  const long long t_ep0 = clock64();
-#endif
-  lm_epilogue<NRT, KT, 4>(a, acc, hbuf, tile, row0, v0, w, tid);
-#ifdef SS_LM_TIMING
-  if (lane == 0) {
-    long long* dbg = (long long*)(a.cand_key + (size_t)a.N * a.n_tiles * a.K) + 64 + (blockIdx.x * 4 + w) * 8;
-    for (int i = 0; i < 4; ++i) dbg[i] = tacc[i];
-    dbg[4] = clock64() - t_ep0;
-    dbg[5] = n_k;
-    dbg[6] = clock64() - t_entry;
-    dbg[7] = (long long)__builtin_amdgcn_s_getreg(4 | (31 << 11)) | ((long long)(__builtin_amdgcn_s_getreg(20 | (31 << 11)) & 0xf) << 32);
-  }
-#endif
-}
-
-// ------------------------------------------------------------------ bf16 MFMA kernel, W through LDS
-//
-// With few rows per workgroup the loop above is bound by its W loads, not by the matrix cores: a
-// register load gives every lane 16 bytes of its own row, so one instruction touches 32 lines for 32
-// bytes each and the L1 spends its tag lookups on them.  Here W takes the road `hidden` takes: direct
-// global->LDS loads of whole 128-byte lines (8 rows per instruction, the same XOR swizzle), each wave
-// loading the 32 rows it owns, and one extra operand read per MFMA round.  A block is hidden (32*NRT
-// rows) followed by W (32*NW rows); NBUF buffers, filled NBUF-1 blocks ahead; every global load of the
-// loop is hand-written, so the only wait is the one at the end of a step: all loads but the step's own
-// must have landed.  NW = 4 waves (tile of 128 ids) or 8 (256 ids, two waves per SIMD).  The 4*NRT
+// A block in LDS is hidden (32*NRT rows) followed by W (32*NW rows, each wave loading the 32 rows it
+// owns); NBUF buffers, filled NBUF-1 blocks ahead; one extra operand read per MFMA round for W.  Every
+// global load of the loop is hand-written, so the only wait is the one before a step's barrier.  NW = 4
+// waves (tile of 128 ids, four buffers) or 8 (256 ids, two waves per SIMD, three buffers).  The 4*NRT
 // hidden load slots are dealt to the waves in rounds; in a last, incomplete round the spare waves load
 // a slot a second time (same bytes to the same place), which keeps the load count equal for all.
 template <int NRT, int KT, int NW, int NBUF>
-__global__ __launch_bounds__(64 * NW, 1) void lm_head_bf16_wlds_kernel(LmArgs a) {
+__global__ __launch_bounds__(64 * NW, 1) void lm_head_bf16_kernel(LmArgs a) {
   constexpr int ROWS = 32 * NRT;
   constexpr int TI = 32 * NW;
   constexpr int HB = ROWS * 128;     // bytes of one block of `hidden`
@@ -493,7 +311,10 @@ __global__ __launch_bounds__(64 * NW, 1) void lm_head_bf16_wlds_kernel(LmArgs a)
   extern __shared__ __attribute__((aligned(16))) unsigned char hbuf[];  // [NBUF][BB], reused by the epilogue
   const int tid = threadIdx.x, lane = tid & 63, ln = lane & 31, lh = lane >> 5;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int xcd = blockIdx.x & 7, turn = blockIdx.x >> 3;  // as in the kernel above
+  // Workgroup -> (vocabulary tile, row chunk).  Workgroups are dealt to the eight XCDs in turn; the row
+  // chunks of one vocabulary tile take consecutive turns of ONE XCD, so that they run together and
+  // share that tile of W in its L2.
+  const int xcd = blockIdx.x & 7, turn = blockIdx.x >> 3;
   const int tile = (turn / a.n_chunks) * 8 + xcd;
   if (tile >= a.n_tiles) return;
   const int v0 = tile * TI + 32 * w;
@@ -537,7 +358,6 @@ __global__ __launch_bounds__(64 * NW, 1) void lm_head_bf16_wlds_kernel(LmArgs a)
     for (int i = 0; i < 4; ++i) load_to_lds16(wb, w_voff[i], lds0 + buf * BB + HB + (4 * w + i) * 1024);
   };
   constexpr int WAIT_ALL = 0x0F70;                                     // s_waitcnt vmcnt(0)
-  constexpr int WAIT_STEP = 0x0F70 | (NLD & 15) | ((NLD >> 4) << 14);  // s_waitcnt vmcnt(NLD)
 #pragma unroll
   for (int j = 0; j < NBUF - 1; ++j) load_block(min(j, n_k - 1), j);
   __builtin_amdgcn_s_waitcnt(WAIT_ALL);
@@ -548,12 +368,16 @@ __global__ __launch_bounds__(64 * NW, 1) void lm_head_bf16_wlds_kernel(LmArgs a)
   for (int rt = 0; rt < NRT; ++rt)
     hop[0][rt] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(hbuf + hrd[0] + rt * (32 * 128)));
   wop[0] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(hbuf + w_rd + hrd[0]));
-  // Step J reads buffer J % NBUF and fills the buffer before it, which every wave has left at the
-  // barrier of the step before; that barrier published every block up to J + NBUF - 3.  With four
-  // buffers this includes block J+1, so the operands of step J+1's first round are read during the last
-  // round of step J (no LDS latency after the barrier); with three they are read after the barrier.
-  // Past the end the last block is fetched again: no condition in the loop.
-  constexpr bool EARLY = NBUF >= 4;
+  // Step J (four MFMA rounds) computes from buffer J % NBUF and asks for block J + NBUF - 1, into the
+  // buffer before its own.  Its one barrier stands before the last round: by then every load older than
+  // the step's own and the NBUF - 3 blocks before them must have landed, which publishes block J+1; the
+  // last round can therefore read the operands of step J+1's first round (no LDS latency is exposed
+  // after a barrier), and no wave reads buffer J % NBUF after that barrier except from registers, so
+  // step J+1 may overwrite it.  Past the end the last block is fetched again: no condition in the loop.
+  constexpr int N012 = (3 * NLD) / 4;                 // loads a step issues before its barrier
+  constexpr int PEND = (NBUF - 3) * NLD + N012;        // loads that may be in flight at the barrier
+  constexpr int WAIT_MID = 0x0F70 | (PEND & 15) | ((PEND >> 4) << 14);
+  static_assert(PEND < 64, "vmcnt is a 6-bit counter");
   int buf = 0;
   for (int J = 0; J < n_k; ++J) {
     const int buf_next = buf + 1 == NBUF ? 0 : buf + 1;
@@ -566,13 +390,15 @@ __global__ __launch_bounds__(64 * NW, 1) void lm_head_bf16_wlds_kernel(LmArgs a)
     const uint32_t dst = lds0 + buf_fill * BB;
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-      if (c < 3 || EARLY) {
-        const unsigned char* src = c < 3 ? cur + hrd[c + 1] : nxt + hrd[0];
-#pragma unroll
-        for (int rt = 0; rt < NRT; ++rt)
-          hop[(c + 1) & 1][rt] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(src + rt * (32 * 128)));
-        wop[(c + 1) & 1] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(src + w_rd));
+      if (c == 3) {
+        __builtin_amdgcn_s_waitcnt(WAIT_MID);
+        __syncthreads();
       }
+      const unsigned char* src = c < 3 ? cur + hrd[c + 1] : nxt + hrd[0];
+#pragma unroll
+      for (int rt = 0; rt < NRT; ++rt)
+        hop[(c + 1) & 1][rt] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(src + rt * (32 * 128)));
+      wop[(c + 1) & 1] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(src + w_rd));
 #pragma unroll
       for (int l = (c * NLD) / 4; l < ((c + 1) * NLD) / 4; ++l) {
         if (l < NH) load_to_lds16(h_base, h_voff[l], dst + h_slot[l] * 1024);
@@ -584,14 +410,6 @@ __global__ __launch_bounds__(64 * NW, 1) void lm_head_bf16_wlds_kernel(LmArgs a)
       __builtin_amdgcn_sched_barrier(0);
     }
     buf = buf_next;
-    __builtin_amdgcn_s_waitcnt(WAIT_STEP);  // all blocks but the one this step asked for have landed
-    __syncthreads();
-    if (!EARLY) {
-#pragma unroll
-      for (int rt = 0; rt < NRT; ++rt)
-        hop[0][rt] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(nxt + hrd[0] + rt * (32 * 128)));
-      wop[0] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uintx4*>(nxt + hrd[0] + w_rd));
-    }
   }
   __builtin_amdgcn_s_waitcnt(WAIT_ALL);  // the redundant tail loads, before LDS is reused
   __syncthreads();
@@ -638,7 +456,7 @@ __global__ __launch_bounds__(64) void lm_head_reduce_kernel(LmArgs a) {
 
 struct LmFlavour {
   int nrt;   // 32-row tiles per workgroup
-  int wide;  // 0: 4 waves, tile of 128 ids; 1: 8 waves, tile of 256 ids (NRT <= 5, W through LDS)
+  int wide;  // 0: 4 waves, tile of 128 ids, nrt <= 6; 1: 8 waves, tile of 256 ids, nrt <= 5
 };
 
 template <int NRT, int KT, int WIDE>
@@ -647,15 +465,12 @@ static int launch_lm_bf16_rk(hipStream_t st, const LmArgs& a) {
   size_t lds;
   int threads = 256;
   if constexpr (WIDE == 1) {
-    kern = lm_head_bf16_wlds_kernel<NRT, KT, 8, 3>;
+    kern = lm_head_bf16_kernel<NRT, KT, 8, 3>;
     lds = 3 * ((size_t)(32 * NRT) * 128 + 256 * 128);
     threads = 512;
-  } else if constexpr (NRT <= 6) {
-    kern = lm_head_bf16_wlds_kernel<NRT, KT, 4, 4>;
-    lds = 4 * ((size_t)(32 * NRT) * 128 + 128 * 128);
   } else {
-    kern = lm_head_bf16_kernel<NRT, KT>;
-    lds = 4 * (size_t)(32 * NRT) * 128;
+    kern = lm_head_bf16_kernel<NRT, KT, 4, 4>;
+    lds = 4 * ((size_t)(32 * NRT) * 128 + 128 * 128);
   }
   static bool attr_set = false;
   if (!attr_set) {
@@ -695,11 +510,7 @@ static int launch_lm_bf16(LmFlavour f, int KT, hipStream_t st, const LmArgs& a) 
     case 3: return launch_lm_bf16_r<3, 0>(KT, st, a);
     case 4: return launch_lm_bf16_r<4, 0>(KT, st, a);
     case 5: return launch_lm_bf16_r<5, 0>(KT, st, a);
-    case 6: return launch_lm_bf16_r<6, 0>(KT, st, a);
-    case 7: return launch_lm_bf16_r<7, 0>(KT, st, a);
-    case 8: return launch_lm_bf16_r<8, 0>(KT, st, a);
-    case 9: return launch_lm_bf16_r<9, 0>(KT, st, a);
-    default: return launch_lm_bf16_r<10, 0>(KT, st, a);
+    default: return launch_lm_bf16_r<6, 0>(KT, st, a);
   }
 }
 
@@ -708,8 +519,8 @@ static int launch_lm_bf16(LmFlavour f, int KT, hipStream_t st, const LmArgs& a) 
 // allows: rows are cut into more chunks while the workgroups still fit the chip (the chunks of a
 // vocabulary tile share its part of W in L2).  Up to 192 rows, or few outputs (V <= 8192): 4 waves,
 // tiles of 128 ids.  Otherwise 8 waves, tiles of 256 ids, at most 160 rows: measured faster than both
-// the 4-wave tile with 160 rows and the 320-row tile of the register-fed kernel (LM head of
-// 320 x 4096 x 32000: 92 against 112 us; projection to 22016 outputs: 66 against 76 us).
+// the 4-wave tile with 160 rows and a 320-row tile fed from registers (LM head of 320 x 4096 x 32000:
+// 92 against 112 us; projection to 22016 outputs: 66 against 76 us).
 static LmFlavour lm_choose(int N, int V, LmArgs* a) {
   const int n32 = ceil_div(N, 32);
   const int tiles128 = ceil_div(V, 128), tiles256 = ceil_div(V, 256);
@@ -740,7 +551,7 @@ static void lm_flavour_override(const char* var, int N, int V, LmFlavour* f, LmA
   char* end = nullptr;
   const long want = strtol(e, &end, 10);
   const int wide = end && *end == 'w';
-  if (want < 1 || want > (wide ? 5 : 10)) return;
+  if (want < 1 || want > (wide ? 5 : 6)) return;
   const int n32 = ceil_div(N, 32);
   a->n_chunks = ceil_div(n32, (int)want);
   f->nrt = ceil_div(n32, a->n_chunks);
