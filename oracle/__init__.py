@@ -191,6 +191,40 @@ def tree_draft(stream_topk, last, bonus, tmpl_parent, tmpl_rank):
     return next_tok, next_parent
 
 
+def lm_head_lse(h, W):
+    """n2.  log-sum-exp over the vocabulary of every row's logits h.W^T -> [N] float64."""
+    h, W = _f32(h), _f32(W)
+    N, d = h.shape
+    lse = np.zeros(N, np.float64)
+    _load().ora_lm_head_lse(_p(h), _p(W), N, d, W.shape[0], _p(lse))
+    return lse
+
+
+def transition_probs(h, W, tok, parent):
+    """n2.  h [B,T,d] = o(M) of the tree nodes, W [V,d]; prob[b,i] = softmax(h[b,parent[i]].W^T)[tok[b,i]],
+    prob[b,0] = 1.  Returns [B,T] float64."""
+    h, W, tok, parent = _f32(h), _f32(W), _i32(tok), _i32(parent)
+    B, T, d = h.shape
+    assert tok.shape == (B, T) and parent.shape == (B, T) and W.shape[1] == d
+    prob = np.zeros((B, T), np.float64)
+    _load().ora_transition_probs(_p(h), _p(W), _p(tok), _p(parent), B, T, d, W.shape[0], _p(prob))
+    return prob
+
+
+def tree_prune(tok, parent, prob, threshold: float):
+    """n2.  Drops every child with prob < threshold and its sub-tree; compacts.  prob is taken in single
+    precision.  Returns dict(keep, tok, parent, old_index [B,T] int32, n_nodes [B] int32)."""
+    tok, parent = _i32(tok), _i32(parent)
+    prob = _f32(prob)
+    B, T = tok.shape
+    assert T <= 64 and parent.shape == (B, T) and prob.shape == (B, T)
+    out = {k: np.zeros((B, T), np.int32) for k in ("keep", "tok", "parent", "old_index")}
+    out["n_nodes"] = np.zeros(B, np.int32)
+    _load().ora_tree_prune(_p(tok), _p(parent), _p(prob), ctypes.c_float(threshold), B, T, _p(out["keep"]),
+                           _p(out["tok"]), _p(out["parent"]), _p(out["old_index"]), _p(out["n_nodes"]))
+    return out
+
+
 def kv_commit(k_new, v_new, k_cache, v_cache, block_table, seq_lens, path, n_accept):
     """n3.  Appends the main-row keys/values of the accepted path (path [B,max_depth+1], n_accept [B]
     as verification returns them) to copies of the caches.  Returns (k_cache, v_cache, new_seq_lens)."""

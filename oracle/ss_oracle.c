@@ -381,6 +381,91 @@ void ora_tree_draft(const int32_t* stream_topk, long batch_stride, int K, const 
 }
 
 /*
+ * n2: parallel tree pruning (Sec. 3.2.3, Appendix A.1 and its generation-step figure).
+ *
+ * Early-exit logits of main row i are zt_i = H(o(M_i)): h [B,T,d] holds o(M), the main-stream hidden
+ * states of the tree nodes after the low-rank map, W [V,d] is the LM head H.  Z_i = softmax(zt_i) are
+ * the normalised early-exit logits, and the transition probability between a parent p and its child c
+ * is Z_p at the child's token: prob[c] = exp(zt_p[tok_c]) / sum_v exp(zt_p[v]).  The root has no
+ * parent: prob[0] = 1.  A token outside [0,V) has probability 0.
+ */
+void ora_lm_head_lse(const float* h, const float* W, int N, int d, int V, double* lse) {
+#pragma omp parallel for schedule(dynamic)
+  for (int n = 0; n < N; n++) {
+    double* z = (double*)malloc(sizeof(double) * (size_t)V);
+    double m = -INFINITY, s = 0.0;
+    for (int v = 0; v < V; v++) {
+      double acc = 0.0;
+      for (int e = 0; e < d; e++) acc += (double)h[(size_t)n * d + e] * (double)W[(size_t)v * d + e];
+      z[v] = acc;
+      if (acc > m) m = acc;
+    }
+    for (int v = 0; v < V; v++) s += exp(z[v] - m);
+    lse[n] = m + log(s);
+    free(z);
+  }
+}
+
+void ora_transition_probs(const float* h, const float* W, const int32_t* tok, const int32_t* parent, int B,
+                          int T, int d, int V, double* prob) {
+  for (int b = 0; b < B; b++) {
+    prob[(size_t)b * T] = 1.0;
+    for (int i = 1; i < T; i++) {
+      const int p = ora_parent(parent + (size_t)b * T, i);
+      const int c = tok[(size_t)b * T + i];
+      const float* hp = h + ((size_t)b * T + p) * d;
+      double m = -INFINITY, s = 0.0, zc = 0.0;
+      double* z = (double*)malloc(sizeof(double) * (size_t)V);
+      for (int v = 0; v < V; v++) {
+        double acc = 0.0;
+        for (int e = 0; e < d; e++) acc += (double)hp[e] * (double)W[(size_t)v * d + e];
+        z[v] = acc;
+        if (acc > m) m = acc;
+      }
+      for (int v = 0; v < V; v++) s += exp(z[v] - m);
+      if (c >= 0 && c < V) zc = exp(z[c] - m) / s;
+      prob[(size_t)b * T + i] = (c >= 0 && c < V) ? zc : 0.0;
+      free(z);
+    }
+  }
+}
+
+/*
+ * A child whose transition probability is below the threshold is pruned together with its sub-tree
+ * (Appendix A.1: the sub-tree starting at the pruned token goes).  The kept nodes keep their order and
+ * are renumbered 0..n-1; new_parent refers to the new numbers; old_index maps back.  Entries from n
+ * on are padding: token -1 (matches no prediction, so verification never accepts it), parent 0,
+ * old_index -1.  prob is what the pruning layer decides on, in single precision.
+ */
+void ora_tree_prune(const int32_t* tok, const int32_t* parent, const float* prob, float threshold, int B,
+                    int T, int32_t* keep, int32_t* new_tok, int32_t* new_parent, int32_t* old_index,
+                    int32_t* n_nodes) {
+  for (int b = 0; b < B; b++) {
+    const int32_t* par = parent + (size_t)b * T;
+    int32_t* kp = keep + (size_t)b * T;
+    int new_of[64];
+    int n = 0;
+    for (int i = 0; i < T; i++) {
+      if (i == 0) kp[i] = 1;
+      else kp[i] = kp[ora_parent(par, i)] && !(prob[(size_t)b * T + i] < threshold);
+      new_of[i] = kp[i] ? n : -1;
+      if (kp[i]) {
+        new_tok[(size_t)b * T + n] = tok[(size_t)b * T + i];
+        new_parent[(size_t)b * T + n] = (i == 0) ? -1 : new_of[ora_parent(par, i)];
+        old_index[(size_t)b * T + n] = i;
+        n++;
+      }
+    }
+    n_nodes[b] = n;
+    for (int i = n; i < T; i++) {
+      new_tok[(size_t)b * T + i] = -1;
+      new_parent[(size_t)b * T + i] = 0;
+      old_index[(size_t)b * T + i] = -1;
+    }
+  }
+}
+
+/*
  * n3: KV-cache commit.  Main-stream keys/values are cached, those of the speculative streams never
  * are (Sec. 3.2.1), and the cache is trimmed back to what was accepted after each generation step
  * (Appendix A.1): of the step's own rows only the main rows of the accepted path stay, appended in
