@@ -198,6 +198,44 @@ int ss_stream_insert(const void* M, const void* fM, const void* P, int B, int T,
                      int dtype, void* X, void* stream);
 
 /*
+ * n2. Parallel tree pruning (Sec. 3.2.3; Appendix A.1 and its generation-step
+ * figure).  Early-exit logits of node i are zt_i = H(o(M_i)): the LM head H = W
+ * applied to the main-stream hidden state after the low-rank map o (two
+ * ss_linear_rows calls).  The transition probability between a parent p and its
+ * child c is the softmax of zt_p at the child's token; a child below the
+ * threshold is pruned with its sub-tree.  Three calls:
+ *
+ * ss_lm_head_logsumexp: lse[n] = log sum_v exp(sum_e hidden[n,e]*W[v,e]); the
+ *  logits never reach memory (a3's loop with another epilogue; same limits and
+ *  the workspace of ss_lm_head_workspace_bytes(N, d, V, 1, dtype)).
+ *  hidden [N,d], W [V,d] of type dtype; lse [N] f32.
+ *
+ * ss_transition_probs: prob[b,0] = 1; for i > 0, with p = parent[b,i] (clamped
+ *  as everywhere) and c = tok[b,i]:
+ *     prob[b,i] = exp(sum_e h[b,p,e]*W[c,e] - lse[b*T + p]),  0 if c is outside [0,V).
+ *  h [B,T,d] = o(M) of the tree nodes (the rows ss_lm_head_logsumexp was given,
+ *  N = B*T), W [V,d], tok/parent [B,T] int32, lse [B*T] f32, prob [B,T] f32.
+ *
+ * ss_tree_prune: keep[b,0] = 1, keep[b,i] = keep[b,p] and not (prob[b,i] <
+ *  threshold), compared in single precision.  Kept nodes keep their order and are
+ *  renumbered 0..n-1: new_tok, new_parent (in new numbers, -1 for the root),
+ *  old_index (the node's number before).  Entries n..T-1 are padding: new_tok -1
+ *  (it matches no prediction, so ss_tree_verify never accepts it), new_parent 0,
+ *  old_index -1.  n_nodes[b] = n.  All arrays [B,T] int32 except n_nodes [B];
+ *  outputs must not alias inputs.  The padded tree is a valid input of every
+ *  other call of this header: rows of padding nodes are computed and ignored.
+ * All pointers are device memory.  B == 0 / N == 0 are no-ops.
+ */
+int ss_lm_head_logsumexp(const void* hidden, const void* W, int N, int d, int V, int dtype, float* lse,
+                         void* workspace, size_t workspace_bytes, void* stream);
+int ss_transition_probs(const void* h, const void* W, const int32_t* tok, const int32_t* parent,
+                        const float* lse, int B, int T, int d, int V, int dtype, float* prob,
+                        void* stream);
+int ss_tree_prune(const int32_t* tok, const int32_t* parent, const float* prob, float threshold, int B,
+                  int T, int32_t* keep, int32_t* new_tok, int32_t* new_parent, int32_t* old_index,
+                  int32_t* n_nodes, void* stream);
+
+/*
  * a4. Greedy ("hard matching") tree verification (Sec. 3.2.2, Appendix A.1):
  * the root is always accepted; node i is accepted iff its parent is accepted
  * and tok[i] equals the main-stream argmax token at its parent.  `last` is the

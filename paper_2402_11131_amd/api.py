@@ -28,6 +28,7 @@ EXPORTS = (
     "ss_version", "ss_last_error", "ss_check_tree_host", "ss_build_mask", "ss_msa_workspace_bytes",
     "ss_msa_attention", "ss_msa_set_split_keys", "ss_lm_head_workspace_bytes", "ss_lm_head_argmax_topk",
     "ss_tree_verify", "ss_tree_draft", "ss_full_tree_template_host", "ss_kv_commit", "ss_linear_rows", "ss_stream_insert",
+    "ss_lm_head_logsumexp", "ss_transition_probs", "ss_tree_prune",
 )
 
 _lib = None
@@ -69,6 +70,9 @@ def load_library() -> ctypes.CDLL:
     lib.ss_kv_commit.argtypes = [vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp, vp]
     lib.ss_linear_rows.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp]
     lib.ss_stream_insert.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp, vp]
+    lib.ss_lm_head_logsumexp.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, sz, vp]
+    lib.ss_transition_probs.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp]
+    lib.ss_tree_prune.argtypes = [vp, vp, vp, c.c_float, i32, i32, vp, vp, vp, vp, vp, vp]
     for name in EXPORTS:
         getattr(lib, name)
     _lib = lib
@@ -338,3 +342,59 @@ def ss_stream_insert(M: torch.Tensor, P: torch.Tensor, fM: Optional[torch.Tensor
     _check(lib.ss_stream_insert(_dev(M, dt, "M"), None if fM is None else _dev(fM, dt, "fM"), _dev(P, dt, "P"),
                                 B, T, gamma, d, code, _dev(X, dt, "X"), _stream()))
     return X
+
+
+def ss_lm_head_logsumexp(hidden: torch.Tensor, W: torch.Tensor, lse: Optional[torch.Tensor] = None,
+                         workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """n2.  lse [N] f32 = log-sum-exp over the vocabulary of hidden [N,d] . W[V,d]^T."""
+    lib = load_library()
+    code = _dtype_code(hidden)
+    dt = hidden.dtype
+    N, d = hidden.shape
+    V = W.shape[0]
+    if tuple(W.shape) != (V, d):
+        raise ValueError("W must be [V,%d]" % d)
+    if lse is None:
+        lse = torch.empty(N, dtype=torch.float32, device=hidden.device)
+    need = ss_lm_head_workspace_bytes(N, d, V, 1, code)
+    if workspace is None:
+        workspace = torch.empty(max(need, 1), dtype=torch.uint8, device=hidden.device)
+    _check(lib.ss_lm_head_logsumexp(_dev(hidden, dt, "hidden"), _dev(W, dt, "W"), N, d, V, code,
+                                    _dev(lse, torch.float32, "lse"), workspace.data_ptr(), workspace.numel(), _stream()))
+    return lse
+
+
+def ss_transition_probs(h: torch.Tensor, W: torch.Tensor, tok: torch.Tensor, parent: torch.Tensor,
+                        lse: torch.Tensor, prob: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """n2.  prob [B,T] f32: softmax of the parent's early-exit logits at each node's token (root: 1)."""
+    lib = load_library()
+    code = _dtype_code(h)
+    dt = h.dtype
+    B, T, d = h.shape
+    V = W.shape[0]
+    if tuple(W.shape) != (V, d) or tuple(tok.shape) != (B, T) or tuple(parent.shape) != (B, T) or lse.numel() != B * T:
+        raise ValueError("W must be [V,d], tok/parent [B,T], lse [B*T]")
+    if prob is None:
+        prob = torch.empty(B, T, dtype=torch.float32, device=h.device)
+    i32 = torch.int32
+    _check(lib.ss_transition_probs(_dev(h, dt, "h"), _dev(W, dt, "W"), _dev(tok, i32, "tok"), _dev(parent, i32, "parent"),
+                                   _dev(lse, torch.float32, "lse"), B, T, d, V, code, _dev(prob, torch.float32, "prob"),
+                                   _stream()))
+    return prob
+
+
+def ss_tree_prune(tok: torch.Tensor, parent: torch.Tensor, prob: torch.Tensor, threshold: float) -> dict:
+    """n2.  Returns dict(keep, tok, parent, old_index [B,T] int32, n_nodes [B] int32) of the pruned, compacted and
+    padded trees."""
+    lib = load_library()
+    B, T = tok.shape
+    if tuple(parent.shape) != (B, T) or tuple(prob.shape) != (B, T):
+        raise ValueError("parent and prob must be [B,T]")
+    i32 = torch.int32
+    out = {k: torch.empty(B, T, dtype=i32, device=tok.device) for k in ("keep", "tok", "parent", "old_index")}
+    out["n_nodes"] = torch.empty(B, dtype=i32, device=tok.device)
+    _check(lib.ss_tree_prune(_dev(tok, i32, "tok"), _dev(parent, i32, "parent"), _dev(prob, torch.float32, "prob"),
+                             float(threshold), B, T, _dev(out["keep"], i32, "keep"), _dev(out["tok"], i32, "tok"),
+                             _dev(out["parent"], i32, "parent"), _dev(out["old_index"], i32, "old_index"),
+                             _dev(out["n_nodes"], i32, "n_nodes"), _stream()))
+    return out

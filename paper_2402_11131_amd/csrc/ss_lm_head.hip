@@ -22,10 +22,19 @@ struct LmArgs {
   int32_t* idx;        // [N,K]
   float* val;          // [N,K]
   void* y;             // [N,V], plain-projection flavour only (same type as the inputs)
+  float* lse;          // [N], log-sum-exp flavour only; its parts (max, sum) per (row, tile) use cand_key's memory
 };
 
 SS_DEV bool cand_better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
 SS_DEV bool cand_after(float v, int i, float pv, int pi) { return v < pv || (v == pv && i > pi); }
+
+// (max, sum of exp(x - max)) of two sets of logits -> of their union.  An empty set is (-inf, 0).
+SS_DEV float2 lse_merge(float2 p, float2 q) {
+  const float m = fmaxf(p.x, q.x);
+  const float sp = p.x == -INFINITY ? 0.f : p.y * __expf(p.x - m);
+  const float sq = q.x == -INFINITY ? 0.f : q.y * __expf(q.x - m);
+  return make_float2(m, sp + sq);
+}
 
 // A candidate as one 64-bit key whose unsigned order is the candidate order: the logit mapped to an
 // order-preserving unsigned pattern in the high word, the complement of the token id in the low word
@@ -48,8 +57,9 @@ SS_DEV int key_id(uint64_t k) { return k == 0 ? INT_MAX : (int)(0xffffffffu - (u
 // Workgroup tile 32 rows x 64 vocabulary columns, feature chunks of 32 through
 // LDS; thread (wave w, lane c) accumulates rows w, w+4, ... of column c.
 //
-// STORE = true is the plain projection: the tile is written to y instead of being searched.
-template <bool STORE>
+// MODE 0: top-K search.  MODE 1: the plain projection, the tile is written to y.  MODE 2: (max, sum of
+// exp) of the tile's logits per row, for the log-sum-exp over the vocabulary.
+template <int MODE>
 __global__ __launch_bounds__(256) void lm_head_f32_kernel(LmArgs a) {
   constexpr int BM = 32, BN = 64, BK = 32;
   __shared__ float As[BM][BK + 1];
@@ -80,7 +90,7 @@ __global__ __launch_bounds__(256) void lm_head_f32_kernel(LmArgs a) {
       for (int i = 0; i < BM / 4; ++i) acc[i] = fmaf(As[w + 4 * i][kk], wv, acc[i]);
     }
   }
-  if constexpr (STORE) {
+  if constexpr (MODE == 1) {
 #pragma unroll
     for (int i = 0; i < BM / 4; ++i) {
       const int row = r0 + w + 4 * i, col = v0 + lane;
@@ -91,6 +101,17 @@ __global__ __launch_bounds__(256) void lm_head_f32_kernel(LmArgs a) {
 #pragma unroll
   for (int i = 0; i < BM / 4; ++i) Z[w + 4 * i][lane] = acc[i];
   __syncthreads();
+  if constexpr (MODE == 2) {
+    for (int rr = w; rr < BM; rr += 4) {
+      const int row = r0 + rr;
+      if (row >= a.N) break;
+      float2 p = v0 + lane < a.V ? make_float2(Z[rr][lane], 1.f) : make_float2(-INFINITY, 0.f);
+      for (int off = 32; off > 0; off >>= 1)
+        p = lse_merge(p, make_float2(__shfl_xor(p.x, off, 64), __shfl_xor(p.y, off, 64)));
+      if (lane == 0) reinterpret_cast<float2*>(a.cand_key)[(size_t)row * a.n_tiles + blockIdx.x] = p;
+    }
+    return;
+  }
   // wave w selects for rows w, w+4, ...: K rounds of a wave-wide arg-max over the 64 columns
   for (int rr = w; rr < BM; rr += 4) {
     const int row = r0 + rr;
@@ -213,7 +234,33 @@ SS_DEV void lm_epilogue(const LmArgs& a, floatx16 (&acc)[NRT], unsigned char* hb
   constexpr int ROWS = 32 * NRT;
   constexpr int TI = 32 * NW;  // ids per tile
   const int lane = tid & 63, ln = lane & 31, lh = lane >> 5;
-  if constexpr (KT == 0) {
+  if constexpr (KT == -1) {
+    // Log-sum-exp: (max, sum of exp) of this lane's 16 logits of a row, of the row's two lanes, of the
+    // NW waves through LDS; one thread per row leaves the tile's pair.
+    float2* pairs = reinterpret_cast<float2*>(hbuf);  // [ROWS][NW]
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt) {
+      float m = -INFINITY;
+#pragma unroll
+      for (int e = 0; e < 16; ++e)
+        if (v0 + 8 * (e >> 2) + 4 * lh + (e & 3) < a.V) m = fmaxf(m, acc[rt][e]);
+      float sum = 0.f;
+#pragma unroll
+      for (int e = 0; e < 16; ++e)
+        if (v0 + 8 * (e >> 2) + 4 * lh + (e & 3) < a.V) sum += __expf(acc[rt][e] - m);
+      float2 p = make_float2(m, sum);
+      p = lse_merge(p, make_float2(__shfl_xor(p.x, 32, 64), __shfl_xor(p.y, 32, 64)));
+      if (lh == 0) pairs[(32 * rt + ln) * NW + w] = p;
+    }
+    __syncthreads();
+    for (int r = tid; r < ROWS; r += 64 * NW) {
+      float2 p = pairs[r * NW];
+#pragma unroll
+      for (int j = 1; j < NW; ++j) p = lse_merge(p, pairs[r * NW + j]);
+      if (row0 + r < a.N) reinterpret_cast<float2*>(a.cand_key)[(size_t)(row0 + r) * a.n_tiles + tile] = p;
+    }
+    return;
+  } else if constexpr (KT == 0) {
     // Plain projection: the tile is rounded to bf16 and turned round through LDS ([ROWS] rows of TI
     // outputs, padded by 16 bytes so that the 8-byte writes of 32 rows spread over the banks), then
     // leaves in 16-byte pieces, 2*TI contiguous bytes per row.
@@ -459,6 +506,17 @@ struct LmFlavour {
   int wide;  // 0: 4 waves, tile of 128 ids, nrt <= 6; 1: 8 waves, tile of 256 ids, nrt <= 5
 };
 
+// Log-sum-exp of a row from its tiles' (max, sum) pairs: one wavefront per row.
+__global__ __launch_bounds__(64) void lm_head_lse_reduce_kernel(LmArgs a) {
+  const int lane = threadIdx.x, row = blockIdx.x;
+  const float2* pairs = reinterpret_cast<const float2*>(a.cand_key) + (size_t)row * a.n_tiles;
+  float2 p = make_float2(-INFINITY, 0.f);
+  for (int t = lane; t < a.n_tiles; t += 64) p = lse_merge(p, pairs[t]);
+  for (int off = 32; off > 0; off >>= 1)
+    p = lse_merge(p, make_float2(__shfl_xor(p.x, off, 64), __shfl_xor(p.y, off, 64)));
+  if (lane == 0) a.lse[row] = p.x + logf(p.y);
+}
+
 template <int NRT, int KT, int WIDE>
 static int launch_lm_bf16_rk(hipStream_t st, const LmArgs& a) {
   void (*kern)(LmArgs);
@@ -486,6 +544,7 @@ static int launch_lm_bf16_rk(hipStream_t st, const LmArgs& a) {
 template <int NRT, int WIDE>
 static int launch_lm_bf16_r(int KT, hipStream_t st, const LmArgs& a) {
   switch (KT) {
+    case -1: return launch_lm_bf16_rk<NRT, -1, WIDE>(st, a);
     case 0: return launch_lm_bf16_rk<NRT, 0, WIDE>(st, a);
     case 1: return launch_lm_bf16_rk<NRT, 1, WIDE>(st, a);
     case 4: return launch_lm_bf16_rk<NRT, 4, WIDE>(st, a);
@@ -605,12 +664,12 @@ int ss_lm_head_argmax_topk(const void* hidden, const void* W, int N, int d, int 
   char* ws = (char*)(((uintptr_t)workspace + 255) & ~(uintptr_t)255);
   a.cand_key = (uint64_t*)ws;
   a.idx = idx; a.val = val;
-  a.y = nullptr;
+  a.y = nullptr; a.lse = nullptr;
   hipStream_t st = (hipStream_t)stream;
   if (dtype == SS_F32) {
     dim3 grid(a.n_tiles, ceil_div(N, 32));
     SS_REQUIRE(grid.y <= 65535, SS_ERR_UNSUPPORTED, "%s: N too large", fn);
-    hipLaunchKernelGGL(lm_head_f32_kernel<false>, grid, dim3(256), 0, st, a);
+    hipLaunchKernelGGL(lm_head_f32_kernel<0>, grid, dim3(256), 0, st, a);
   } else {
     LmFlavour f = lm_choose(N, V, &a);
     lm_flavour_override("SS_LM_FLAVOUR", N, V, &f, &a);
@@ -620,6 +679,39 @@ int ss_lm_head_argmax_topk(const void* hidden, const void* W, int N, int d, int 
   }
   if (int rc = check_launch(fn)) return rc;
   hipLaunchKernelGGL(lm_head_reduce_kernel, dim3(N), dim3(64), 0, st, a);
+  return check_launch(fn);
+}
+
+int ss_lm_head_logsumexp(const void* hidden, const void* W, int N, int d, int V, int dtype, float* lse,
+                         void* workspace, size_t workspace_bytes, void* stream) {
+  using namespace ss;
+  clear_error();
+  const char* fn = "ss_lm_head_logsumexp";
+  if (int rc = gemm_check(fn, N, d, V, dtype)) return rc;
+  SS_REQUIRE(N == 0 || (hidden && W && lse), SS_ERR_INVALID_ARG, "%s: NULL tensor argument", fn);
+  const size_t need = ss_lm_head_workspace_bytes(N, d, V, 1, dtype);
+  SS_REQUIRE(N == 0 || (workspace != nullptr && workspace_bytes >= need), SS_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given",
+             fn, need, workspace_bytes);
+  if (N == 0) return SS_OK;
+  LmArgs a;
+  a.hidden = hidden; a.W = W; a.N = N; a.d = d; a.V = V; a.K = 0;
+  a.n_tiles = lm_tiles(V, dtype);
+  a.n_chunks = 1;
+  a.cand_key = (uint64_t*)(((uintptr_t)workspace + 255) & ~(uintptr_t)255);
+  a.idx = nullptr; a.val = nullptr; a.y = nullptr;
+  a.lse = lse;
+  hipStream_t st = (hipStream_t)stream;
+  if (dtype == SS_F32) {
+    dim3 grid(a.n_tiles, ceil_div(N, 32));
+    SS_REQUIRE(grid.y <= 65535, SS_ERR_UNSUPPORTED, "%s: N too large", fn);
+    hipLaunchKernelGGL(lm_head_f32_kernel<2>, grid, dim3(256), 0, st, a);
+  } else {
+    LmFlavour f = lm_choose(N, V, &a);
+    SS_REQUIRE((long)a.n_chunks * (a.n_tiles + 7) < (1L << 27), SS_ERR_UNSUPPORTED, "%s: N x V too large", fn);
+    if (int rc = launch_lm_bf16(f, -1, st, a)) return rc;
+  }
+  if (int rc = check_launch(fn)) return rc;
+  hipLaunchKernelGGL(lm_head_lse_reduce_kernel, dim3(N), dim3(64), 0, st, a);
   return check_launch(fn);
 }
 
@@ -635,13 +727,13 @@ int ss_linear_rows(const void* x, const void* W, int N, int d, int V, int dtype,
   a.hidden = x; a.W = W; a.N = N; a.d = d; a.V = V; a.K = 0;
   a.n_tiles = lm_tiles(V, dtype);
   a.n_chunks = 1;
-  a.cand_key = nullptr; a.idx = nullptr; a.val = nullptr;
+  a.cand_key = nullptr; a.idx = nullptr; a.val = nullptr; a.lse = nullptr;
   a.y = y;
   hipStream_t st = (hipStream_t)stream;
   if (dtype == SS_F32) {
     dim3 grid(a.n_tiles, ceil_div(N, 32));
     SS_REQUIRE(grid.y <= 65535, SS_ERR_UNSUPPORTED, "%s: N too large", fn);
-    hipLaunchKernelGGL(lm_head_f32_kernel<true>, grid, dim3(256), 0, st, a);
+    hipLaunchKernelGGL(lm_head_f32_kernel<1>, grid, dim3(256), 0, st, a);
   } else {
     LmFlavour f = lm_choose(N, V, &a);
     lm_flavour_override("SS_LINEAR_FLAVOUR", N, V, &f, &a);
