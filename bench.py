@@ -303,6 +303,24 @@ def main():
                 del xs, y
             dense["layer_total_us"] = round(total, 2)
             extra["linear_rows"] = dense
+            # The pruning layer (also after the hot path): log-sum-exp of the early-exit logits of the B*T main
+            # rows over the whole vocabulary, transition probabilities, pruning decision and compaction.
+            hm = synth.make_lm_head_inputs(cfg, 60, device=dev, N=cfg.B * cfg.T)["hidden"].view(cfg.B, cfg.T, dm)
+            w_copies = [lm["W"], lm["W"].clone()]
+            lse = torch.empty(cfg.B * cfg.T, dtype=torch.float32, device=dev)
+            prob = torch.empty(cfg.B, cfg.T, dtype=torch.float32, device=dev)
+
+            def prune_layer(i):
+                api.ss_lm_head_logsumexp(hm.view(cfg.B * cfg.T, dm), w_copies[i & 1], lse=lse, workspace=lm_ws)
+                api.ss_transition_probs(hm, w_copies[i & 1], tok, parent, lse, prob=prob)
+                return api.ss_tree_prune(tok, parent, prob, 0.01)
+            prune_layer(0)
+            us_prune = timed(prune_layer, it, torch)
+            us_lse = timed(lambda i: api.ss_lm_head_logsumexp(hm.view(cfg.B * cfg.T, dm), w_copies[i & 1], lse=lse,
+                                                              workspace=lm_ws), it, torch)
+            extra["prune_layer"] = {"us": round(us_prune, 2), "logsumexp_us": round(us_lse, 2),
+                                    "logsumexp_hbm_gbps": round(cfg.vocab * dm * 2 / (us_lse * 1e-6) / 1e9, 1)}
+            del w_copies
 
     result = {
         "metric": "verify+speculate step time (MSA layers + LM-head argmax/top-k + verify + draft)",
