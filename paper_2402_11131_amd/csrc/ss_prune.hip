@@ -35,6 +35,24 @@ __global__ __launch_bounds__(64) void transition_prob_kernel(ProbArgs a) {
   }
   const size_t hr = ((size_t)b * a.T + p) * a.d, wr = (size_t)c * a.d;
   float acc = 0.f;
+  constexpr int PER = BF16 ? 8 : 4;  // elements per 16-byte piece
+  const bool vec = a.d % PER == 0 && (((uintptr_t)a.h | (uintptr_t)a.W) & 15) == 0;
+  if (vec) {
+    const uintx4* hv = reinterpret_cast<const uintx4*>((const unsigned char*)a.h + hr * (BF16 ? 2 : 4));
+    const uintx4* wv = reinterpret_cast<const uintx4*>((const unsigned char*)a.W + wr * (BF16 ? 2 : 4));
+    for (int c0 = lane; c0 < a.d / PER; c0 += 64) {
+      const uintx4 x = hv[c0], y = wv[c0];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        if constexpr (BF16) {
+          acc = fmaf(bf16_bits_to_f32(x[q] & 0xffffu), bf16_bits_to_f32(y[q] & 0xffffu), acc);
+          acc = fmaf(bf16_bits_to_f32(x[q] >> 16), bf16_bits_to_f32(y[q] >> 16), acc);
+        } else {
+          acc = fmaf(__uint_as_float(x[q]), __uint_as_float(y[q]), acc);
+        }
+      }
+    }
+  } else
   for (int e = lane; e < a.d; e += 64) {
     float x, y;
     if constexpr (BF16) {
