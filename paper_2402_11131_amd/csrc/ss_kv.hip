@@ -1,6 +1,6 @@
 // n3: KV-cache commit after verification (Sec. 3.2.1, Appendix A.1).  Of the step's own rows only the
 // main rows of the accepted path are appended to the paged cache; stream rows and rejected nodes are
-// dropped.  A few KB per sequence: one workgroup per (sequence, path position), pure copies.
+// dropped.  A few KB per sequence: one workgroup per (sequence, path position, KV head), pure copies.
 #include "ss_common.h"
 
 namespace ss {
@@ -20,12 +20,12 @@ struct KvArgs {
 
 // E = element type of the tensors as an unsigned integer of the same size (the copy is bit-exact).
 template <typename E>
-__global__ __launch_bounds__(256) void kv_commit_kernel(KvArgs a) {
+__global__ __launch_bounds__(128) void kv_commit_kernel(KvArgs a) {
   const int b = blockIdx.x / (a.max_depth + 1), j = blockIdx.x % (a.max_depth + 1);
   const int cap = a.max_pages * a.page;
   const int L = min(max(a.seq_lens[b], 0), cap);
   const int n_acc = min(max(a.n_accept[b], 0), a.max_depth);
-  if (j == 0 && threadIdx.x == 0 && a.new_seq_lens) a.new_seq_lens[b] = min(L + n_acc + 1, cap);
+  if (j == 0 && blockIdx.y == 0 && threadIdx.x == 0 && a.new_seq_lens) a.new_seq_lens[b] = min(L + n_acc + 1, cap);
   const int pos = L + j;
   if (j > n_acc || pos >= cap) return;
   const int node = min(max(a.path[(size_t)b * (a.max_depth + 1) + j], 0), a.T - 1);
@@ -35,8 +35,9 @@ __global__ __launch_bounds__(256) void kv_commit_kernel(KvArgs a) {
   const E* vs = (const E*)a.v_new + ((size_t)b * a.R + node) * a.Hkv * a.D;
   E* kd = (E*)a.k_cache + (size_t)pg * a.Hkv * a.page * a.D + (size_t)slot * a.D;  // + h*page*D + d
   E* vd = (E*)a.v_cache + (size_t)pg * a.Hkv * a.D * a.page + slot;                // + (h*D + d)*page
-  for (int e = threadIdx.x; e < a.Hkv * a.D; e += 256) {
-    const int h = e / a.D, d = e % a.D;
+  const int h = blockIdx.y;  // one workgroup per (sequence, path position, KV head)
+  for (int d = threadIdx.x; d < a.D; d += 128) {
+    const int e = h * a.D + d;
     kd[(size_t)h * a.page * a.D + d] = ks[e];
     vd[(size_t)e * a.page] = vs[e];
   }
@@ -78,8 +79,9 @@ extern "C" int ss_kv_commit(const void* k_new, const void* v_new, void* k_cache,
   a.B = B; a.T = T; a.R = T * (1 + gamma); a.Hkv = Hkv; a.D = D; a.page = page_size;
   a.page_shift = page_size == 16 ? 4 : (page_size == 32 ? 5 : 6);
   a.max_pages = max_pages_per_seq; a.num_pages = num_pages; a.max_depth = max_depth;
-  const dim3 grid((unsigned)(B * (max_depth + 1)));
-  if (dtype == SS_F32) hipLaunchKernelGGL(kv_commit_kernel<uint32_t>, grid, dim3(256), 0, (hipStream_t)stream, a);
-  else hipLaunchKernelGGL(kv_commit_kernel<uint16_t>, grid, dim3(256), 0, (hipStream_t)stream, a);
+  SS_REQUIRE(Hkv <= 65535, SS_ERR_UNSUPPORTED, "%s: Hkv=%d", fn, Hkv);
+  const dim3 grid((unsigned)(B * (max_depth + 1)), (unsigned)Hkv);
+  if (dtype == SS_F32) hipLaunchKernelGGL(kv_commit_kernel<uint32_t>, grid, dim3(128), 0, (hipStream_t)stream, a);
+  else hipLaunchKernelGGL(kv_commit_kernel<uint16_t>, grid, dim3(128), 0, (hipStream_t)stream, a);
   return check_launch(fn);
 }
