@@ -707,6 +707,7 @@ int ss_lm_head_logsumexp(const void* hidden, const void* W, int N, int d, int V,
     hipLaunchKernelGGL(lm_head_f32_kernel<2>, grid, dim3(256), 0, st, a);
   } else {
     LmFlavour f = lm_choose(N, V, &a);
+    lm_flavour_override("SS_LM_FLAVOUR", N, V, &f, &a);
     SS_REQUIRE((long)a.n_chunks * (a.n_tiles + 7) < (1L << 27), SS_ERR_UNSUPPORTED, "%s: N x V too large", fn);
     if (int rc = launch_lm_bf16(f, -1, st, a)) return rc;
   }
