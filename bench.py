@@ -127,7 +127,8 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus %d is not supported (the path uses no collectives; "
-              "see DESIGN.md for how it would shard)" % args.gpus, file=sys.stderr)
+              "sequences, heads or vocabulary slices would be sharded, one small exchange per step)" % args.gpus,
+              file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
