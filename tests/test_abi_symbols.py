@@ -79,6 +79,29 @@ def test_argument_validation_needs_no_device():
     assert b"page_size" in lib.ss_last_error()
 
 
+def test_argument_validation_of_the_rows_around_the_hot_path():
+    lib = api.load_library()
+    one = ctypes.c_void_p(8)  # never dereferenced: validation fails first
+    f = ctypes.c_float
+    assert lib.ss_linear_rows(one, one, 4, 100, 50, 1, one, None) == 2            # bf16 needs d % 64 == 0
+    assert lib.ss_linear_rows(one, one, 4, 128, 50, 7, one, None) == 2            # dtype
+    assert lib.ss_linear_rows(None, one, 4, 128, 50, 1, one, None) == 1           # NULL tensor
+    assert lib.ss_linear_rows(None, None, 0, 128, 50, 1, None, None) == 0         # N == 0: no-op
+    assert lib.ss_stream_insert(one, None, one, 1, 65, 2, 64, 1, one, None) == 2  # T above the limit
+    assert lib.ss_stream_insert(one, None, one, 1, 4, 9, 64, 1, one, None) == 2   # gamma above the limit
+    assert lib.ss_stream_insert(one, None, None, 1, 4, 2, 64, 1, one, None) == 1  # P missing with gamma > 0
+    assert lib.ss_stream_insert(None, None, None, 0, 4, 2, 64, 1, None, None) == 0
+    assert lib.ss_lm_head_logsumexp(one, one, 4, 100, 50, 1, one, one, 1 << 20, None) == 2
+    assert lib.ss_lm_head_logsumexp(one, one, 4, 128, 50, 1, one, one, 8, None) == 4  # workspace too small
+    assert b"workspace" in lib.ss_last_error()
+    assert lib.ss_transition_probs(one, one, one, one, one, 1, 65, 64, 50, 1, one, None) == 2
+    assert lib.ss_transition_probs(one, one, one, one, None, 1, 4, 64, 50, 1, one, None) == 1
+    assert lib.ss_tree_prune(one, one, one, f(0.5), 1, 0, one, one, one, one, one, None) == 2
+    assert lib.ss_tree_prune(one, one, one, f(0.5), 1, 4, one, one, one, one, one, None) == 1  # outputs alias inputs
+    assert lib.ss_kv_commit(one, one, one, one, one, 8, 16, one, one, one, 1, 8, 3, 4, 64, 24, 3, 1, one, None) == 2
+    assert b"page_size" in lib.ss_last_error()
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(api, "_lib", None)
     monkeypatch.setattr(api, "LIB_PATH", "/nonexistent/libss.so")
