@@ -319,6 +319,12 @@ def main():
             us_prune = timed(prune_layer, it, torch)
             us_lse = timed(lambda i: api.ss_lm_head_logsumexp(hm.view(cfg.B * cfg.T, dm), w_copies[i & 1], lse=lse,
                                                               workspace=lm_ws), it, torch)
+            # Stream insertion (Eq. 3) for the same batch: elementwise, B*R*d elements
+            P_emb = synth.make_lm_head_inputs(synth.scaled(cfg, vocab=64, d_model=dm), 61, device=dev, N=cfg.gamma)["hidden"]
+            X_rows = torch.empty(cfg.B, cfg.R, dm, dtype=hm.dtype, device=dev)
+            api.ss_stream_insert(hm, P_emb, X=X_rows)
+            us_ins = timed(lambda i: api.ss_stream_insert(hm, P_emb, X=X_rows), it, torch)
+            extra["stream_insert_us"] = round(us_ins, 2)
             extra["prune_layer"] = {"us": round(us_prune, 2), "logsumexp_us": round(us_lse, 2),
                                     "logsumexp_hbm_gbps": round(cfg.vocab * dm * 2 / (us_lse * 1e-6) / 1e9, 1)}
             del w_copies
