@@ -65,3 +65,22 @@ def test_log_sum_exp(problem, flavour):
     os.environ["SS_LM_FLAVOUR"] = flavour
     lse = api.ss_lm_head_logsumexp(x, W).cpu().numpy()
     assert (np.abs(lse - ref["lse"]) <= 2e-3 * np.maximum(1.0, np.abs(ref["lse"]))).all()
+
+
+@pytest.mark.parametrize("K", [1, 8])
+@pytest.mark.parametrize("flavour", ["2", "6", "1w", "3w", "5w"])
+def test_top_1_and_top_8(problem, flavour, K):
+    # the other two widths of the candidate lists (K = 1 and K = 5..8) in both shapes
+    x, W, ref = problem
+    os.environ["SS_LM_FLAVOUR"] = flavour
+    idx, val = api.ss_lm_head_argmax_topk(x, W, K)
+    torch.cuda.synchronize()
+    idx, val = idx.cpu().numpy(), val.cpu().numpy()
+    o_idx, o_val = oracle.lm_head_topk(to_np_f32(x.cpu()), to_np_f32(W.cpu()), K)[:2]
+    tau = 1e-4 * np.abs(ref["z"]).max()
+    z_at = np.take_along_axis(ref["z"], idx.astype(np.int64), axis=1)
+    assert (np.abs(val - z_at) <= tau).all()
+    differs = idx != o_idx
+    assert (np.abs(z_at - o_val)[differs] <= tau).all() and differs.sum() <= 2
+    for n in range(idx.shape[0]):
+        assert len(set(idx[n].tolist())) == K
