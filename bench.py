@@ -111,6 +111,54 @@ def calibrate_copy(torch, dev):
     torch.cuda.synchronize()
 
 
+def time_rows_after_hot_path(api, synth, torch, cfg, dev, N, it, lm, lm_ws, tok, parent, extra):
+    """Rows after the hot path (not part of `value`), each in a loop of its own; fills `extra`."""
+    # Dense projections of one MSA layer on the step's N rows (the row after the hot path: not part of
+    # `value`): fused QKV, attention output, fused gate+up and down of a 4096/11008 feed-forward block.
+    dm, dff = cfg.d_model, 11008
+    dense = {}
+    total = 0.0
+    for name, (din, dout) in (("qkv", (dm, 3 * cfg.H * cfg.D)), ("attn_out", (cfg.H * cfg.D, dm)),
+                              ("gate_up", (dm, 2 * dff)), ("down", (dff, dm))):
+        xs = [synth.make_lm_head_inputs(synth.scaled(cfg, vocab=dout, d_model=din), 50 + j, device=dev, N=N)
+              for j in range(2)]
+        y = torch.empty(N, dout, dtype=xs[0]["hidden"].dtype, device=dev)
+        for j in range(2):
+            api.ss_linear_rows(xs[j]["hidden"], xs[j]["W"], y)
+        us = timed(lambda i: api.ss_linear_rows(xs[i % 2]["hidden"], xs[i % 2]["W"], y), it, torch)
+        total += us
+        dense[name] = {"d_in": din, "d_out": dout, "us": round(us, 2),
+                       "tflops": round(2.0 * N * din * dout / (us * 1e-6) / 1e12, 1),
+                       "hbm_gbps": round((din * dout + N * din + N * dout) * 2 / (us * 1e-6) / 1e9, 1)}
+        del xs, y
+    dense["layer_total_us"] = round(total, 2)
+    extra["linear_rows"] = dense
+    # The pruning layer (also after the hot path): log-sum-exp of the early-exit logits of the B*T main
+    # rows over the whole vocabulary, transition probabilities, pruning decision and compaction.
+    hm = synth.make_lm_head_inputs(cfg, 60, device=dev, N=cfg.B * cfg.T)["hidden"].view(cfg.B, cfg.T, dm)
+    w_copies = [lm["W"], lm["W"].clone()]
+    lse = torch.empty(cfg.B * cfg.T, dtype=torch.float32, device=dev)
+    prob = torch.empty(cfg.B, cfg.T, dtype=torch.float32, device=dev)
+
+    def prune_layer(i):
+        api.ss_lm_head_logsumexp(hm.view(cfg.B * cfg.T, dm), w_copies[i & 1], lse=lse, workspace=lm_ws)
+        api.ss_transition_probs(hm, w_copies[i & 1], tok, parent, lse, prob=prob)
+        return api.ss_tree_prune(tok, parent, prob, 0.01)
+    prune_layer(0)
+    us_prune = timed(prune_layer, it, torch)
+    us_lse = timed(lambda i: api.ss_lm_head_logsumexp(hm.view(cfg.B * cfg.T, dm), w_copies[i & 1], lse=lse,
+                                                      workspace=lm_ws), it, torch)
+    # Stream insertion (Eq. 3) for the same batch: elementwise, B*R*d elements
+    P_emb = synth.make_lm_head_inputs(synth.scaled(cfg, vocab=64, d_model=dm), 61, device=dev, N=cfg.gamma)["hidden"]
+    X_rows = torch.empty(cfg.B, cfg.R, dm, dtype=hm.dtype, device=dev)
+    api.ss_stream_insert(hm, P_emb, X=X_rows)
+    us_ins = timed(lambda i: api.ss_stream_insert(hm, P_emb, X=X_rows), it, torch)
+    extra["stream_insert_us"] = round(us_ins, 2)
+    extra["prune_layer"] = {"us": round(us_prune, 2), "logsumexp_us": round(us_lse, 2),
+                            "logsumexp_hbm_gbps": round(cfg.vocab * dm * 2 / (us_lse * 1e-6) / 1e9, 1)}
+    del w_copies
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -284,50 +332,10 @@ def main():
                                                        (us_lm * 1e-6) / 1e9, 1)}
         extra["accepted_per_sequence"] = state["ver"]["n_accept"].tolist()
         if args.workload == "c4":
-            # Dense projections of one MSA layer on the step's N rows (the row after the hot path: not part of
-            # `value`): fused QKV, attention output, fused gate+up and down of a 4096/11008 feed-forward block.
-            dm, dff = cfg.d_model, 11008
-            dense = {}
-            total = 0.0
-            for name, (din, dout) in (("qkv", (dm, 3 * cfg.H * cfg.D)), ("attn_out", (cfg.H * cfg.D, dm)),
-                                      ("gate_up", (dm, 2 * dff)), ("down", (dff, dm))):
-                xs = [synth.make_lm_head_inputs(synth.scaled(cfg, vocab=dout, d_model=din), 50 + j, device=dev, N=N)
-                      for j in range(2)]
-                y = torch.empty(N, dout, dtype=xs[0]["hidden"].dtype, device=dev)
-                for j in range(2):
-                    api.ss_linear_rows(xs[j]["hidden"], xs[j]["W"], y)
-                us = timed(lambda i: api.ss_linear_rows(xs[i % 2]["hidden"], xs[i % 2]["W"], y), it, torch)
-                total += us
-                dense[name] = {"d_in": din, "d_out": dout, "us": round(us, 2),
-                               "tflops": round(2.0 * N * din * dout / (us * 1e-6) / 1e12, 1),
-                               "hbm_gbps": round((din * dout + N * din + N * dout) * 2 / (us * 1e-6) / 1e9, 1)}
-                del xs, y
-            dense["layer_total_us"] = round(total, 2)
-            extra["linear_rows"] = dense
-            # The pruning layer (also after the hot path): log-sum-exp of the early-exit logits of the B*T main
-            # rows over the whole vocabulary, transition probabilities, pruning decision and compaction.
-            hm = synth.make_lm_head_inputs(cfg, 60, device=dev, N=cfg.B * cfg.T)["hidden"].view(cfg.B, cfg.T, dm)
-            w_copies = [lm["W"], lm["W"].clone()]
-            lse = torch.empty(cfg.B * cfg.T, dtype=torch.float32, device=dev)
-            prob = torch.empty(cfg.B, cfg.T, dtype=torch.float32, device=dev)
-
-            def prune_layer(i):
-                api.ss_lm_head_logsumexp(hm.view(cfg.B * cfg.T, dm), w_copies[i & 1], lse=lse, workspace=lm_ws)
-                api.ss_transition_probs(hm, w_copies[i & 1], tok, parent, lse, prob=prob)
-                return api.ss_tree_prune(tok, parent, prob, 0.01)
-            prune_layer(0)
-            us_prune = timed(prune_layer, it, torch)
-            us_lse = timed(lambda i: api.ss_lm_head_logsumexp(hm.view(cfg.B * cfg.T, dm), w_copies[i & 1], lse=lse,
-                                                              workspace=lm_ws), it, torch)
-            # Stream insertion (Eq. 3) for the same batch: elementwise, B*R*d elements
-            P_emb = synth.make_lm_head_inputs(synth.scaled(cfg, vocab=64, d_model=dm), 61, device=dev, N=cfg.gamma)["hidden"]
-            X_rows = torch.empty(cfg.B, cfg.R, dm, dtype=hm.dtype, device=dev)
-            api.ss_stream_insert(hm, P_emb, X=X_rows)
-            us_ins = timed(lambda i: api.ss_stream_insert(hm, P_emb, X=X_rows), it, torch)
-            extra["stream_insert_us"] = round(us_ins, 2)
-            extra["prune_layer"] = {"us": round(us_prune, 2), "logsumexp_us": round(us_lse, 2),
-                                    "logsumexp_hbm_gbps": round(cfg.vocab * dm * 2 / (us_lse * 1e-6) / 1e9, 1)}
-            del w_copies
+            try:
+                time_rows_after_hot_path(api, synth, torch, cfg, dev, N, it, lm, lm_ws, tok, parent, extra)
+            except Exception as e:  # the headline measurement must survive a failure here
+                extra["rows_after_hot_path_error"] = "%s: %s" % (type(e).__name__, e)
 
     result = {
         "metric": "verify+speculate step time (MSA layers + LM-head argmax/top-k + verify + draft)",
