@@ -9,7 +9,10 @@
  * of Eq. 4 / the attention-mask figure of the appendix), the LM head turns the
  * last hidden states into logits, the longest draft path the main stream agrees
  * with is accepted, and the streams of the last accepted node give the next
- * tree draft.  The five calls below are those pieces.
+ * tree draft.  The calls a1..a5 below are those pieces; n1..n4 are the rows
+ * around them: the dense projections of a layer, the parallel tree-pruning layer
+ * (Sec. 3.2.3), the commit of the accepted path to the KV cache (Appendix A.1)
+ * and the insertion of the stream rows (Eq. 3).
  *
  * Conventions (all calls)
  *  - extern "C", plain pointers and sizes.  Unless a parameter says "host",
