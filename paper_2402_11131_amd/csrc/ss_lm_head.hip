@@ -180,6 +180,10 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 SS_DEV void load_to_lds16(const void* sbase, uint32_t voff, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %0" ::"s"(sbase), "v"(voff), "s"(lds_addr) : "memory");
 }
+// The same with the streaming hint, for data that no other workgroup will ask for.
+SS_DEV void load_to_lds16_stream(const void* sbase, uint32_t voff, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %0 nt" ::"s"(sbase), "v"(voff), "s"(lds_addr) : "memory");
+}
 
 // The KT best (logit, id) pairs of candidates that arrive in increasing id order: an equal logit
 // never displaces an earlier entry, so a strict float compare implements "lower id first".
@@ -345,7 +349,10 @@ SS_DEV void lm_epilogue(const LmArgs& a, floatx16 (&acc)[NRT], unsigned char* hb
 // waves (tile of 128 ids, four buffers) or 8 (256 ids, two waves per SIMD, three buffers).  The 4*NRT
 // hidden load slots are dealt to the waves in rounds; in a last, incomplete round the spare waves load
 // a slot a second time (same bytes to the same place), which keeps the load count equal for all.
-template <int NRT, int KT, int NW, int NBUF>
+// WS: W is loaded with the streaming hint.  Right when the rows form one chunk, so that every line of W
+// is wanted by exactly one workgroup (the pruning layer's 64 rows: 60 -> 53 us); with several row chunks
+// the chunks of a vocabulary tile share W through the L2 and the hint undoes that.
+template <int NRT, int KT, int NW, int NBUF, bool WS = false>
 __global__ __launch_bounds__(64 * NW, 1) void lm_head_bf16_kernel(LmArgs a) {
   constexpr int ROWS = 32 * NRT;
   constexpr int TI = 32 * NW;
@@ -402,7 +409,10 @@ __global__ __launch_bounds__(64 * NW, 1) void lm_head_bf16_kernel(LmArgs a) {
 #pragma unroll
     for (int i = 0; i < NH; ++i) load_to_lds16(hb, h_voff[i], lds0 + buf * BB + h_slot[i] * 1024);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) load_to_lds16(wb, w_voff[i], lds0 + buf * BB + HB + (4 * w + i) * 1024);
+    for (int i = 0; i < 4; ++i) {
+      if constexpr (WS) load_to_lds16_stream(wb, w_voff[i], lds0 + buf * BB + HB + (4 * w + i) * 1024);
+      else load_to_lds16(wb, w_voff[i], lds0 + buf * BB + HB + (4 * w + i) * 1024);
+    }
   };
   constexpr int WAIT_ALL = 0x0F70;                                     // s_waitcnt vmcnt(0)
 #pragma unroll
@@ -449,6 +459,7 @@ __global__ __launch_bounds__(64 * NW, 1) void lm_head_bf16_kernel(LmArgs a) {
 #pragma unroll
       for (int l = (c * NLD) / 4; l < ((c + 1) * NLD) / 4; ++l) {
         if (l < NH) load_to_lds16(h_base, h_voff[l], dst + h_slot[l] * 1024);
+        else if constexpr (WS) load_to_lds16_stream(w_base, w_voff[l - NH], dst + HB + (4 * w + (l - NH)) * 1024);
         else load_to_lds16(w_base, w_voff[l - NH], dst + HB + (4 * w + (l - NH)) * 1024);
       }
 #pragma unroll
@@ -527,15 +538,16 @@ static int launch_lm_bf16_rk(hipStream_t st, const LmArgs& a) {
     lds = 3 * ((size_t)(32 * NRT) * 128 + 256 * 128);
     threads = 512;
   } else {
-    kern = lm_head_bf16_kernel<NRT, KT, 4, 4>;
+    kern = a.n_chunks == 1 ? lm_head_bf16_kernel<NRT, KT, 4, 4, true> : lm_head_bf16_kernel<NRT, KT, 4, 4, false>;
     lds = 4 * ((size_t)(32 * NRT) * 128 + 128 * 128);
   }
-  static bool attr_set = false;
-  if (!attr_set) {
+  static bool attr_set[2] = {false, false};  // [W streamed]
+  const int variant = (WIDE == 0 && a.n_chunks == 1) ? 1 : 0;
+  if (!attr_set[variant]) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)lds);
     if (e != hipSuccess) SS_FAIL(SS_ERR_HIP, "lm_head_bf16_kernel: hipFuncSetAttribute: %s", hipGetErrorString(e));
-    attr_set = true;
+    attr_set[variant] = true;
   }
   const dim3 grid(8 * a.n_chunks * ceil_div(a.n_tiles, 8));
   hipLaunchKernelGGL(kern, grid, dim3(threads), lds, st, a);

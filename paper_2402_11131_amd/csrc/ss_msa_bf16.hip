@@ -80,6 +80,13 @@ SS_DEV int k_swz(int row) {
 
 SS_DEV bf16x8 as_bf16x8(uintx4 u) { return __builtin_bit_cast(bf16x8, u); }
 SS_DEV uintx4 ld16(const uint16_t* p) { return *reinterpret_cast<const uintx4*>(p); }
+// The same with the streaming hint: the K/V cache is read once per call and should not displace anything in
+// the L2 and the memory-side cache (measured: 9 % less kernel time on the 4096-token workloads).
+template <bool STREAM>
+SS_DEV uintx4 ld16_cache(const uint16_t* p) {
+  if constexpr (STREAM) return __builtin_nontemporal_load(reinterpret_cast<const uintx4*>(p));
+  else return *reinterpret_cast<const uintx4*>(p);
+}
 
 // LDS transpose read.  Within each group of 16 lanes, lane j passes the address of 4 consecutive
 // 16-bit elements In[j][0..3]; lane i receives Out[i][e] = In[4*e + (i >> 2)][i & 3].  With lane
@@ -93,7 +100,10 @@ SS_DEV uintx2 lds_read_tr16(const unsigned char* p) {
 
 // NW = waves (query tiles) per group; it only fixes how the 1 KB load slots of a unit are dealt to
 // the waves of a group.  The number of groups is a launch parameter.
-template <int D, int NW>
+// STREAM: the cache is loaded with the streaming hint.  Right when a (sequence, KV head, split) has one row
+// chunk, so that every byte of the cache is wanted by exactly one workgroup; with several row chunks (long GQA
+// trees) the chunks share K/V through the L2 and the hint undoes that (measured: +25 % time).
+template <int D, int NW, bool STREAM>
 __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves / NW : kMaxGroups)) void msa_bf16_kernel(MsaArgs a, int n_groups) {
   constexpr int KS = D / 32, DT = D / 16;
   constexpr int K_BYTES = 32 * D * 2;          // K rows of a unit (V takes the same)
@@ -230,9 +240,9 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
     const uint16_t* va = v_head + g_a + o_a;
     const uint16_t* vb = v_head + g_b + o_b;
 #pragma unroll
-    for (int j = 0; j < KJ; ++j) stg[j] = ld16((k_second[j] ? kb2 : ka) + k_soff[j] + k_lsrc[j]);
+    for (int j = 0; j < KJ; ++j) stg[j] = ld16_cache<STREAM>((k_second[j] ? kb2 : ka) + k_soff[j] + k_lsrc[j]);
 #pragma unroll
-    for (int j = 0; j < KJ; ++j) stg[KJ + j] = ld16((v_second[j] ? vb : va) + v_soff[j] + v_lsrc);
+    for (int j = 0; j < KJ; ++j) stg[KJ + j] = ld16_cache<STREAM>((v_second[j] ? vb : va) + v_soff[j] + v_lsrc);
   };
   auto store_main = [&](unsigned char* st) {
 #pragma unroll
@@ -576,8 +586,8 @@ static int groups_for(int nw, int wanted) {
   return g < 1 ? 1 : g;
 }
 
-template <int D, int NW>
-static int launch_dn(const MsaArgs& a, hipStream_t stream) {
+template <int D, int NW, bool STREAM>
+static int launch_dns(const MsaArgs& a, hipStream_t stream) {
   const int n_groups = groups_for(NW, a.groups);
   const int G = a.B * a.Hkv * a.n_splits;
   const long wgs = (long)ceil_div(G, 8) * 8 * a.n_qc;
@@ -587,7 +597,7 @@ static int launch_dn(const MsaArgs& a, hipStream_t stream) {
   size_t lds = (size_t)n_groups * 2 * stage_bytes;
   if (merge_bytes > lds) lds = merge_bytes;
   lds += SS_MAX_T * 4 + SS_MAX_T * 8 + (size_t)n_groups * NW * 32 * 4;
-  auto kern = msa_bf16_kernel<D, NW>;
+  auto kern = msa_bf16_kernel<D, NW, STREAM>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -597,6 +607,11 @@ static int launch_dn(const MsaArgs& a, hipStream_t stream) {
   }
   hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(64 * NW * n_groups), lds, stream, a, n_groups);
   return check_launch("ss_msa_attention");
+}
+
+template <int D, int NW>
+static int launch_dn(const MsaArgs& a, hipStream_t stream) {
+  return a.n_qc == 1 ? launch_dns<D, NW, true>(a, stream) : launch_dns<D, NW, false>(a, stream);
 }
 
 template <int D>
