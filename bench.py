@@ -15,8 +15,10 @@ layer(s) of the other configurations (no LM head in those).
 Prints ONE JSON line.  `value` is microseconds per step.  `roofline` describes the
 dominant kernel (the bf16 MSA kernel): algorithmic bytes per launch divided by the
 kernel's own average duration, measured here with events on the launch stream
-with the split-merge kernel switched off.  `cpu_baseline` times the CPU oracle on
-a bounded sample of the same workload and scales it to a full step.
+around a loop of launches with the split-merge kernel switched off (rotating
+input sets).  `kernels.msa_kernel_in_step_with_events_us` is the same kernel
+bracketed by events launch by launch inside the steps.  `cpu_baseline` times the
+CPU oracle on whole steps of the same workload.
 """
 import argparse
 import json
@@ -225,10 +227,19 @@ def main():
 
     state = {}
 
-    def step(i):
+    def step(i, kernel_events=None):
         base = (i * cfg.n_layers) % n_sets
         for j in range(cfg.n_layers):
-            msa_call(layers[base + j], outs[j])
+            if kernel_events is None:
+                msa_call(layers[base + j], outs[j])
+            else:
+                # the same two kernels as two calls, with a pair of events around the attention kernel alone
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                msa_call(layers[base + j], outs[j], api.SS_MSA_PARTIALS_ONLY)
+                e1.record()
+                msa_call(layers[base + j], outs[j], api.SS_MSA_MERGE_ONLY)
+                kernel_events.append((e0, e1))
         if has_lm:
             hidden = outs[-1].view(N, cfg.d_model)
             api.ss_lm_head_argmax_topk(hidden, lm["W"], cfg.K, idx=idx, val=val, workspace=lm_ws)
@@ -283,7 +294,17 @@ def main():
     it = max(20, args.steps)
     us_msa_call = timed(lambda i: msa_call(layers[i % n_sets], outs[0]), it, torch)
     us_msa_kernel = timed(lambda i: msa_call(layers[i % n_sets], outs[0], api.SS_MSA_PARTIALS_ONLY), it, torch)
-    kern = {"msa_call_us": round(us_msa_call, 2), "msa_kernel_us": round(us_msa_kernel, 2)}
+    # The same kernel inside the step, for comparison with a kernel trace: the timed steps again, every
+    # attention call made in its two halves (kernel, then split merge: the same kernels in the same order) with
+    # a pair of events around the first.  This figure includes what the two events cost themselves.
+    evs = []
+    for i in range(args.steps):
+        step(i, evs)
+    torch.cuda.synchronize()
+    us_msa_in_step = sum(a_.elapsed_time(b_) for a_, b_ in evs) * 1000.0 / len(evs)
+    del evs
+    kern = {"msa_call_us": round(us_msa_call, 2), "msa_kernel_us": round(us_msa_kernel, 2),
+            "msa_kernel_in_step_with_events_us": round(us_msa_in_step, 2)}
     b_msa = msa_bytes(cfg, seq_lens)
     f_msa = msa_flops(cfg, seq_lens)
     gbps = b_msa / (us_msa_kernel * 1e-6) / 1e9

@@ -73,6 +73,12 @@ extern "C" {
  * kernel that merges the KV splits; `out` is then left unwritten whenever the
  * problem is split (the per-split partial results stay in the workspace). */
 #define SS_MSA_PARTIALS_ONLY 2u
+/* ... and its counterpart: run only the kernel that merges the KV splits, on the
+ * partial results a call with SS_MSA_PARTIALS_ONLY left in the same workspace
+ * (same arguments).  A no-op when the problem is not split.  The two flags
+ * together make one full call in two steps, so that a profiler or a pair of
+ * events can bracket the attention kernel alone inside a real step. */
+#define SS_MSA_MERGE_ONLY 4u
 
 /* Library version (major*100 + minor). */
 int ss_version(void);

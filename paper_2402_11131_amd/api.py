@@ -22,6 +22,7 @@ SS_OK = 0
 SS_F32, SS_BF16 = 0, 1
 SS_STREAM_EXCLUDE_SELF = 1
 SS_MSA_PARTIALS_ONLY = 2
+SS_MSA_MERGE_ONLY = 4
 SS_MAX_T, SS_MAX_GAMMA, SS_MAX_K = 64, 8, 8
 
 EXPORTS = (

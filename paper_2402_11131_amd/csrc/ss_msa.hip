@@ -337,7 +337,7 @@ int ss_msa_attention(const void* q, const void* k_new, const void* v_new, const 
   SS_REQUIRE((long)max_pages_per_seq * page_size <= (1L << 30), SS_ERR_UNSUPPORTED, "%s: sequence capacity too large",
              fn);
   SS_REQUIRE(scale > 0.f && isfinite(scale), SS_ERR_INVALID_ARG, "%s: scale must be positive and finite", fn);
-  SS_REQUIRE((flags & ~(SS_STREAM_EXCLUDE_SELF | SS_MSA_PARTIALS_ONLY)) == 0, SS_ERR_INVALID_ARG,
+  SS_REQUIRE((flags & ~(SS_STREAM_EXCLUDE_SELF | SS_MSA_PARTIALS_ONLY | SS_MSA_MERGE_ONLY)) == 0, SS_ERR_INVALID_ARG,
              "%s: unknown flags 0x%x", fn, flags);
   if (B == 0) return SS_OK;
 
@@ -361,7 +361,11 @@ int ss_msa_attention(const void* q, const void* k_new, const void* v_new, const 
   a.flags = flags;
   hipStream_t st = (hipStream_t)stream;
 
-  if (dtype == SS_F32) {
+  SS_REQUIRE((flags & (SS_MSA_PARTIALS_ONLY | SS_MSA_MERGE_ONLY)) != (SS_MSA_PARTIALS_ONLY | SS_MSA_MERGE_ONLY),
+             SS_ERR_INVALID_ARG, "%s: SS_MSA_PARTIALS_ONLY and SS_MSA_MERGE_ONLY exclude each other", fn);
+  if (flags & SS_MSA_MERGE_ONLY) {
+    // the attention kernel ran in an earlier call with SS_MSA_PARTIALS_ONLY
+  } else if (dtype == SS_F32) {
     dim3 grid(plan.n_qc, plan.n_splits, B * H);
     SS_REQUIRE((long)B * H <= 65535 && plan.n_splits <= 65535, SS_ERR_UNSUPPORTED, "%s: grid too large", fn);
     if (D == 64) hipLaunchKernelGGL(msa_f32_kernel<64>, grid, dim3(256), 0, st, a);

@@ -174,3 +174,26 @@ def test_full_size_sampled_pairs(name, n_pairs):
         err = rel_err(to_np_f32(got[b:b + 1, :, hk * g:(hk + 1) * g]), want)
         print("%s pair (b=%d, hk=%d, L=%d): err %.2e" % (name, b, hk, lens[b], err), flush=True)
         assert err <= TOL["bf16"], (name, b, hk, err)
+
+
+def test_attention_kernel_and_split_merge_as_two_calls():
+    # SS_MSA_PARTIALS_ONLY then SS_MSA_MERGE_ONLY on the same workspace is the full call, bit for bit
+    cfg = synth.scaled(synth.CONFIGS["c2"], B=2, H=4, Hkv=4, L_min=900, L_max=1300)
+    inp = synth.make_msa_inputs(cfg, 11, device=DEV)
+    args = (inp["q"], inp["k_new"], inp["v_new"], inp["k_cache"], inp["v_cache"], inp["block_table"], inp["seq_lens"],
+            inp["parent"], cfg.gamma, inp["scale"])
+    prev = api.ss_msa_set_split_keys(256)          # several splits
+    try:
+        need = api.ss_msa_workspace_bytes(cfg.B, cfg.T, cfg.gamma, cfg.H, cfg.Hkv, cfg.D,
+                                          inp["block_table"].shape[1] * cfg.page, api.SS_BF16)
+        ws = torch.empty(need, dtype=torch.uint8, device=DEV)
+        full = api.ss_msa_attention(*args, workspace=ws).clone()
+        out = torch.zeros_like(full)
+        api.ss_msa_attention(*args, flags=api.SS_MSA_PARTIALS_ONLY, out=out, workspace=ws)
+        api.ss_msa_attention(*args, flags=api.SS_MSA_MERGE_ONLY, out=out, workspace=ws)
+        torch.cuda.synchronize()
+        assert torch.equal(out, full)
+        with pytest.raises(api.SSError):
+            api.ss_msa_attention(*args, flags=api.SS_MSA_PARTIALS_ONLY | api.SS_MSA_MERGE_ONLY, out=out, workspace=ws)
+    finally:
+        api.ss_msa_set_split_keys(prev)
