@@ -161,6 +161,18 @@ int ss_msa_attention(const void* q, const void* k_new, const void* v_new, const 
 int ss_msa_set_split_keys(int split_keys);
 
 /*
+ * Tuning knob for a2 (MFMA path, problems split in two): merge the two splits
+ * inside the attention kernel instead of in a second kernel (default: on).  The
+ * split that finishes second adds the other's partial rows to its own and writes
+ * `out`; the arithmetic is that of the merge kernel, so the result is the same
+ * bit for bit and does not depend on which split finishes first.  The splits
+ * find each other through arrival counters that live in the library (one region
+ * of 32 per call, taken in turn): at most 32 calls may be in flight on one GPU
+ * at the same time with this on.  Returns the previous setting.
+ */
+int ss_msa_set_merge_in_kernel(int on);
+
+/*
  * a3. LM head with fused argmax / top-K (Sec. 3.2.1: the last layer's main row
  * predicts y_t, stream j predicts y_{t+j}; Sec. 3.2.2: top-k tokens per stream).
  *    z[n,v] = sum_d hidden[n,d] * W[v,d]          (never written to memory)

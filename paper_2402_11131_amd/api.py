@@ -27,7 +27,7 @@ SS_MAX_T, SS_MAX_GAMMA, SS_MAX_K = 64, 8, 8
 
 EXPORTS = (
     "ss_version", "ss_last_error", "ss_check_tree_host", "ss_build_mask", "ss_msa_workspace_bytes",
-    "ss_msa_attention", "ss_msa_set_split_keys", "ss_lm_head_workspace_bytes", "ss_lm_head_argmax_topk",
+    "ss_msa_attention", "ss_msa_set_split_keys", "ss_msa_set_merge_in_kernel", "ss_lm_head_workspace_bytes", "ss_lm_head_argmax_topk",
     "ss_tree_verify", "ss_tree_draft", "ss_full_tree_template_host", "ss_kv_commit", "ss_linear_rows", "ss_stream_insert",
     "ss_lm_head_logsumexp", "ss_transition_probs", "ss_tree_prune",
 )
@@ -135,6 +135,11 @@ def ss_msa_workspace_bytes(B, T, gamma, H, Hkv, D, max_seq_len, dtype_code) -> i
 
 def ss_msa_set_split_keys(split_keys: int) -> int:
     return load_library().ss_msa_set_split_keys(int(split_keys))
+
+
+def ss_msa_set_merge_in_kernel(on: bool) -> bool:
+    """Tuning knob: merge two KV splits inside the attention kernel (default on).  Returns the previous setting."""
+    return bool(load_library().ss_msa_set_merge_in_kernel(1 if on else 0))
 
 
 def ss_msa_attention(q, k_new, v_new, k_cache, v_cache, block_table, seq_lens, parent, gamma: int, scale: float,

@@ -55,6 +55,15 @@ SS_DEV uint32_t pack_bf16x2(float lo, float hi) {
 }
 SS_DEV float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
 
+// One step of merging per-split attention results (both the merge kernel and the in-kernel merge use it, so
+// that they agree bit for bit): acc <- acc*keep + v*w with the roundings fixed.
+SS_DEV floatx4 merge_step(floatx4 acc, float keep, floatx4 v, float w) {
+  floatx4 r;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) r[i] = __builtin_fmaf(v[i], w, acc[i] * keep);
+  return r;
+}
+
 // Node 0 is the root; for i > 0 a parent outside [0,i) counts as 0 (documented clamp).
 SS_DEV int clamp_parent(int p, int i) { return (i == 0) ? -1 : ((p < 0 || p >= i) ? 0 : p); }
 

@@ -24,6 +24,7 @@ struct MsaArgs {
   int n_splits;    // S: upper bound on splits per sequence
   int n_qc;        // query-row chunks per (sequence, KV head) (MFMA path)
   int groups;      // wave groups per workgroup the plan asks for (MFMA path)
+  int arrive_region;  // MFMA path, split launches: region of the arrival counters for the in-kernel merge, or -1
   float scale_log2;  // softmax scale times log2(e)
   uint32_t flags;
 };
@@ -32,6 +33,12 @@ struct MsaArgs {
 // also scans the step's new keys).  Split s takes the tokens [s*split_keys, min(L,(s+1)*split_keys)).
 SS_DEV int clamp_len(int L, const MsaArgs& a) { return min(max(L, 0), a.max_pages * a.page); }
 SS_DEV int active_splits(int L, const MsaArgs& a) { return max(1, (L + a.split_keys - 1) / a.split_keys); }
+
+// Arrival counters of the in-kernel split merge: kArriveRegions regions (calls take them in turn, so that calls
+// in flight on different streams do not share one) of kArriveSlots counters, one per (sequence, KV head, row
+// chunk, query tile).
+constexpr int kArriveRegions = 32;
+constexpr int kArriveSlots = 8192;
 
 // MFMA path (bf16, D = 64 or 128).  Returns SS_OK or an error code.
 int launch_msa_bf16(const MsaArgs& a, hipStream_t stream);

@@ -4,6 +4,8 @@
 #include <math.h>
 #include <stdlib.h>
 
+#include <atomic>
+
 #include "ss_msa.h"
 
 namespace ss {
@@ -198,8 +200,8 @@ __global__ __launch_bounds__(256) void msa_combine_kernel(MsaArgs a) {
       if (s0 + i < n_active && l[i] > -INFINITY) {
         const float m_new = fmaxf(m, l[i]);
         const float keep = exp2f(m - m_new), w = exp2f(l[i] - m_new);
-        acc = acc * keep + v[i] * w;
-        wsum = wsum * keep + w;
+        acc = merge_step(acc, keep, v[i], w);
+        wsum = __builtin_fmaf(wsum, keep, w);
         m = m_new;
       }
     }
@@ -217,6 +219,7 @@ __global__ __launch_bounds__(256) void msa_combine_kernel(MsaArgs a) {
 // ------------------------------------------------------------------ planning (host)
 
 static int g_split_keys_override = 0;
+static std::atomic<int> g_merge_in_kernel{1};
 
 struct MsaPlan {
   int split_keys, n_splits, n_qc, groups;
@@ -313,6 +316,8 @@ int ss_msa_set_split_keys(int split_keys) {
   return prev;
 }
 
+int ss_msa_set_merge_in_kernel(int on) { return ss::g_merge_in_kernel.exchange(on ? 1 : 0); }
+
 size_t ss_msa_workspace_bytes(int B, int T, int gamma, int H, int Hkv, int D, int max_seq_len, int dtype) {
   ss::clear_error();
   if (ss::check_shape("ss_msa_workspace_bytes", B, T, gamma, H, Hkv, D, dtype) != SS_OK) return 0;
@@ -358,6 +363,15 @@ int ss_msa_attention(const void* q, const void* k_new, const void* v_new, const 
   a.max_pages = max_pages_per_seq; a.num_pages = num_pages;
   a.split_keys = plan.split_keys; a.n_splits = plan.n_splits; a.n_qc = plan.n_qc; a.groups = plan.groups;
   a.scale_log2 = scale * 1.4426950408889634f;
+  // In-kernel merge (MFMA path, two splits): the second split of a (sequence, head) to finish adds the other's
+  // partial rows to its own and writes the output, which saves the merge kernel and its kernel boundary.  With
+  // more splits the partial rows would be fetched one split after the other and the merge kernel is faster.
+  a.arrive_region = -1;
+  if (g_merge_in_kernel.load() && dtype == SS_BF16 && plan.n_splits == 2 && !(flags & SS_MSA_MERGE_ONLY) &&
+      (long)B * Hkv * plan.n_qc * 5 <= kArriveSlots) {
+    static std::atomic<unsigned int> next_region{0};
+    a.arrive_region = (int)(next_region.fetch_add(1) % kArriveRegions);
+  }
   a.flags = flags;
   hipStream_t st = (hipStream_t)stream;
 
@@ -374,7 +388,7 @@ int ss_msa_attention(const void* q, const void* k_new, const void* v_new, const 
   } else {
     if (int rc = launch_msa_bf16(a, st)) return rc;
   }
-  if (plan.n_splits > 1 && !(flags & SS_MSA_PARTIALS_ONLY)) {
+  if (plan.n_splits > 1 && !(flags & SS_MSA_PARTIALS_ONLY) && a.arrive_region < 0) {
     const long threads = (long)B * R * H * (D / 4);
     dim3 grid((unsigned)((threads + 255) / 256));
     if (dtype == SS_F32) hipLaunchKernelGGL(msa_combine_kernel<false>, grid, dim3(256), 0, st, a);

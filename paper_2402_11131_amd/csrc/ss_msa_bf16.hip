@@ -62,6 +62,48 @@
 
 namespace ss {
 
+// Stores and loads that are coherent at device scope by themselves (the sc1 bit: written through to, read from,
+// the level all XCDs share), for the partial results the in-kernel split merge hands from one workgroup to
+// another: no cache-wide write-back or invalidate is then needed around the arrival counter.
+SS_DEV void st16_device(float* p, floatx4 v) { asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory"); }
+SS_DEV void st4_device(float* p, float v) { asm volatile("global_store_dword %0, %1, off sc1" ::"v"(p), "v"(v) : "memory"); }
+// lse and DT 16-byte pieces (64 bytes apart) of one partial row; returns when all have arrived.
+template <int DT>
+SS_DEV void ld_row_device(const float* lse_p, const float* o_p, float& lse, floatx4 (&o)[DT]) {
+  static_assert(DT == 4 || DT == 8, "D is 64 or 128");
+  if constexpr (DT == 8) {
+    asm volatile(
+        "global_load_dword %0, %9, off sc1\n\t"
+        "global_load_dwordx4 %1, %10, off sc1\n\t"
+        "global_load_dwordx4 %2, %10, off offset:64 sc1\n\t"
+        "global_load_dwordx4 %3, %10, off offset:128 sc1\n\t"
+        "global_load_dwordx4 %4, %10, off offset:192 sc1\n\t"
+        "global_load_dwordx4 %5, %10, off offset:256 sc1\n\t"
+        "global_load_dwordx4 %6, %10, off offset:320 sc1\n\t"
+        "global_load_dwordx4 %7, %10, off offset:384 sc1\n\t"
+        "global_load_dwordx4 %8, %10, off offset:448 sc1\n\t"
+        "s_waitcnt vmcnt(0)"
+        : "=&v"(lse), "=&v"(o[0]), "=&v"(o[1]), "=&v"(o[2]), "=&v"(o[3]), "=&v"(o[4]), "=&v"(o[5]), "=&v"(o[6]), "=&v"(o[7])
+        : "v"(lse_p), "v"(o_p)
+        : "memory");
+  } else {
+    asm volatile(
+        "global_load_dword %0, %5, off sc1\n\t"
+        "global_load_dwordx4 %1, %6, off sc1\n\t"
+        "global_load_dwordx4 %2, %6, off offset:64 sc1\n\t"
+        "global_load_dwordx4 %3, %6, off offset:128 sc1\n\t"
+        "global_load_dwordx4 %4, %6, off offset:192 sc1\n\t"
+        "s_waitcnt vmcnt(0)"
+        : "=&v"(lse), "=&v"(o[0]), "=&v"(o[1]), "=&v"(o[2]), "=&v"(o[3])
+        : "v"(lse_p), "v"(o_p)
+        : "memory");
+  }
+}
+
+// Arrival counters of the in-kernel split merge (zero when the library is loaded; the last split to arrive
+// sets its counter back to zero).
+__device__ unsigned int g_msa_arrive[kArriveRegions * kArriveSlots];
+
 constexpr float kLazyLog2 = 16.0f;
 constexpr int kMaxGroups = 4;  // wave groups per workgroup
 constexpr int kMaxWaves = 16;  // waves per workgroup: 4 per SIMD leaves each wave 128 vector registers
@@ -541,9 +583,69 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
   } else {
     const size_t pr = (((size_t)b * a.H + q_h) * a.n_splits + s) * R + q_r;
     float* op = a.part_o + pr * D + 4 * lg;
+    const float my_lse = mm * c + __log2f(l_run);
+    const bool merge_here = a.arrive_region >= 0 && !(a.flags & SS_MSA_PARTIALS_ONLY);
+    if (!merge_here) {
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt) *reinterpret_cast<floatx4*>(op + 16 * dt) = O[dt] * inv;
-    if (lg == 0) a.part_lse[pr] = mm * c + __log2f(l_run);
+      for (int dt = 0; dt < DT; ++dt) *reinterpret_cast<floatx4*>(op + 16 * dt) = O[dt] * inv;
+      if (lg == 0) a.part_lse[pr] = my_lse;
+    } else {
+      // In-kernel merge of the splits: every query tile of every split announces itself once its partial
+      // result is in memory; the one that finds all others there (none waits for any) adds them to what it
+      // still holds in registers and writes the final rows.  The splits run on different XCDs: the partial
+      // rows are stored and loaded coherently at device scope, and a wave announces itself only when its
+      // stores have completed.
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) st16_device(op + 16 * dt, O[dt] * inv);
+      if (lg == 0) st4_device(a.part_lse + pr, my_lse);
+      __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's partial rows are where every XCD reads them
+      unsigned int* ctr = g_msa_arrive + (size_t)a.arrive_region * kArriveSlots +
+                          (((size_t)b * a.Hkv + hk) * a.n_qc + qc) * NW + wt;
+      unsigned int seen = 0;
+      if (lane == 0) seen = atomicAdd(ctr, 1u);  // lane 0 holds the tile's first row: valid whenever any is
+      seen = __builtin_amdgcn_readfirstlane(seen);
+      if (seen + 1 == (unsigned)n_active) {
+        // the splits in index order with the arithmetic of the merge kernel, so that the result does not
+        // depend on which split came last (its own rows are taken from registers, the others' from memory)
+        floatx4 mine[DT], acc[DT];
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+          mine[dt] = O[dt] * inv;
+          acc[dt] = floatx4{0.f, 0.f, 0.f, 0.f};
+        }
+        float M = -INFINITY, wsum = 0.f;
+        auto fold = [&](float l2, const floatx4 (&o2)[DT]) {
+          if (l2 > -INFINITY) {
+            const float m_new = fmaxf(M, l2);
+            const float keep = exp2f(M - m_new), w2 = exp2f(l2 - m_new);
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) acc[dt] = merge_step(acc[dt], keep, o2[dt], w2);
+            wsum = __builtin_fmaf(wsum, keep, w2);
+            M = m_new;
+          }
+        };
+        auto fold_from_memory = [&](int s2) {
+          const size_t pr2 = (((size_t)b * a.H + q_h) * a.n_splits + s2) * R + q_r;
+          float l2;
+          floatx4 o2[DT];
+          ld_row_device<DT>(a.part_lse + pr2, a.part_o + pr2 * D + 4 * lg, l2, o2);
+          fold(l2, o2);
+        };
+        for (int s2 = 0; s2 < s; ++s2) fold_from_memory(s2);
+        fold(my_lse, mine);
+        for (int s2 = s + 1; s2 < n_active; ++s2) fold_from_memory(s2);
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) O[dt] = acc[dt];
+        const float inv2 = wsum > 0.f ? 1.f / wsum : 0.f;
+        uint16_t* outp = (uint16_t*)a.out + (((size_t)b * R + q_r) * a.H + q_h) * D + 4 * lg;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+          const floatx4 v = O[dt] * inv2;
+          *reinterpret_cast<uintx2*>(outp + 16 * dt) = uintx2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+        }
+        if (lane == 0) *ctr = 0;  // for the next call that gets this region
+      }
+    }
   }
 #ifdef SS_MSA_TIMING
   if (lane == 0 && blockIdx.x < 1024) {

@@ -197,3 +197,30 @@ def test_attention_kernel_and_split_merge_as_two_calls():
             api.ss_msa_attention(*args, flags=api.SS_MSA_PARTIALS_ONLY | api.SS_MSA_MERGE_ONLY, out=out, workspace=ws)
     finally:
         api.ss_msa_set_split_keys(prev)
+
+
+@pytest.mark.parametrize("name", ["c4", "c4short", "gqa"])
+def test_merge_in_kernel_equals_merge_kernel(name):
+    # two splits merged inside the attention kernel (default) against the separate merge kernel: bit for bit,
+    # call after call (the arrival counters must come back to zero), also for sequences with one active split
+    if name == "c4":
+        cfg, lens = synth.CONFIGS["c4"], None
+    elif name == "c4short":
+        cfg, lens = synth.CONFIGS["c4"], [4096, 900, 0, 2500]     # 900 and 0: a single active split
+    else:
+        cfg, lens = synth.scaled(synth.CONFIGS["c5"], B=4, H=16, Hkv=4, L_min=2000, L_max=3000), None   # 8 row chunks
+    inp = synth.make_msa_inputs(cfg, 12, device=DEV)
+    if lens is not None:
+        inp["seq_lens"] = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    args = (inp["q"], inp["k_new"], inp["v_new"], inp["k_cache"], inp["v_cache"], inp["block_table"], inp["seq_lens"],
+            inp["parent"], cfg.gamma, inp["scale"])
+    prev = api.ss_msa_set_merge_in_kernel(False)
+    try:
+        ref = api.ss_msa_attention(*args).clone()
+        api.ss_msa_set_merge_in_kernel(True)
+        for _ in range(3):
+            got = api.ss_msa_attention(*args)
+            torch.cuda.synchronize()
+            assert torch.equal(got, ref)
+    finally:
+        api.ss_msa_set_merge_in_kernel(prev)
