@@ -35,9 +35,11 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, vendor figure
 
 # HBM traffic of one launch of the MSA kernel, from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE; KiB
 # per dispatch), each scaled by what the same counter reads for the 256 MiB device copy of --calibrate-copy
-# (FETCH_SIZE reads half of the bytes the copy fetches: factor 2.0; WRITE_SIZE factor 1.0).  c4: 136309 KiB
-# x 2.0 fetched + 12720 KiB written (the fp32 partials of the two splits).  Summaries are under profiles/.
-MSA_TRAFFIC_BYTES = {"c4": int((136309.0 * 2.0 + 12720.0) * 1024), "c2": None, "c3": None, "c5": None}
+# (FETCH_SIZE reads half of the bytes the copy fetches: factor 2.0; WRITE_SIZE factor 1.0).  c4, the launch
+# the steps make (two splits merged inside the kernel): 139179 KiB x 2.0 fetched (the cache once + one split's
+# partial rows read back) + 15588 KiB written (both splits' fp32 partials + the output).  Summaries are under
+# profiles/.
+MSA_TRAFFIC_BYTES = {"c4": int((139179.0 * 2.0 + 15588.0) * 1024), "c2": None, "c3": None, "c5": None}
 
 
 def msa_bytes(cfg, seq_lens):
@@ -169,6 +171,8 @@ def main():
     ap.add_argument("--workload", default="c4", choices=["c2", "c3", "c4", "c5"])
     ap.add_argument("--split-keys", type=int, default=0, help="KV split length of the MSA kernel (0 = automatic)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--in-step-events", action="store_true",
+                    help="also time the attention kernel inside the steps with a pair of events per launch")
     ap.add_argument("--graph", action="store_true",
                     help="capture the step's launches once into a HIP graph and replay it (measured: no faster "
                          "than launching from the host, the step is bound by the kernels, not by launches)")
@@ -293,18 +297,27 @@ def main():
     # ---- per-kernel figures (each in its own timed loop, same rotation of inputs)
     it = max(20, args.steps)
     us_msa_call = timed(lambda i: msa_call(layers[i % n_sets], outs[0]), it, torch)
-    us_msa_kernel = timed(lambda i: msa_call(layers[i % n_sets], outs[0], api.SS_MSA_PARTIALS_ONLY), it, torch)
-    # The same kernel inside the step, for comparison with a kernel trace: the timed steps again, every
-    # attention call made in its two halves (kernel, then split merge: the same kernels in the same order) with
-    # a pair of events around the first.  This figure includes what the two events cost themselves.
-    evs = []
-    for i in range(args.steps):
-        step(i, evs)
-    torch.cuda.synchronize()
-    us_msa_in_step = sum(a_.elapsed_time(b_) for a_, b_ in evs) * 1000.0 / len(evs)
-    del evs
+    us_msa_partials = timed(lambda i: msa_call(layers[i % n_sets], outs[0], api.SS_MSA_PARTIALS_ONLY), it, torch)
+    # The roofline is that of the attention kernel as the step launches it.  A full call is that kernel alone
+    # when the prefix is unsplit or its two splits are merged inside the kernel (c4): then the loop of whole
+    # calls times it; otherwise a merge kernel follows and the loop that leaves the merge out does.
+    max_len = layers[0]["block_table"].shape[1] * cfg.page
+    n_splits, n_kernels = api.ss_msa_plan(cfg.B, cfg.T, cfg.gamma, cfg.H, cfg.Hkv, cfg.D, max_len,
+                                          api.SS_BF16 if cfg.dtype == "bf16" else api.SS_F32)
+    us_msa_kernel = us_msa_call if n_kernels == 1 else us_msa_partials
     kern = {"msa_call_us": round(us_msa_call, 2), "msa_kernel_us": round(us_msa_kernel, 2),
-            "msa_kernel_in_step_with_events_us": round(us_msa_in_step, 2)}
+            "msa_kernel_without_split_merge_us": round(us_msa_partials, 2), "msa_splits": n_splits,
+            "msa_kernels_per_call": n_kernels}
+    if args.in_step_events:
+        # The attention kernel inside the step, for comparison with a kernel trace: the timed steps again, every
+        # attention call made in its two halves (kernel, then split merge as a kernel of its own) with a pair of
+        # events around the first.  This figure includes what the two events cost themselves.
+        evs = []
+        for i in range(args.steps):
+            step(i, evs)
+        torch.cuda.synchronize()
+        kern["msa_kernel_in_step_with_events_us"] = round(sum(a_.elapsed_time(b_) for a_, b_ in evs) * 1000.0 / len(evs), 2)
+        del evs
     b_msa = msa_bytes(cfg, seq_lens)
     f_msa = msa_flops(cfg, seq_lens)
     gbps = b_msa / (us_msa_kernel * 1e-6) / 1e9
@@ -320,6 +333,10 @@ def main():
                     "unit": "GB/s", "frac": round(gbps / HBM_PEAK_GBPS, 4),
                     "traffic": MSA_TRAFFIC_BYTES.get(args.workload), "algorithmic_bytes": b_msa,
                     "mfma_tflops": round(tflops, 1)}
+    if n_kernels == 1 and n_splits > 1:
+        # for comparison: the same kernel when it leaves the split merge to a second kernel
+        roofline["without_split_merge"] = {"us": round(us_msa_partials, 2),
+                                           "frac": round(b_msa / (us_msa_partials * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)}
     extra = {}
     if has_lm:
         hidden = outs[-1].view(N, cfg.d_model)

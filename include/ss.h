@@ -153,6 +153,17 @@ int ss_msa_attention(const void* q, const void* k_new, const void* v_new, const 
                      void* stream);
 
 /*
+ * What a full call of a2 with this shape will launch, as currently tuned:
+ * *n_splits = number of splits of the cached prefix (1 = unsplit, no workspace
+ * needed), *n_kernels = 1 if the call is a single kernel (unsplit, or two
+ * splits merged inside the attention kernel), 2 if a merge kernel follows.
+ * Either pointer may be NULL.  Host-only, no GPU work.  Returns SS_OK or the
+ * error ss_msa_attention would return for the shape.
+ */
+int ss_msa_plan(int B, int T, int gamma, int H, int Hkv, int D, int max_seq_len, int dtype,
+                int* n_splits, int* n_kernels);
+
+/*
  * Tuning knob for a2: number of cached tokens one workgroup scans (the KV
  * split length).  0 = choose from the problem shape (default).  Values are
  * rounded up to a multiple of 128.  The result of a2 does not depend on it

@@ -27,7 +27,7 @@ SS_MAX_T, SS_MAX_GAMMA, SS_MAX_K = 64, 8, 8
 
 EXPORTS = (
     "ss_version", "ss_last_error", "ss_check_tree_host", "ss_build_mask", "ss_msa_workspace_bytes",
-    "ss_msa_attention", "ss_msa_set_split_keys", "ss_msa_set_merge_in_kernel", "ss_lm_head_workspace_bytes", "ss_lm_head_argmax_topk",
+    "ss_msa_attention", "ss_msa_plan", "ss_msa_set_split_keys", "ss_msa_set_merge_in_kernel", "ss_lm_head_workspace_bytes", "ss_lm_head_argmax_topk",
     "ss_tree_verify", "ss_tree_draft", "ss_full_tree_template_host", "ss_kv_commit", "ss_linear_rows", "ss_stream_insert",
     "ss_lm_head_logsumexp", "ss_transition_probs", "ss_tree_prune",
 )
@@ -59,6 +59,8 @@ def load_library() -> ctypes.CDLL:
     lib.ss_build_mask.argtypes = [vp, i32, i32, i32, u32, vp, vp, vp, vp]
     lib.ss_msa_workspace_bytes.argtypes = [i32] * 8
     lib.ss_msa_workspace_bytes.restype = sz
+    lib.ss_msa_plan.argtypes = [i32] * 8 + [ctypes.POINTER(ctypes.c_int)] * 2
+    lib.ss_msa_plan.restype = i32
     lib.ss_msa_attention.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, i32, i32, i32, i32, i32, i32, i32,
                                      c.c_float, i32, u32, vp, vp, sz, vp]
     lib.ss_msa_set_split_keys.argtypes = [i32]
@@ -131,6 +133,13 @@ def ss_build_mask(parent: torch.Tensor, gamma: int, flags: int = 0, want_mask: b
 
 def ss_msa_workspace_bytes(B, T, gamma, H, Hkv, D, max_seq_len, dtype_code) -> int:
     return load_library().ss_msa_workspace_bytes(B, T, gamma, H, Hkv, D, max_seq_len, dtype_code)
+
+
+def ss_msa_plan(B, T, gamma, H, Hkv, D, max_seq_len, dtype_code):
+    """(n_splits, n_kernels) of a full ss_msa_attention call of this shape, as currently tuned."""
+    ns, nk = ctypes.c_int(0), ctypes.c_int(0)
+    _check(load_library().ss_msa_plan(B, T, gamma, H, Hkv, D, max_seq_len, dtype_code, ctypes.byref(ns), ctypes.byref(nk)))
+    return ns.value, nk.value
 
 
 def ss_msa_set_split_keys(split_keys: int) -> int:

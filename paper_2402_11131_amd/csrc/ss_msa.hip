@@ -294,6 +294,12 @@ static MsaPlan make_plan(int B, int R, int H, int Hkv, int D, int max_len, int d
   return p;
 }
 
+// Whether a full call folds its two splits inside the attention kernel (see ss_msa_attention).
+static bool merges_in_kernel(const MsaPlan& plan, int B, int Hkv, int dtype) {
+  return g_merge_in_kernel.load() && dtype == SS_BF16 && plan.n_splits == 2 &&
+         (long)B * Hkv * plan.n_qc * 5 <= kArriveSlots;
+}
+
 static int check_shape(const char* fn, int B, int T, int gamma, int H, int Hkv, int D, int dtype) {
   SS_REQUIRE(B >= 0, SS_ERR_INVALID_ARG, "%s: B=%d", fn, B);
   SS_REQUIRE(T >= 1 && T <= SS_MAX_T, SS_ERR_UNSUPPORTED, "%s: T=%d outside [1,%d]", fn, T, SS_MAX_T);
@@ -317,6 +323,17 @@ int ss_msa_set_split_keys(int split_keys) {
 }
 
 int ss_msa_set_merge_in_kernel(int on) { return ss::g_merge_in_kernel.exchange(on ? 1 : 0); }
+
+int ss_msa_plan(int B, int T, int gamma, int H, int Hkv, int D, int max_seq_len, int dtype, int* n_splits,
+                int* n_kernels) {
+  ss::clear_error();
+  if (int rc = ss::check_shape("ss_msa_plan", B, T, gamma, H, Hkv, D, dtype)) return rc;
+  if (max_seq_len < 0) max_seq_len = 0;
+  const ss::MsaPlan plan = ss::make_plan(B, T * (1 + gamma), H, Hkv, D, max_seq_len, dtype);
+  if (n_splits) *n_splits = plan.n_splits;
+  if (n_kernels) *n_kernels = (plan.n_splits > 1 && !ss::merges_in_kernel(plan, B, Hkv, dtype)) ? 2 : 1;
+  return SS_OK;
+}
 
 size_t ss_msa_workspace_bytes(int B, int T, int gamma, int H, int Hkv, int D, int max_seq_len, int dtype) {
   ss::clear_error();
@@ -367,8 +384,7 @@ int ss_msa_attention(const void* q, const void* k_new, const void* v_new, const 
   // partial rows to its own and writes the output, which saves the merge kernel and its kernel boundary.  With
   // more splits the partial rows would be fetched one split after the other and the merge kernel is faster.
   a.arrive_region = -1;
-  if (g_merge_in_kernel.load() && dtype == SS_BF16 && plan.n_splits == 2 && !(flags & SS_MSA_MERGE_ONLY) &&
-      (long)B * Hkv * plan.n_qc * 5 <= kArriveSlots) {
+  if (merges_in_kernel(plan, B, Hkv, dtype) && !(flags & SS_MSA_MERGE_ONLY)) {
     static std::atomic<unsigned int> next_region{0};
     a.arrive_region = (int)(next_region.fetch_add(1) % kArriveRegions);
   }

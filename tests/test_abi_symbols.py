@@ -102,6 +102,24 @@ def test_argument_validation_of_the_rows_around_the_hot_path():
     assert b"page_size" in lib.ss_last_error()
 
 
+def test_attention_plan_query_is_host_only():
+    # c4's shape: two splits merged inside the kernel (one kernel per call), two kernels with the knob off;
+    # c3's 512 (sequence, head) items: unsplit; c2: more than two splits, so a merge kernel follows
+    assert api.ss_msa_plan(4, 16, 4, 32, 32, 128, 4096 + 96, api.SS_BF16) == (2, 1)
+    prev = api.ss_msa_set_merge_in_kernel(False)
+    try:
+        assert api.ss_msa_plan(4, 16, 4, 32, 32, 128, 4096 + 96, api.SS_BF16) == (2, 2)
+    finally:
+        api.ss_msa_set_merge_in_kernel(prev)
+    assert api.ss_msa_plan(16, 16, 4, 32, 32, 128, 4096 + 96, api.SS_BF16) == (1, 1)
+    n_splits, n_kernels = api.ss_msa_plan(1, 16, 4, 32, 32, 128, 2048 + 96, api.SS_BF16)
+    assert n_splits > 2 and n_kernels == 2
+    with pytest.raises(api.SSError):
+        api.ss_msa_plan(1, 16, 4, 32, 32, 96, 2048, api.SS_BF16)     # head dim 96
+    # the workspace query agrees: nothing but the header when unsplit
+    assert api.ss_msa_workspace_bytes(16, 16, 4, 32, 32, 128, 4096 + 96, api.SS_BF16) == 256
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(api, "_lib", None)
     monkeypatch.setattr(api, "LIB_PATH", "/nonexistent/libss.so")

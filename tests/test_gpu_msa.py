@@ -224,3 +224,48 @@ def test_merge_in_kernel_equals_merge_kernel(name):
             assert torch.equal(got, ref)
     finally:
         api.ss_msa_set_merge_in_kernel(prev)
+
+
+SWEEP = [
+    # (B, H, Hkv, D, page, T, gamma, branching, max_depth, L_min, L_max)
+    (1, 4, 4, 128, 16, 1, 0, (1,), 1, 300, 300),
+    (3, 8, 2, 128, 16, 5, 1, (2, 2), 2, 64, 700),
+    (2, 8, 1, 128, 32, 16, 4, (4, 2, 2), 3, 500, 1500),
+    (5, 4, 4, 64, 16, 33, 2, (4, 3, 2, 2), 4, 0, 900),
+    (2, 8, 8, 64, 64, 64, 1, (8, 4, 2), 3, 700, 1100),
+    (4, 16, 4, 128, 64, 12, 8, (3, 2, 2), 3, 100, 2100),
+    (2, 4, 2, 128, 16, 64, 8, (8, 4, 2), 3, 257, 800),
+    (7, 2, 2, 64, 32, 7, 3, (2, 2, 2), 3, 31, 640),
+]
+
+
+@pytest.mark.parametrize("case", range(len(SWEEP)))
+def test_two_split_merge_in_kernel_over_shapes(case):
+    # exactly two key splits forced on shapes with one and several row chunks, both head dims, all page
+    # sizes, GQA groups 1..8, ragged lengths down to 0: merged in the kernel = merged by the merge kernel,
+    # bit for bit, on three calls in a row; and the result is the oracle's
+    B, H, Hkv, D, page, T, gamma, br, md, lo, hi = SWEEP[case]
+    cfg = synth.scaled(synth.CONFIGS["c2"], B=B, H=H, Hkv=Hkv, D=D, page=page, T=T, gamma=gamma, branching=br,
+                       max_depth=md, L_min=lo, L_max=hi)
+    inp = synth.make_msa_inputs(cfg, 40 + case, device=DEV)
+    args = (inp["q"], inp["k_new"], inp["v_new"], inp["k_cache"], inp["v_cache"], inp["block_table"], inp["seq_lens"],
+            inp["parent"], cfg.gamma, inp["scale"])
+    max_len = inp["block_table"].shape[1] * page
+    prev_keys = api.ss_msa_set_split_keys(max(64, (max_len // 2 + 31) // 32 * 32))
+    prev = api.ss_msa_set_merge_in_kernel(False)
+    try:
+        ws = torch.empty(api.ss_msa_workspace_bytes(B, T, gamma, H, Hkv, D, max_len, api.SS_BF16), dtype=torch.uint8,
+                         device=DEV)
+        ref = api.ss_msa_attention(*args, workspace=ws).clone()
+        api.ss_msa_set_merge_in_kernel(True)
+        for _ in range(3):
+            got = api.ss_msa_attention(*args, workspace=ws)
+            torch.cuda.synchronize()
+            assert torch.equal(got, ref), SWEEP[case]
+    finally:
+        api.ss_msa_set_merge_in_kernel(prev)
+        api.ss_msa_set_split_keys(prev_keys)
+    want = _oracle({k: (v.cpu() if isinstance(v, torch.Tensor) else v) for k, v in inp.items()}, cfg.gamma)
+    err = rel_err(to_np_f32(ref), want)
+    print("sweep case", SWEEP[case], "err %.2e" % err, flush=True)
+    assert err <= TOL["bf16"]
