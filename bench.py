@@ -171,6 +171,8 @@ def main():
     ap.add_argument("--workload", default="c4", choices=["c2", "c3", "c4", "c5"])
     ap.add_argument("--split-keys", type=int, default=0, help="KV split length of the MSA kernel (0 = automatic)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--separate-tail", action="store_true",
+                    help="LM head, verification and drafting as three calls instead of the fused one")
     ap.add_argument("--in-step-events", action="store_true",
                     help="also time the attention kernel inside the steps with a pair of events per launch")
     ap.add_argument("--graph", action="store_true",
@@ -246,11 +248,20 @@ def main():
                 kernel_events.append((e0, e1))
         if has_lm:
             hidden = outs[-1].view(N, cfg.d_model)
-            api.ss_lm_head_argmax_topk(hidden, lm["W"], cfg.K, idx=idx, val=val, workspace=lm_ws)
-            ver = api.ss_tree_verify(tok, parent, idx, cfg.max_depth, batch_stride=cfg.R * cfg.K, node_stride=cfg.K)
-            nxt = api.ss_tree_draft(idx, cfg.K, ver["last"], ver["bonus"], cfg.T, cfg.gamma,
-                                    branching=cfg.draft_branching, batch_stride=cfg.R * cfg.K, offset=cfg.T * cfg.K)
-            state["ver"], state["nxt"] = ver, nxt
+            if args.separate_tail:
+                # a3, a4 and a5 as three calls (four kernels)
+                api.ss_lm_head_argmax_topk(hidden, lm["W"], cfg.K, idx=idx, val=val, workspace=lm_ws)
+                ver = api.ss_tree_verify(tok, parent, idx, cfg.max_depth, batch_stride=cfg.R * cfg.K, node_stride=cfg.K)
+                nxt = api.ss_tree_draft(idx, cfg.K, ver["last"], ver["bonus"], cfg.T, cfg.gamma,
+                                        branching=cfg.draft_branching, batch_stride=cfg.R * cfg.K, offset=cfg.T * cfg.K)
+                state["ver"], state["nxt"], state["argmax"] = ver, nxt, idx.view(cfg.B, cfg.R, cfg.K)[:, :cfg.T, 0]
+            else:
+                # the same three rows in one call (two kernels): the candidate merge happens in the kernel
+                # that verifies and drafts, for the rows those steps read
+                t = api.ss_lm_head_verify_draft(hidden, lm["W"], cfg.K, tok, parent, cfg.gamma, cfg.max_depth,
+                                                branching=cfg.draft_branching, workspace=lm_ws, out=state.get("tail"))
+                state["tail"] = t
+                state["ver"], state["nxt"], state["argmax"] = t, (t["next_tok"], t["next_parent"]), t["main_argmax"]
 
     for i in range(args.warmup):
         step(i)
@@ -260,7 +271,7 @@ def main():
         # Plant the draft the way a decode loop would have produced it: along one seeded root path per
         # sequence each draft token equals the main stream's token at its parent with probability 0.7
         # (until the first miss), which gives the accepted lengths the paper's call-reduction ratios imply.
-        a = idx.cpu().numpy().reshape(cfg.B, cfg.R, cfg.K)[:, :cfg.T, 0]
+        a = state["argmax"].cpu().numpy()
         par = parent.cpu().numpy()
         rng = synth.rng_for(99)
         for b in range(cfg.B):
@@ -277,14 +288,14 @@ def main():
     use_graph = args.graph and n_sets == cfg.n_layers
     run_step = step
     if use_graph:
-        eager = [state["ver"]["out_tokens"].clone(), state["nxt"][0].clone(), idx.clone()] if has_lm else [o.clone() for o in outs]
+        eager = [state["ver"]["out_tokens"].clone(), state["nxt"][0].clone(), state["argmax"].clone()] if has_lm else [o.clone() for o in outs]
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
             step(0)
         for _ in range(3):
             graph.replay()
             torch.cuda.synchronize()
-            now = [state["ver"]["out_tokens"], state["nxt"][0], idx] if has_lm else outs
+            now = [state["ver"]["out_tokens"], state["nxt"][0], state["argmax"]] if has_lm else outs
             for e_, n_ in zip(eager, now):
                 if not torch.equal(e_, n_):
                     print("bench.py: a graph replay differs from the eager step", file=sys.stderr)
@@ -345,6 +356,10 @@ def main():
         w_copies = [lm["W"], lm["W"].clone()]
         us_lm = timed(lambda i: api.ss_lm_head_argmax_topk(hidden, w_copies[i & 1], cfg.K, idx=idx, val=val,
                                                            workspace=lm_ws), it, torch)
+        tail_out = state.get("tail")
+        us_tail = timed(lambda i: api.ss_lm_head_verify_draft(hidden, w_copies[i & 1], cfg.K, tok, parent, cfg.gamma,
+                                                              cfg.max_depth, branching=cfg.draft_branching,
+                                                              workspace=lm_ws, out=tail_out), it, torch)
         del w_copies
         us_ver = timed(lambda i: api.ss_tree_verify(tok, parent, idx, cfg.max_depth, batch_stride=cfg.R * cfg.K,
                                                     node_stride=cfg.K), it, torch)
@@ -359,7 +374,7 @@ def main():
         us_commit = timed(lambda i: [api.ss_kv_commit(l["k_new"], l["v_new"], l["k_cache"], l["v_cache"], l["block_table"], short,
                                                        ver["path"], ver["n_accept"], cfg.gamma, new_seq_lens=new_lens)
                                      for l in layers[:cfg.n_layers]], it, torch)
-        kern.update({"lm_head_call_us": round(us_lm, 2), "verify_us": round(us_ver, 2), "draft_us": round(us_draft, 2),
+        kern.update({"lm_head_call_us": round(us_lm, 2), "lm_head_verify_draft_call_us": round(us_tail, 2), "verify_us": round(us_ver, 2), "draft_us": round(us_draft, 2),
                      "kv_commit_all_layers_us": round(us_commit, 2)})
         f_lm = 2.0 * N * cfg.vocab * cfg.d_model
         tf = f_lm / (us_lm * 1e-6) / 1e12

@@ -321,6 +321,33 @@ int ss_tree_draft(const int32_t* stream_topk, long topk_batch_stride, int K, con
                   int32_t* next_parent, void* stream);
 
 /*
+ * a3 + a4 + a5 in one call: the tail of a decode step (Sec. 3.2.1, 3.2.2,
+ * Appendix A.1) in two kernels instead of four.  `hidden` holds the last
+ * layer's rows of B sequences, R = T*(1+gamma) rows each: the main row of node
+ * i at row i, stream j (1..gamma) of node i at row T + i*gamma + (j-1).  The
+ * result equals ss_lm_head_argmax_topk on all B*R rows, then ss_tree_verify
+ * on the main rows' arg-max, then ss_tree_draft on the stream rows' top-K;
+ * the merge of the per-tile candidates is done only for the rows those two
+ * steps read (the T main rows; the gamma stream rows of the last accepted
+ * node), inside the kernel that verifies and drafts.
+ *  hidden [B*R,d], W [V,d], dtype, K: as for a3 (K = width of the draft).
+ *  tok, parent [B,T]; max_depth; n_accept, last, bonus [B]; path, out_tokens
+ *  [B,max_depth+1]: as for a4.
+ *  tmpl_parent, tmpl_rank (DEVICE) or branching (HOST), T2, next_tok [B,T2],
+ *  next_parent [T2] or NULL: as for a5.
+ *  main_argmax [B,T] int32 out or NULL: the main rows' arg-max tokens.
+ *  workspace: at least ss_lm_head_workspace_bytes(B*R, d, V, K, dtype) bytes.
+ * Limits and errors: those of a3, a4 and a5.
+ */
+int ss_lm_head_verify_draft(const void* hidden, const void* W, int d, int V, int K, int dtype,
+                            const int32_t* tok, const int32_t* parent, int B, int T, int gamma,
+                            int max_depth, const int32_t* tmpl_parent, const int32_t* tmpl_rank,
+                            const int32_t* branching, int T2, int32_t* n_accept, int32_t* last,
+                            int32_t* bonus, int32_t* path, int32_t* out_tokens, int32_t* next_tok,
+                            int32_t* next_parent, int32_t* main_argmax, void* workspace,
+                            size_t workspace_bytes, void* stream);
+
+/*
  * Host helper for a5: writes the full-tree template described above into HOST
  * arrays parent_out/rank_out/depth_out (each [T2] or NULL) and returns the node
  * count, or -1 if it would exceed `capacity` or SS_MAX_T.  All pointers HOST.

@@ -27,7 +27,7 @@ SS_MAX_T, SS_MAX_GAMMA, SS_MAX_K = 64, 8, 8
 
 EXPORTS = (
     "ss_version", "ss_last_error", "ss_check_tree_host", "ss_build_mask", "ss_msa_workspace_bytes",
-    "ss_msa_attention", "ss_msa_plan", "ss_msa_set_split_keys", "ss_msa_set_merge_in_kernel", "ss_lm_head_workspace_bytes", "ss_lm_head_argmax_topk",
+    "ss_msa_attention", "ss_msa_plan", "ss_msa_set_split_keys", "ss_msa_set_merge_in_kernel", "ss_lm_head_workspace_bytes", "ss_lm_head_argmax_topk", "ss_lm_head_verify_draft",
     "ss_tree_verify", "ss_tree_draft", "ss_full_tree_template_host", "ss_kv_commit", "ss_linear_rows", "ss_stream_insert",
     "ss_lm_head_logsumexp", "ss_transition_probs", "ss_tree_prune",
 )
@@ -68,6 +68,7 @@ def load_library() -> ctypes.CDLL:
     lib.ss_lm_head_workspace_bytes.restype = sz
     lib.ss_lm_head_argmax_topk.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, sz, vp]
     lib.ss_tree_verify.argtypes = [vp, vp, vp, lng, lng, i32, i32, i32, vp, vp, vp, vp, vp, vp]
+    lib.ss_lm_head_verify_draft.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, i32, i32, i32, i32, vp, vp, vp, i32] + [vp] * 9 + [sz, vp]
     lib.ss_tree_draft.argtypes = [vp, lng, i32, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, vp]
     lib.ss_full_tree_template_host.argtypes = [vp, i32, i32, vp, vp, vp]
     lib.ss_kv_commit.argtypes = [vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp, vp]
@@ -289,6 +290,61 @@ def ss_tree_draft(stream_topk, K: int, last, bonus, T: int, gamma: int, tmpl_par
                              None if tmpl_rank is None else _dev(tmpl_rank, i32, "tmpl_rank"), br_ptr, B, T, gamma,
                              T2, next_tok.data_ptr(), next_parent.data_ptr(), _stream()))
     return next_tok, next_parent
+
+
+def ss_lm_head_verify_draft(hidden, W, K: int, tok, parent, gamma: int, max_depth: int, tmpl_parent=None,
+                            tmpl_rank=None, branching: Optional[Sequence[int]] = None, T2: Optional[int] = None,
+                            workspace=None, out: Optional[dict] = None) -> dict:
+    """a3 + a4 + a5 in one call.  hidden [B*T*(1+gamma), d] (main rows of a sequence first, then its stream
+    rows node by node), W [V,d], tok/parent [B,T] int32.  Returns the outputs of ss_tree_verify plus next_tok
+    [B,T2], next_parent [T2] and main_argmax [B,T]; `out` (a dict from an earlier call) is reused if given."""
+    lib = load_library()
+    dt = hidden.dtype
+    code = _dtype_code(hidden)
+    N, d = hidden.shape
+    V = W.shape[0]
+    B, T = tok.shape
+    if W.shape[1] != d:
+        raise ValueError("hidden and W disagree on d")
+    if N != B * T * (1 + gamma):
+        raise ValueError("hidden has %d rows, expected B*T*(1+gamma) = %d" % (N, B * T * (1 + gamma)))
+    i32 = torch.int32
+    br = None
+    br_ptr = None
+    if tmpl_parent is None:
+        if branching is None:
+            raise ValueError("give a template or per-level branching")
+        br = torch.tensor(list(branching), dtype=i32)
+        br_ptr = br.data_ptr()
+        if T2 is None:
+            T2, width = 1, 1
+            for k in branching:
+                width *= int(k)
+                T2 += width
+    else:
+        T2 = tmpl_parent.shape[0]
+    dev = hidden.device
+    if out is None:
+        out = dict(n_accept=torch.empty(B, dtype=i32, device=dev), last=torch.empty(B, dtype=i32, device=dev),
+                   bonus=torch.empty(B, dtype=i32, device=dev),
+                   path=torch.empty((B, max_depth + 1), dtype=i32, device=dev),
+                   out_tokens=torch.empty((B, max_depth + 1), dtype=i32, device=dev),
+                   next_tok=torch.empty((B, T2), dtype=i32, device=dev),
+                   next_parent=torch.empty(T2, dtype=i32, device=dev),
+                   main_argmax=torch.empty((B, T), dtype=i32, device=dev))
+    elif out["next_tok"].shape != (B, T2) or out["path"].shape != (B, max_depth + 1) or out["main_argmax"].shape != (B, T):
+        raise ValueError("`out` was made for another shape")
+    need = lib.ss_lm_head_workspace_bytes(N, d, V, K, code)
+    if workspace is None:
+        workspace = torch.empty(max(need, 1), dtype=torch.uint8, device=dev)
+    _check(lib.ss_lm_head_verify_draft(
+        _dev(hidden, dt, "hidden"), _dev(W, dt, "W"), d, V, K, code, _dev(tok, i32, "tok"), _dev(parent, i32, "parent"),
+        B, T, gamma, max_depth, None if tmpl_parent is None else _dev(tmpl_parent, i32, "tmpl_parent"),
+        None if tmpl_rank is None else _dev(tmpl_rank, i32, "tmpl_rank"), br_ptr, T2,
+        *[_dev(out[k], i32, k) for k in ("n_accept", "last", "bonus", "path", "out_tokens", "next_tok", "next_parent",
+                                        "main_argmax")],
+        _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream()))
+    return out
 
 
 def ss_kv_commit(k_new, v_new, k_cache, v_cache, block_table, seq_lens, path, n_accept, gamma: int,

@@ -9,6 +9,7 @@
 #include <stdlib.h>
 
 #include "ss_common.h"
+#include "ss_tree.h"
 
 namespace ss {
 
@@ -475,15 +476,11 @@ __global__ __launch_bounds__(64 * NW, 1) void lm_head_bf16_kernel(LmArgs a) {
 }
 
 // ------------------------------------------------------------------ merge of the parts' candidates
-// One wavefront (one workgroup) per row.  Every lane folds its share of the row's candidates into a K-entry list in
+// One wavefront per row.  Every lane folds its share of the row's candidates into a K-entry list in
 // one pass over memory; then K rounds of a wave-wide arg-max over the heads of the lists, the
-// winning lane popping its head.
-__global__ __launch_bounds__(64) void lm_head_reduce_kernel(LmArgs a) {
-  const int lane = threadIdx.x;
-  const int row = blockIdx.x;
-  if (row >= a.N) return;
-  const int n = a.n_tiles * a.K;
-  const uint64_t* ck = a.cand_key + (size_t)row * n;
+// winning lane popping its head.  `emit(k, key)` is called on every lane with the k-th best key.
+template <typename Emit>
+SS_DEV void row_topk(const uint64_t* __restrict__ ck, int n, int K, int lane, Emit emit) {
   TopList<SS_MAX_K> top;
   top.clear();
   for (int e0 = lane; e0 < n; e0 += 256) {
@@ -493,23 +490,94 @@ __global__ __launch_bounds__(64) void lm_head_reduce_kernel(LmArgs a) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) top.insert(c[j]);
   }
-  for (int k = 0; k < a.K; ++k) {
+  for (int k = 0; k < K; ++k) {
     uint64_t best = top.k[0];
     for (int off = 32; off > 0; off >>= 1) {
       const uint32_t lo = __shfl_xor((uint32_t)best, off, 64), hi = __shfl_xor((uint32_t)(best >> 32), off, 64);
       const uint64_t o = ((uint64_t)hi << 32) | lo;
       best = o > best ? o : best;
     }
-    if (lane == 0) {
-      a.idx[(size_t)row * a.K + k] = key_id(best);
-      a.val[(size_t)row * a.K + k] = key_value(best);
-    }
+    emit(k, best);
     if (best == top.k[0] && best != 0) {  // keys are unique (token ids are): this lane won, pop its head
 #pragma unroll
       for (int j = 0; j + 1 < SS_MAX_K; ++j) top.k[j] = top.k[j + 1];
       top.k[SS_MAX_K - 1] = 0;
     }
   }
+}
+
+__global__ __launch_bounds__(64) void lm_head_reduce_kernel(LmArgs a) {
+  const int lane = threadIdx.x;
+  const int row = blockIdx.x;
+  if (row >= a.N) return;
+  const int n = a.n_tiles * a.K;
+  row_topk(a.cand_key + (size_t)row * n, n, a.K, lane, [&](int k, uint64_t best) {
+    if (lane == 0) {
+      a.idx[(size_t)row * a.K + k] = key_id(best);
+      a.val[(size_t)row * a.K + k] = key_value(best);
+    }
+  });
+}
+
+// ------------------------------------------------------------------ fused tail: merge + verify + draft
+// One workgroup of 16 wavefronts per sequence.  Only the rows the two tree steps read are merged: the
+// arg-max of the T main rows (a wave per row), then, once the accepted path is known, the top-K of the
+// gamma stream rows of its last node (a wave per stream).  Rows of a sequence: main row of node i at i,
+// stream j of node i at T + i*gamma + (j-1).
+struct TailArgs {
+  const uint64_t* cand_key;  // [B*R][n_parts][K]
+  int n_parts, K;
+  const int32_t *tok, *parent;
+  int T, gamma, max_depth, T2;
+  const int32_t *tmpl_parent, *tmpl_rank;
+  TemplateArg targ;
+  int32_t *n_accept, *last, *bonus, *path, *out_tokens, *next_tok, *next_parent, *main_argmax;
+};
+
+__global__ __launch_bounds__(1024) void lm_tail_kernel(TailArgs t) {
+  __shared__ VerifyLds vs;
+  __shared__ int am[64];
+  __shared__ int topk[SS_MAX_GAMMA * SS_MAX_K];
+  __shared__ int dpar[64];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, b = blockIdx.x;
+  const int R = t.T * (1 + t.gamma);
+  const int n = t.n_parts * t.K;
+  int p, my_tok;
+  verify_load(tid, b, t.tok, t.parent, t.T, p, my_tok);  // in flight during the arg-max pass
+  int tp, trank;
+  draft_load(tid, t.tmpl_parent, t.tmpl_rank, t.targ, t.T2, tp, trank);
+  for (int i = w; i < t.T; i += 16) {
+    const uint64_t* ck = t.cand_key + ((size_t)b * R + i) * n;
+    uint64_t best = 0;
+    for (int e0 = lane; e0 < n; e0 += 512) {  // eight independent loads, then the compares
+      uint64_t c[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) c[j] = e0 + 64 * j < n ? ck[e0 + 64 * j] : 0;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) best = c[j] > best ? c[j] : best;
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+      const uint32_t lo = __shfl_xor((uint32_t)best, off, 64), hi = __shfl_xor((uint32_t)(best >> 32), off, 64);
+      const uint64_t o = ((uint64_t)hi << 32) | lo;
+      best = o > best ? o : best;
+    }
+    if (lane == 0) {
+      am[i] = key_id(best);
+      if (t.main_argmax) t.main_argmax[(size_t)b * t.T + i] = key_id(best);
+    }
+  }
+  __syncthreads();
+  int node, bonus_tok;
+  verify_sequence(tid, b, p, my_tok, am, 1, t.T, t.max_depth, t.n_accept, t.last, t.bonus, t.path, t.out_tokens, vs,
+                  node, bonus_tok);
+  if (w < t.gamma) {
+    const uint64_t* ck = t.cand_key + ((size_t)b * R + t.T + (size_t)node * t.gamma + w) * n;
+    row_topk(ck, n, t.K, lane, [&](int k, uint64_t best) {
+      if (lane == 0) topk[w * t.K + k] = key_id(best);
+    });
+  }
+  __syncthreads();
+  draft_sequence(tid, b, tp, trank, topk, t.K, bonus_tok, t.gamma, t.T2, t.next_tok, t.next_parent, dpar);
 }
 
 struct LmFlavour {
@@ -658,26 +726,19 @@ size_t ss_lm_head_workspace_bytes(int N, int d, int V, int K, int dtype) {
   return (size_t)(N < 1 ? 1 : N) * ss::lm_tiles(V, dtype) * K * 8 + 512;
 }
 
-int ss_lm_head_argmax_topk(const void* hidden, const void* W, int N, int d, int V, int K, int dtype, int32_t* idx,
-                           float* val, void* workspace, size_t workspace_bytes, void* stream) {
+// The first kernel of a3: K candidates per (row, vocabulary tile) into the workspace.  Arguments are checked
+// by the callers; fills *a for the kernel that merges the candidates.
+static int lm_candidates(const char* fn, const void* hidden, const void* W, int N, int d, int V, int K, int dtype,
+                         void* workspace, hipStream_t st, ss::LmArgs* out) {
   using namespace ss;
-  clear_error();
-  const char* fn = "ss_lm_head_argmax_topk";
-  if (int rc = lm_check(fn, N, d, V, K, dtype)) return rc;
-  SS_REQUIRE(N == 0 || (hidden && W && idx && val), SS_ERR_INVALID_ARG, "%s: NULL tensor argument", fn);
-  const size_t need = ss_lm_head_workspace_bytes(N, d, V, K, dtype);
-  SS_REQUIRE(N == 0 || (workspace != nullptr && workspace_bytes >= need), SS_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given",
-             fn, need, workspace_bytes);
-  if (N == 0) return SS_OK;
   LmArgs a;
   a.hidden = hidden; a.W = W; a.N = N; a.d = d; a.V = V; a.K = K;
   a.n_tiles = lm_tiles(V, dtype);
   a.n_chunks = 1;
   char* ws = (char*)(((uintptr_t)workspace + 255) & ~(uintptr_t)255);
   a.cand_key = (uint64_t*)ws;
-  a.idx = idx; a.val = val;
+  a.idx = nullptr; a.val = nullptr;
   a.y = nullptr; a.lse = nullptr;
-  hipStream_t st = (hipStream_t)stream;
   if (dtype == SS_F32) {
     dim3 grid(a.n_tiles, ceil_div(N, 32));
     SS_REQUIRE(grid.y <= 65535, SS_ERR_UNSUPPORTED, "%s: N too large", fn);
@@ -689,8 +750,73 @@ int ss_lm_head_argmax_topk(const void* hidden, const void* W, int N, int d, int 
     const int KT = K == 1 ? 1 : (K <= 4 ? 4 : 8);
     if (int rc = launch_lm_bf16(f, KT, st, a)) return rc;
   }
-  if (int rc = check_launch(fn)) return rc;
+  *out = a;
+  return check_launch(fn);
+}
+
+int ss_lm_head_argmax_topk(const void* hidden, const void* W, int N, int d, int V, int K, int dtype, int32_t* idx,
+                           float* val, void* workspace, size_t workspace_bytes, void* stream) {
+  using namespace ss;
+  clear_error();
+  const char* fn = "ss_lm_head_argmax_topk";
+  if (int rc = lm_check(fn, N, d, V, K, dtype)) return rc;
+  SS_REQUIRE(N == 0 || (hidden && W && idx && val), SS_ERR_INVALID_ARG, "%s: NULL tensor argument", fn);
+  const size_t need = ss_lm_head_workspace_bytes(N, d, V, K, dtype);
+  SS_REQUIRE(N == 0 || (workspace != nullptr && workspace_bytes >= need), SS_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given",
+             fn, need, workspace_bytes);
+  if (N == 0) return SS_OK;
+  hipStream_t st = (hipStream_t)stream;
+  LmArgs a;
+  if (int rc = lm_candidates(fn, hidden, W, N, d, V, K, dtype, workspace, st, &a)) return rc;
+  a.idx = idx; a.val = val;
   hipLaunchKernelGGL(lm_head_reduce_kernel, dim3(N), dim3(64), 0, st, a);
+  return check_launch(fn);
+}
+
+int ss_lm_head_verify_draft(const void* hidden, const void* W, int d, int V, int K, int dtype, const int32_t* tok,
+                            const int32_t* parent, int B, int T, int gamma, int max_depth, const int32_t* tmpl_parent,
+                            const int32_t* tmpl_rank, const int32_t* branching, int T2, int32_t* n_accept,
+                            int32_t* last, int32_t* bonus, int32_t* path, int32_t* out_tokens, int32_t* next_tok,
+                            int32_t* next_parent, int32_t* main_argmax, void* workspace, size_t workspace_bytes,
+                            void* stream) {
+  using namespace ss;
+  clear_error();
+  const char* fn = "ss_lm_head_verify_draft";
+  SS_REQUIRE(B >= 0 && B <= (1 << 20), SS_ERR_INVALID_ARG, "%s: B=%d", fn, B);
+  SS_REQUIRE(T >= 1 && T <= SS_MAX_T && T2 >= 1 && T2 <= SS_MAX_T, SS_ERR_UNSUPPORTED, "%s: T=%d or T2=%d outside [1,%d]",
+             fn, T, T2, SS_MAX_T);
+  SS_REQUIRE(gamma >= 0 && gamma <= SS_MAX_GAMMA, SS_ERR_UNSUPPORTED, "%s: gamma=%d outside [0,%d]", fn, gamma,
+             SS_MAX_GAMMA);
+  SS_REQUIRE(max_depth >= 0 && max_depth < SS_MAX_T, SS_ERR_UNSUPPORTED, "%s: max_depth=%d outside [0,%d)", fn, max_depth,
+             SS_MAX_T);
+  const long rows = (long)B * T * (1 + gamma);
+  SS_REQUIRE(rows < (1L << 30), SS_ERR_UNSUPPORTED, "%s: %ld rows", fn, rows);
+  const int N = (int)rows;
+  if (int rc = lm_check(fn, N, d, V, K, dtype)) return rc;
+  SS_REQUIRE(B == 0 || (hidden && W && tok && parent && n_accept && last && bonus && path && out_tokens && next_tok),
+             SS_ERR_INVALID_ARG, "%s: NULL argument", fn);
+  SS_REQUIRE((tmpl_parent == nullptr) == (tmpl_rank == nullptr), SS_ERR_INVALID_ARG,
+             "%s: tmpl_parent and tmpl_rank must both be given or both be NULL", fn);
+  TailArgs t;
+  if (!tmpl_parent) {
+    if (int rc = draft_template_from_branching(fn, branching, gamma, K, T2, &t.targ)) return rc;
+  } else {
+    for (int i = 0; i < SS_MAX_T; ++i) t.targ.parent[i] = t.targ.rank[i] = 0;
+  }
+  const size_t need = ss_lm_head_workspace_bytes(N, d, V, K, dtype);
+  SS_REQUIRE(B == 0 || (workspace != nullptr && workspace_bytes >= need), SS_ERR_WORKSPACE,
+             "%s: workspace of %zu bytes needed, %zu given", fn, need, workspace_bytes);
+  if (B == 0) return SS_OK;
+  hipStream_t st = (hipStream_t)stream;
+  LmArgs a;
+  if (int rc = lm_candidates(fn, hidden, W, N, d, V, K, dtype, workspace, st, &a)) return rc;
+  t.cand_key = a.cand_key; t.n_parts = a.n_tiles; t.K = K;
+  t.tok = tok; t.parent = parent;
+  t.T = T; t.gamma = gamma; t.max_depth = max_depth; t.T2 = T2;
+  t.tmpl_parent = tmpl_parent; t.tmpl_rank = tmpl_rank;
+  t.n_accept = n_accept; t.last = last; t.bonus = bonus; t.path = path; t.out_tokens = out_tokens;
+  t.next_tok = next_tok; t.next_parent = next_parent; t.main_argmax = main_argmax;
+  hipLaunchKernelGGL(lm_tail_kernel, dim3(B), dim3(1024), 0, st, t);
   return check_launch(fn);
 }
 

@@ -102,6 +102,27 @@ def test_argument_validation_of_the_rows_around_the_hot_path():
     assert b"page_size" in lib.ss_last_error()
 
 
+def test_argument_validation_of_the_fused_tail():
+    lib = api.load_library()
+    one = ctypes.c_void_p(8)  # never dereferenced: validation fails first
+    br = (ctypes.c_int32 * 2)(2, 2)
+
+    def call(d=128, V=500, K=4, dtype=1, B=2, T=8, gamma=2, max_depth=3, tp=None, tr=None, branching=br, T2=7,
+             ws=one, ws_bytes=1 << 30, hidden=one):
+        return lib.ss_lm_head_verify_draft(hidden, one, d, V, K, dtype, one, one, B, T, gamma, max_depth, tp, tr,
+                                           branching, T2, one, one, one, one, one, one, None, None, ws, ws_bytes, None)
+
+    assert call(T=65) == 2 and call(gamma=9) == 2 and call(max_depth=64) == 2 and call(K=9) == 2
+    assert call(d=100) == 2                                  # bf16 needs d % 64 == 0
+    assert call(T2=6) == 1 and b"7" in lib.ss_last_error()   # branching (2,2) has 7 nodes
+    assert call(K=1) == 1                                    # branching 2 exceeds K = 1
+    assert call(branching=None) == 1                         # neither template nor branching
+    assert call(tp=one) == 1                                 # template given by half
+    assert call(hidden=None) == 1
+    assert call(ws_bytes=64) == 4 and b"workspace" in lib.ss_last_error()
+    assert call(B=0, hidden=None, ws=None, ws_bytes=0) == 0  # empty batch: no-op
+
+
 def test_attention_plan_query_is_host_only():
     # c4's shape: two splits merged inside the kernel (one kernel per call), two kernels with the knob off;
     # c3's 512 (sequence, head) items: unsplit; c2: more than two splits, so a merge kernel follows
