@@ -89,3 +89,46 @@ def test_fused_tail_with_a_device_template():
     assert np.array_equal(out["next_tok"].cpu().numpy(), o_next)
     assert (out["next_tok"][:, 9] == -1).all()
     assert np.array_equal(out["out_tokens"].cpu().numpy(), o_ver["out_tokens"])
+
+
+def test_c4_full_size_fused_tail():
+    # workload c4 at full size (320 x 4096 x 32000), acceptance planted in the hidden states: the fused call
+    # equals the three calls bit for bit, finds the planted accepted lengths, and the rows it merged (the main
+    # rows, the stream rows of the last accepted node) agree with the oracle's logits for those rows
+    cfg = synth.CONFIGS["c4"]
+    B, T, R, K, gamma = cfg.B, cfg.T, cfg.R, cfg.K, cfg.gamma
+    inp = synth.make_lm_head_inputs(cfg, 3)
+    parent = synth.make_trees(3, B, T, cfg.branching, cfg.max_depth)
+    tok = synth.make_draft_tokens(3, parent, cfg.vocab)
+    planted = synth.plant_acceptance(3, parent, tok, inp["hidden"], inp["W"], R, p_match=0.8)
+    g_h, g_W = inp["hidden"].to(DEV), inp["W"].to(DEV)
+    g_tok, g_par = torch.from_numpy(tok).to(DEV), torch.from_numpy(parent).to(DEV)
+    idx, _ = api.ss_lm_head_argmax_topk(g_h, g_W, K)
+    ver = api.ss_tree_verify(g_tok, g_par, idx, cfg.max_depth, batch_stride=R * K, node_stride=K)
+    nxt, npar = api.ss_tree_draft(idx, K, ver["last"], ver["bonus"], T, gamma, branching=cfg.draft_branching,
+                                  batch_stride=R * K, offset=T * K)
+    out = api.ss_lm_head_verify_draft(g_h, g_W, K, g_tok, g_par, gamma, cfg.max_depth, branching=cfg.draft_branching)
+    torch.cuda.synchronize()
+    for k in ("n_accept", "last", "bonus", "path", "out_tokens"):
+        assert torch.equal(out[k], ver[k]), k
+    assert torch.equal(out["next_tok"], nxt) and torch.equal(out["next_parent"], npar)
+    assert np.array_equal(out["n_accept"].cpu().numpy(), planted) and planted.max() >= 1
+    # oracle on the rows the tail read: B*T main rows (arg-max) and B*gamma stream rows (top-K)
+    last = out["last"].cpu().numpy()
+    h32, w32 = to_np_f32(inp["hidden"]), to_np_f32(inp["W"])
+    main_rows = np.array([b * R + i for b in range(B) for i in range(T)])
+    stream_rows = np.array([b * R + T + last[b] * gamma + j for b in range(B) for j in range(gamma)])
+    o_main, o_mval, z_main = oracle.lm_head_topk(h32[main_rows], w32, 1, want_logits=True)
+    tau = 1e-4 * np.abs(z_main).max()
+    g_main = out["main_argmax"].cpu().numpy().reshape(-1)
+    for n in np.nonzero(g_main != o_main[:, 0])[0]:
+        assert abs(z_main[n, g_main[n]] - o_mval[n, 0]) <= tau
+    o_top, o_tval, z_s = oracle.lm_head_topk(h32[stream_rows], w32, K, want_logits=True)
+    tp, tr, td = oracle.full_tree_template(cfg.draft_branching)
+    g_next = out["next_tok"].cpu().numpy()
+    for b in range(B):
+        assert g_next[b, 0] == out["bonus"][b].item()
+        for i in range(1, len(tp)):
+            j, want = td[i] - 1, o_top[b * gamma + td[i] - 1, tr[i]]
+            if g_next[b, i] != want:      # a near tie inside tau may swap two ranks
+                assert abs(z_s[b * gamma + j, g_next[b, i]] - o_tval[b * gamma + j, tr[i]]) <= tau
