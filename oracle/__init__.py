@@ -149,6 +149,20 @@ def stream_insert(M, P, fM=None):
     return X
 
 
+def value_rotate(v, T: int, gamma: int, eps: float):
+    """Value-rotation ablation of the appendix.  v [B,R,Hkv,D] (only its main rows are read) -> float64 copy
+    whose stream rows hold the node's main-row value times e^{i eps n}, features paired (2m, 2m+1)."""
+    v = _f32(v)
+    B, R, Hkv, D = v.shape
+    assert R == T * (1 + gamma) and D % 2 == 0
+    out = np.zeros(v.shape, np.float64)
+    lib = _load()
+    lib.ora_value_rotate.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                     ctypes.c_int, ctypes.c_double, ctypes.c_void_p]
+    lib.ora_value_rotate(_p(v), B, T, gamma, Hkv, D, float(eps), _p(out))
+    return out
+
+
 def tree_verify(tok, parent, main_argmax, max_depth: int):
     """a4.  tok, parent, main_argmax [B,T] -> dict(n_accept, last, bonus, path, out_tokens)."""
     tok, parent, a = _i32(tok), _i32(parent), _i32(main_argmax)

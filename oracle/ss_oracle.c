@@ -283,6 +283,36 @@ void ora_stream_insert(const float* M, const float* fM, const float* P, int B, i
     }
 }
 
+/*
+ * Value rotation (appendix ablation "Value Rotation"): instead of stream
+ * embeddings, the value projection of stream n of a node is the main stream's
+ * value projection of that node times e^{i eps n}, n = 1..gamma.  The paper does
+ * not say how real features form complex numbers; the reading used here is that
+ * of rotary embeddings in the interleaved convention: features (2m, 2m+1) of a
+ * head are (Re, Im) of one complex number, and all pairs turn by the same angle
+ * (the equation has no per-pair frequency).  v [B,R,Hkv,D] in the row order
+ * stated above: main rows are read, stream rows are written; out is the whole
+ * tensor in double (main rows copied).
+ */
+void ora_value_rotate(const float* v, int B, int T, int gamma, int Hkv, int D, double eps, double* out) {
+  const int R = T * (1 + gamma);
+  const size_t row = (size_t)Hkv * D;
+  for (int b = 0; b < B; b++)
+    for (int i = 0; i < T; i++) {
+      const float* main_row = v + ((size_t)b * R + i) * row;
+      for (size_t e = 0; e < row; e++) out[((size_t)b * R + i) * row + e] = (double)main_row[e];
+      for (int n = 1; n <= gamma; n++) {
+        double* dst = out + ((size_t)b * R + T + (size_t)i * gamma + (n - 1)) * row;
+        const double c = cos(eps * n), sn = sin(eps * n);
+        for (size_t m = 0; m < row / 2; m++) {
+          const double re = (double)main_row[2 * m], im = (double)main_row[2 * m + 1];
+          dst[2 * m] = re * c - im * sn;      /* (re + i im)(c + i sn) */
+          dst[2 * m + 1] = re * sn + im * c;
+        }
+      }
+    }
+}
+
 /* ------------------------------------------------------------------ verify */
 
 /*
