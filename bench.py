@@ -158,6 +158,11 @@ def time_rows_after_hot_path(api, synth, torch, cfg, dev, N, it, lm, lm_ws, tok,
     api.ss_stream_insert(hm, P_emb, X=X_rows)
     us_ins = timed(lambda i: api.ss_stream_insert(hm, P_emb, X=X_rows), it, torch)
     extra["stream_insert_us"] = round(us_ins, 2)
+    # The appendix's value-rotation variant on one layer's value block [B,R,Hkv,D], in place
+    v_blk = X_rows.view(cfg.B, cfg.R, cfg.Hkv, dm // cfg.Hkv) if dm % cfg.Hkv == 0 and (dm // cfg.Hkv) % 2 == 0 else None
+    if v_blk is not None:
+        api.ss_value_rotate(v_blk, cfg.T, cfg.gamma, 1e-4)
+        extra["value_rotate_us"] = round(timed(lambda i: api.ss_value_rotate(v_blk, cfg.T, cfg.gamma, 1e-4), it, torch), 2)
     extra["prune_layer"] = {"us": round(us_prune, 2), "logsumexp_us": round(us_lse, 2),
                             "logsumexp_hbm_gbps": round(cfg.vocab * dm * 2 / (us_lse * 1e-6) / 1e9, 1)}
     del w_copies

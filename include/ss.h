@@ -230,6 +230,26 @@ int ss_stream_insert(const void* M, const void* fM, const void* P, int B, int T,
                      int dtype, void* X, void* stream);
 
 /*
+ * Value rotation, the appendix's alternative to stream embeddings (ablation
+ * "Value Rotation"): streams start from the main-stream state (ss_stream_insert
+ * with P = 0) and, in every multi-stream layer, the value projection of stream n
+ * of a node is the main stream's value projection of that node times
+ * e^{i*eps*n}, n = 1..gamma.  Features (2m, 2m+1) of a head are taken as (Re, Im)
+ * of one complex number and every pair turns by the same angle eps*n:
+ *    v[b, T + i*gamma + n-1, h, 2m  ] = re*cos(eps n) - im*sin(eps n)
+ *    v[b, T + i*gamma + n-1, h, 2m+1] = re*sin(eps n) + im*cos(eps n)
+ *  with (re, im) = v[b, i, h, 2m], v[b, i, h, 2m+1] (main row of node i).
+ *  v_new [B,R,Hkv,D] of type dtype, the value block of the step handed to
+ *  ss_msa_attention, updated IN PLACE: main rows are read, stream rows written
+ *  (what they held is ignored).  eps: 0 <= eps <= pi/(2N) in the paper, any
+ *  value accepted; cos and sin are taken in double on the host.  Products in
+ *  fp32, a bf16 result rounded once.  D must be even.  B == 0 or gamma == 0 is
+ *  a no-op.
+ */
+int ss_value_rotate(void* v_new, int B, int T, int gamma, int Hkv, int D, float eps, int dtype,
+                    void* stream);
+
+/*
  * n2. Parallel tree pruning (Sec. 3.2.3; Appendix A.1 and its generation-step
  * figure).  Early-exit logits of node i are zt_i = H(o(M_i)): the LM head H = W
  * applied to the main-stream hidden state after the low-rank map o (two

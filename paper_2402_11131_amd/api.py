@@ -28,7 +28,7 @@ SS_MAX_T, SS_MAX_GAMMA, SS_MAX_K = 64, 8, 8
 EXPORTS = (
     "ss_version", "ss_last_error", "ss_check_tree_host", "ss_build_mask", "ss_msa_workspace_bytes",
     "ss_msa_attention", "ss_msa_plan", "ss_msa_set_split_keys", "ss_msa_set_merge_in_kernel", "ss_lm_head_workspace_bytes", "ss_lm_head_argmax_topk", "ss_lm_head_verify_draft",
-    "ss_tree_verify", "ss_tree_draft", "ss_full_tree_template_host", "ss_kv_commit", "ss_linear_rows", "ss_stream_insert",
+    "ss_tree_verify", "ss_tree_draft", "ss_full_tree_template_host", "ss_kv_commit", "ss_linear_rows", "ss_stream_insert", "ss_value_rotate",
     "ss_lm_head_logsumexp", "ss_transition_probs", "ss_tree_prune",
 )
 
@@ -74,6 +74,7 @@ def load_library() -> ctypes.CDLL:
     lib.ss_kv_commit.argtypes = [vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp, vp]
     lib.ss_linear_rows.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp]
     lib.ss_stream_insert.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp, vp]
+    lib.ss_value_rotate.argtypes = [vp, i32, i32, i32, i32, i32, c.c_float, i32, vp]
     lib.ss_lm_head_logsumexp.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, sz, vp]
     lib.ss_transition_probs.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp]
     lib.ss_tree_prune.argtypes = [vp, vp, vp, c.c_float, i32, i32, vp, vp, vp, vp, vp, vp]
@@ -413,6 +414,18 @@ def ss_stream_insert(M: torch.Tensor, P: torch.Tensor, fM: Optional[torch.Tensor
     _check(lib.ss_stream_insert(_dev(M, dt, "M"), None if fM is None else _dev(fM, dt, "fM"), _dev(P, dt, "P"),
                                 B, T, gamma, d, code, _dev(X, dt, "X"), _stream()))
     return X
+
+
+def ss_value_rotate(v_new: torch.Tensor, T: int, gamma: int, eps: float) -> torch.Tensor:
+    """Value rotation (appendix ablation).  v_new [B,R,Hkv,D], IN PLACE: the stream rows become the node's main-row
+    value times e^{i eps n}, features paired (2m, 2m+1).  Returns v_new."""
+    lib = load_library()
+    B, R, Hkv, D = v_new.shape
+    if R != T * (1 + gamma):
+        raise ValueError("v_new has %d rows per sequence, expected T*(1+gamma) = %d" % (R, T * (1 + gamma)))
+    _check(lib.ss_value_rotate(_dev(v_new, v_new.dtype, "v_new"), B, T, gamma, Hkv, D, float(eps), _dtype_code(v_new),
+                               _stream()))
+    return v_new
 
 
 def ss_lm_head_logsumexp(hidden: torch.Tensor, W: torch.Tensor, lse: Optional[torch.Tensor] = None,

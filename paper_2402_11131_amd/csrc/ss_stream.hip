@@ -1,6 +1,8 @@
 // n4: stream insertion (Eq. 3).  The rows of a step enter the first multi-stream layer as: main row of
 // node i = M_i, stream j of node i = f(M_i) + P_j.  Elementwise and tiny (B*R*d elements): one workgroup
 // per output row, 16-byte pieces where the row length allows.  Sums are formed in fp32 and rounded once.
+#include <math.h>
+
 #include "ss_common.h"
 
 namespace ss {
@@ -58,7 +60,68 @@ __global__ __launch_bounds__(256) void stream_insert_kernel(StreamArgs a) {
   }
 }
 
+// Value rotation (appendix ablation): stream n of node i takes the node's main-row value times e^{i eps n}.
+// Features (2m, 2m+1) are (Re, Im); cos and sin of eps*n come from the host in a table (gamma <= 8 angles).
+// One workgroup per stream row; a thread turns one pair at a time (bf16: one 32-bit word).
+struct RotateArgs {
+  void* v;  // [B,R,Hkv,D]: main rows read, stream rows written
+  int T, gamma, row;  // row = Hkv*D elements
+  float c[SS_MAX_GAMMA], s[SS_MAX_GAMMA];
+};
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void value_rotate_kernel(RotateArgs a) {
+  const int R = a.T * (1 + a.gamma);
+  const int per_seq = a.T * a.gamma;
+  const int b = blockIdx.x / per_seq, k = blockIdx.x % per_seq;
+  const int node = k / a.gamma, n = k % a.gamma;  // stream n+1
+  const float c = a.c[n], sn = a.s[n];
+  const size_t src = ((size_t)b * R + node) * a.row, dst = ((size_t)b * R + a.T + k) * a.row;
+  for (int m = threadIdx.x; m < a.row / 2; m += 256) {
+    float re, im;
+    if constexpr (BF16) {
+      const uint32_t w = ((const uint32_t*)((const uint16_t*)a.v + src))[m];
+      re = bf16_bits_to_f32(w & 0xffffu);
+      im = bf16_bits_to_f32(w >> 16);
+    } else {
+      const float2 w = ((const float2*)((const float*)a.v + src))[m];
+      re = w.x;
+      im = w.y;
+    }
+    const float o_re = __builtin_fmaf(re, c, -(im * sn)), o_im = __builtin_fmaf(re, sn, im * c);
+    if constexpr (BF16) ((uint32_t*)((uint16_t*)a.v + dst))[m] = pack_bf16x2(o_re, o_im);
+    else ((float2*)((float*)a.v + dst))[m] = make_float2(o_re, o_im);
+  }
+}
+
 }  // namespace ss
+
+extern "C" int ss_value_rotate(void* v_new, int B, int T, int gamma, int Hkv, int D, float eps, int dtype,
+                               void* stream) {
+  using namespace ss;
+  clear_error();
+  const char* fn = "ss_value_rotate";
+  SS_REQUIRE(B >= 0 && Hkv >= 1 && D >= 2 && D % 2 == 0, SS_ERR_INVALID_ARG, "%s: B=%d Hkv=%d D=%d (D must be even)", fn,
+             B, Hkv, D);
+  SS_REQUIRE(T >= 1 && T <= SS_MAX_T, SS_ERR_UNSUPPORTED, "%s: T=%d outside [1,%d]", fn, T, SS_MAX_T);
+  SS_REQUIRE(gamma >= 0 && gamma <= SS_MAX_GAMMA, SS_ERR_UNSUPPORTED, "%s: gamma=%d outside [0,%d]", fn, gamma,
+             SS_MAX_GAMMA);
+  SS_REQUIRE(dtype == SS_F32 || dtype == SS_BF16, SS_ERR_UNSUPPORTED, "%s: dtype %d", fn, dtype);
+  SS_REQUIRE(B == 0 || gamma == 0 || v_new, SS_ERR_INVALID_ARG, "%s: NULL tensor argument", fn);
+  SS_REQUIRE((long)Hkv * D <= 0x7fffffffL && (long)B * T * gamma <= 0x7fffffffL, SS_ERR_UNSUPPORTED, "%s: too large", fn);
+  SS_REQUIRE(((uintptr_t)v_new & (dtype == SS_BF16 ? 3 : 7)) == 0, SS_ERR_INVALID_ARG, "%s: v_new is not aligned to a pair", fn);
+  if (B == 0 || gamma == 0) return SS_OK;
+  RotateArgs a;
+  a.v = v_new; a.T = T; a.gamma = gamma; a.row = Hkv * D;
+  for (int n = 0; n < SS_MAX_GAMMA; ++n) {
+    a.c[n] = (float)cos((double)eps * (n + 1));
+    a.s[n] = (float)sin((double)eps * (n + 1));
+  }
+  const dim3 grid((unsigned)(B * T * gamma));
+  if (dtype == SS_F32) hipLaunchKernelGGL(value_rotate_kernel<false>, grid, dim3(256), 0, (hipStream_t)stream, a);
+  else hipLaunchKernelGGL(value_rotate_kernel<true>, grid, dim3(256), 0, (hipStream_t)stream, a);
+  return check_launch(fn);
+}
 
 extern "C" int ss_stream_insert(const void* M, const void* fM, const void* P, int B, int T, int gamma, int d,
                                 int dtype, void* X, void* stream) {

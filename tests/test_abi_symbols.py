@@ -91,6 +91,11 @@ def test_argument_validation_of_the_rows_around_the_hot_path():
     assert lib.ss_stream_insert(one, None, one, 1, 4, 9, 64, 1, one, None) == 2   # gamma above the limit
     assert lib.ss_stream_insert(one, None, None, 1, 4, 2, 64, 1, one, None) == 1  # P missing with gamma > 0
     assert lib.ss_stream_insert(None, None, None, 0, 4, 2, 64, 1, None, None) == 0
+    assert lib.ss_value_rotate(one, 1, 4, 2, 2, 63, f(0.1), 1, None) == 1         # odd head dim
+    assert lib.ss_value_rotate(one, 1, 65, 2, 2, 64, f(0.1), 1, None) == 2
+    assert lib.ss_value_rotate(None, 1, 4, 2, 2, 64, f(0.1), 1, None) == 1
+    assert lib.ss_value_rotate(ctypes.c_void_p(6), 1, 4, 2, 2, 64, f(0.1), 1, None) == 1  # not aligned to a pair
+    assert lib.ss_value_rotate(None, 1, 4, 0, 2, 64, f(0.1), 1, None) == 0          # no streams: no-op
     assert lib.ss_lm_head_logsumexp(one, one, 4, 100, 50, 1, one, one, 1 << 20, None) == 2
     assert lib.ss_lm_head_logsumexp(one, one, 4, 128, 50, 1, one, one, 8, None) == 4  # workspace too small
     assert b"workspace" in lib.ss_last_error()
