@@ -349,6 +349,14 @@ def main():
                     "unit": "GB/s", "frac": round(gbps / HBM_PEAK_GBPS, 4),
                     "traffic": MSA_TRAFFIC_BYTES.get(args.workload), "algorithmic_bytes": b_msa,
                     "mfma_tflops": round(tflops, 1)}
+    # The read rate this GPU reaches with plain 16-byte loads over 1 GiB (four times the last-level cache), next to
+    # the published peak the fraction is taken against
+    probe_buf = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_()
+    probe_sink = torch.zeros(1, dtype=torch.int32, device=dev)
+    roofline["measured_read_ceiling_gbps"] = {
+        "plain": round((1 << 30) / (timed(lambda i: api.ss_probe_hbm_read(probe_buf, False, probe_sink), 20, torch) * 1e-6) / 1e9, 1),
+        "streaming": round((1 << 30) / (timed(lambda i: api.ss_probe_hbm_read(probe_buf, True, probe_sink), 20, torch) * 1e-6) / 1e9, 1)}
+    del probe_buf
     if n_kernels == 1 and n_splits > 1:
         # for comparison: the same kernel when it leaves the split merge to a second kernel
         roofline["without_split_merge"] = {"us": round(us_msa_partials, 2),

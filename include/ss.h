@@ -87,6 +87,17 @@ int ss_version(void);
 const char* ss_last_error(void);
 
 /*
+ * Measurement aid (no part of the method): one pass of plain 16-byte loads
+ * over DEVICE memory at `buf` (16-byte aligned), `bytes` rounded down to a
+ * multiple of 32 MiB (at least that much is required), with the streaming
+ * (non-temporal) hint if `streaming` is non-zero; nothing is written (`sink`,
+ * 4 bytes of device memory, only keeps the loads alive).
+ * Timed over a buffer larger than the last-level cache it gives the read rate
+ * this GPU reaches, the practical ceiling next to the published HBM peak.
+ */
+int ss_probe_hbm_read(const void* buf, size_t bytes, int streaming, void* sink, void* stream);
+
+/*
  * Host-side check of B trees: parent[b*T+0] == -1, 0 <= parent[b*T+i] < i, and
  * (if max_depth >= 0) depth <= max_depth.  `parent` is HOST memory.
  * Returns SS_OK or SS_ERR_BAD_TREE (message names the first offending entry).
