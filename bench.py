@@ -391,11 +391,16 @@ def main():
                      "kv_commit_all_layers_us": round(us_commit, 2)})
         f_lm = 2.0 * N * cfg.vocab * cfg.d_model
         tf = f_lm / (us_lm * 1e-6) / 1e12
+        mfma_sink = torch.zeros(1, dtype=torch.float32, device=dev)
+        mfma_flops = api.ss_probe_mfma_bf16(1000, mfma_sink)
+        us_mfma = timed(lambda i: api.ss_probe_mfma_bf16(1000, mfma_sink), 20, torch)
         extra["roofline_lm_head"] = {"kernel": "lm_head_bf16_kernel + lm_head_reduce_kernel", "bound": "mfma", "achieved": round(tf, 1),
                                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                                      "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
                                      "hbm_gbps": round((cfg.vocab * cfg.d_model * 2 + N * cfg.d_model * 2) /
-                                                       (us_lm * 1e-6) / 1e9, 1)}
+                                                       (us_lm * 1e-6) / 1e9, 1),
+                                     # register-only matrix-core work on the whole chip, at the clock it is granted
+                                     "measured_mfma_ceiling_tflops": round(mfma_flops / (us_mfma * 1e-6) / 1e12, 1)}
         extra["accepted_per_sequence"] = state["ver"]["n_accept"].tolist()
         if args.workload == "c4":
             try:

@@ -98,6 +98,17 @@ const char* ss_last_error(void);
 int ss_probe_hbm_read(const void* buf, size_t bytes, int streaming, void* sink, void* stream);
 
 /*
+ * Measurement aid (no part of the method): 2048 wavefronts (two per SIMD of a
+ * 256-unit GPU) each issue 20*iters bf16 matrix-core instructions of shape
+ * 32x32x16 on registers only, five independent accumulator tiles per wave;
+ * nothing is loaded or stored (`sink`, 4 bytes of device memory, only keeps
+ * the results alive).  *flops (HOST, may be NULL) receives the floating-point
+ * operations of the launch.  Timed, it gives the matrix-core rate the GPU
+ * sustains at the clock it grants, next to the published peak.
+ */
+int ss_probe_mfma_bf16(int iters, double* flops, void* sink, void* stream);
+
+/*
  * Host-side check of B trees: parent[b*T+0] == -1, 0 <= parent[b*T+i] < i, and
  * (if max_depth >= 0) depth <= max_depth.  `parent` is HOST memory.
  * Returns SS_OK or SS_ERR_BAD_TREE (message names the first offending entry).

@@ -26,7 +26,7 @@ SS_MSA_MERGE_ONLY = 4
 SS_MAX_T, SS_MAX_GAMMA, SS_MAX_K = 64, 8, 8
 
 EXPORTS = (
-    "ss_version", "ss_last_error", "ss_probe_hbm_read", "ss_check_tree_host", "ss_build_mask", "ss_msa_workspace_bytes",
+    "ss_version", "ss_last_error", "ss_probe_hbm_read", "ss_probe_mfma_bf16", "ss_check_tree_host", "ss_build_mask", "ss_msa_workspace_bytes",
     "ss_msa_attention", "ss_msa_plan", "ss_msa_set_split_keys", "ss_msa_set_merge_in_kernel", "ss_lm_head_workspace_bytes", "ss_lm_head_argmax_topk", "ss_lm_head_verify_draft",
     "ss_tree_verify", "ss_tree_draft", "ss_full_tree_template_host", "ss_kv_commit", "ss_linear_rows", "ss_stream_insert", "ss_value_rotate",
     "ss_lm_head_logsumexp", "ss_transition_probs", "ss_tree_prune",
@@ -57,6 +57,7 @@ def load_library() -> ctypes.CDLL:
     lib.ss_last_error.restype = c.c_char_p
     lib.ss_check_tree_host.argtypes = [vp, i32, i32, i32]
     lib.ss_probe_hbm_read.argtypes = [vp, sz, i32, vp, vp]
+    lib.ss_probe_mfma_bf16.argtypes = [i32, c.POINTER(c.c_double), vp, vp]
     lib.ss_build_mask.argtypes = [vp, i32, i32, i32, u32, vp, vp, vp, vp]
     lib.ss_msa_workspace_bytes.argtypes = [i32] * 8
     lib.ss_msa_workspace_bytes.restype = sz
@@ -112,6 +113,13 @@ def ss_probe_hbm_read(buf: torch.Tensor, streaming: bool, sink: torch.Tensor) ->
     """Measurement aid: one pass of 16-byte loads over `buf` (a contiguous GPU tensor), nothing written."""
     _check(load_library().ss_probe_hbm_read(buf.data_ptr(), buf.numel() * buf.element_size(), 1 if streaming else 0,
                                             sink.data_ptr(), _stream()))
+
+
+def ss_probe_mfma_bf16(iters: int, sink: torch.Tensor) -> float:
+    """Measurement aid: register-only bf16 matrix-core work on the whole chip; returns the launch's FLOPs."""
+    fl = ctypes.c_double(0.0)
+    _check(load_library().ss_probe_mfma_bf16(int(iters), ctypes.byref(fl), sink.data_ptr(), _stream()))
+    return fl.value
 
 
 def ss_version() -> int:

@@ -40,11 +40,59 @@ __global__ __launch_bounds__(256) void hbm_read_probe_kernel(const uintx4* __res
   if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x9e3779b9u && acc[0] == 0x7f4a7c15u) sink[0] = acc[1];
 }
 
+// Measurement aid: matrix-core instructions on registers only, 2048 waves (two per SIMD), five independent
+// accumulator tiles per wave as in the LM-head kernel: what the chip sustains when nothing has to be loaded.
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 probe_bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float probe_floatx16;
+__global__ __launch_bounds__(256) void mfma_probe_kernel(int iters, float* __restrict__ sink) {
+  probe_floatx16 acc[5];
+#pragma unroll
+  for (int i = 0; i < 5; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+  // operands with random bits (values in (-2, 2)), different for every instruction of a round: constant or
+  // tiny operands would toggle few wires and flatter the clock
+  probe_bf16x8 a[4], b[5];
+  uint32_t h = (blockIdx.x * 256u + threadIdx.x) * 2654435761u + 12345u;
+  auto next = [&]() {
+    h = h * 1664525u + 1013904223u;
+    const uint32_t bits = (h >> 16) & 0xbfffu;                       // sign and mantissa free, exponent below 2^1
+    return __builtin_bit_cast(__bf16, (uint16_t)((bits & 0x807fu) | (((bits >> 7) & 0x7u) + 124u) << 7));
+  };
+#pragma unroll
+  for (int r = 0; r < 4; ++r)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) a[r][e] = next();
+#pragma unroll
+  for (int i = 0; i < 5; ++i)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) b[i][e] = next();
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+      for (int i = 0; i < 5; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[r], b[i], acc[i], 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 5; ++i) s += acc[i][0] + acc[i][15];
+  if (s == 12345.678f) sink[0] = s;
+}
+
 }  // namespace ss
 
 extern "C" {
 
 int ss_version(void) { return 100; }
+
+int ss_probe_mfma_bf16(int iters, double* flops, void* sink, void* stream) {
+  ss::clear_error();
+  SS_REQUIRE(iters >= 1 && iters <= (1 << 20) && sink != nullptr, SS_ERR_INVALID_ARG,
+             "ss_probe_mfma_bf16: iters=%d outside [1, 2^20] or no sink", iters);
+  hipLaunchKernelGGL(ss::mfma_probe_kernel, dim3(512), dim3(256), 0, (hipStream_t)stream, iters, (float*)sink);
+  if (flops) *flops = 2048.0 * iters * 20.0 * (2.0 * 32 * 32 * 16);
+  return ss::check_launch("ss_probe_mfma_bf16");
+}
 
 int ss_probe_hbm_read(const void* buf, size_t bytes, int streaming, void* sink, void* stream) {
   ss::clear_error();

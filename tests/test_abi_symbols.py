@@ -96,6 +96,9 @@ def test_argument_validation_of_the_rows_around_the_hot_path():
     assert lib.ss_value_rotate(None, 1, 4, 2, 2, 64, f(0.1), 1, None) == 1
     assert lib.ss_value_rotate(ctypes.c_void_p(6), 1, 4, 2, 2, 64, f(0.1), 1, None) == 1  # not aligned to a pair
     assert lib.ss_value_rotate(None, 1, 4, 0, 2, 64, f(0.1), 1, None) == 0          # no streams: no-op
+    assert lib.ss_probe_hbm_read(one, 1 << 20, 1, one, None) == 1                  # less than one round of all waves
+    assert lib.ss_probe_hbm_read(ctypes.c_void_p(8), 1 << 30, 0, one, None) == 1    # not 16-byte aligned
+    assert lib.ss_probe_mfma_bf16(0, None, one, None) == 1
     assert lib.ss_lm_head_logsumexp(one, one, 4, 100, 50, 1, one, one, 1 << 20, None) == 2
     assert lib.ss_lm_head_logsumexp(one, one, 4, 128, 50, 1, one, one, 8, None) == 4  # workspace too small
     assert b"workspace" in lib.ss_last_error()
