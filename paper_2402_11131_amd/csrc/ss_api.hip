@@ -50,13 +50,14 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(int iters, float* __res
   for (int i = 0; i < 5; ++i)
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
-  // operands with random bits (values in (-2, 2)), different for every instruction of a round: constant or
+  // operands with random bits (random sign and mantissa, magnitudes in [1/8, 32)), different for every
+  // instruction of a round: constant or
   // tiny operands would toggle few wires and flatter the clock
   probe_bf16x8 a[4], b[5];
   uint32_t h = (blockIdx.x * 256u + threadIdx.x) * 2654435761u + 12345u;
   auto next = [&]() {
     h = h * 1664525u + 1013904223u;
-    const uint32_t bits = (h >> 16) & 0xbfffu;                       // sign and mantissa free, exponent below 2^1
+    const uint32_t bits = h >> 16;
     return __builtin_bit_cast(__bf16, (uint16_t)((bits & 0x807fu) | (((bits >> 7) & 0x7u) + 124u) << 7));
   };
 #pragma unroll
