@@ -201,7 +201,9 @@ int ss_msa_set_split_keys(int split_keys);
  * bit for bit and does not depend on which split finishes first.  The splits
  * find each other through arrival counters that live in the library (one region
  * of 32 per call, taken in turn): at most 32 calls may be in flight on one GPU
- * at the same time with this on.  Returns the previous setting.
+ * at the same time with this on.  A call captured into a HIP graph keeps the
+ * region it was given at capture; replays of one graph follow each other, so
+ * they do not meet themselves.  Returns the previous setting.
  */
 int ss_msa_set_merge_in_kernel(int on);
 
