@@ -19,6 +19,7 @@ struct LmArgs {
   int N, d, V, K;
   int n_tiles;         // vocabulary tiles
   int n_chunks;        // row chunks (bf16 kernel)
+  int k_stagger;       // feature blocks between the starting blocks of neighbouring vocabulary tiles (bf16 kernel)
   uint64_t* cand_key;  // [N, n_tiles, K] candidates as ordered keys
   int32_t* idx;        // [N,K]
   float* val;          // [N,K]
@@ -375,6 +376,12 @@ __global__ __launch_bounds__(64 * NW, 1) void lm_head_bf16_kernel(LmArgs a) {
   const int v0 = tile * TI + 32 * w;
   const int row0 = (turn % a.n_chunks) * ROWS;
   const int d = a.d, n_k = d / 64;
+  // Feature blocks are walked from a start that differs from tile to tile (by one block between neighbours,
+  // when the host asks for it) and wrap around: workgroups that all read the same 128-byte column of W's rows
+  // at the same time meet in few memory channels (a read-only probe of this pattern: 5.0 TB/s in step, 6.9 TB/s
+  // with odd distances between the starts, less again with even ones).  Only the order of the sum changes.
+  const int k_start = (tile * a.k_stagger) % n_k;
+  auto blk = [&](int J) { const int p = J + k_start; return p >= n_k ? p - n_k : p; };
 
   // load slots of 8 rows x 128 bytes; lane -> (row lane/8 of the slot, chunk position lane%8, which
   // receives chunk (lane%8) ^ swizzle(row)).  hidden: wave w takes slots w, w+NW, ...; W: its own rows.
@@ -417,7 +424,7 @@ __global__ __launch_bounds__(64 * NW, 1) void lm_head_bf16_kernel(LmArgs a) {
   };
   constexpr int WAIT_ALL = 0x0F70;                                     // s_waitcnt vmcnt(0)
 #pragma unroll
-  for (int j = 0; j < NBUF - 1; ++j) load_block(min(j, n_k - 1), j);
+  for (int j = 0; j < NBUF - 1; ++j) load_block(blk(min(j, n_k - 1)), j);
   __builtin_amdgcn_s_waitcnt(WAIT_ALL);
   __syncthreads();
 
@@ -442,7 +449,7 @@ __global__ __launch_bounds__(64 * NW, 1) void lm_head_bf16_kernel(LmArgs a) {
     const int buf_fill = buf == 0 ? NBUF - 1 : buf - 1;
     const unsigned char* cur = hbuf + buf * BB;
     const unsigned char* nxt = hbuf + buf_next * BB;
-    const int Jn = min(J + NBUF - 1, n_k - 1);
+    const int Jn = blk(min(J + NBUF - 1, n_k - 1));
     const unsigned char* h_base = (const unsigned char*)a.hidden + (size_t)Jn * 128;
     const unsigned char* w_base = (const unsigned char*)a.W + (size_t)Jn * 128;
     const uint32_t dst = lds0 + buf_fill * BB;
@@ -633,7 +640,13 @@ static int launch_lm_bf16_r(int KT, hipStream_t st, const LmArgs& a) {
 }
 // Rows go to the workgroups in n_chunks chunks of 32*NRT rows; a.n_chunks and a.n_tiles must be set
 // for the flavour (tiles of 256 ids if f.wide).
-static int launch_lm_bf16(LmFlavour f, int KT, hipStream_t st, const LmArgs& a) {
+static int launch_lm_bf16(LmFlavour f, int KT, hipStream_t st, const LmArgs& args) {
+  // Staggered starts when every part of W is wanted by one workgroup only (one row chunk): those launches are
+  // bound by the stream of W (16..160 rows over a 262 MB W: 57..73 us in step, 45..66 us staggered).  With several
+  // row chunks the chunks of a tile walk together either way and the gain is within the noise.
+  LmArgs a = args;
+  a.k_stagger = a.n_chunks == 1 ? 1 : 0;
+  if (const char* e = getenv("SS_LM_STAGGER")) a.k_stagger = atoi(e) < 0 ? 0 : (atoi(e) > 1024 ? 1024 : atoi(e));  // tuning aid
   if (f.wide) {
     switch (f.nrt) {
       case 1: return launch_lm_bf16_r<1, 1>(KT, st, a);
@@ -735,6 +748,7 @@ static int lm_candidates(const char* fn, const void* hidden, const void* W, int 
   a.hidden = hidden; a.W = W; a.N = N; a.d = d; a.V = V; a.K = K;
   a.n_tiles = lm_tiles(V, dtype);
   a.n_chunks = 1;
+  a.k_stagger = 0;
   char* ws = (char*)(((uintptr_t)workspace + 255) & ~(uintptr_t)255);
   a.cand_key = (uint64_t*)ws;
   a.idx = nullptr; a.val = nullptr;
@@ -835,6 +849,7 @@ int ss_lm_head_logsumexp(const void* hidden, const void* W, int N, int d, int V,
   a.hidden = hidden; a.W = W; a.N = N; a.d = d; a.V = V; a.K = 0;
   a.n_tiles = lm_tiles(V, dtype);
   a.n_chunks = 1;
+  a.k_stagger = 0;
   a.cand_key = (uint64_t*)(((uintptr_t)workspace + 255) & ~(uintptr_t)255);
   a.idx = nullptr; a.val = nullptr; a.y = nullptr;
   a.lse = lse;
@@ -866,6 +881,7 @@ int ss_linear_rows(const void* x, const void* W, int N, int d, int V, int dtype,
   a.hidden = x; a.W = W; a.N = N; a.d = d; a.V = V; a.K = 0;
   a.n_tiles = lm_tiles(V, dtype);
   a.n_chunks = 1;
+  a.k_stagger = 0;
   a.cand_key = nullptr; a.idx = nullptr; a.val = nullptr; a.lse = nullptr;
   a.y = y;
   hipStream_t st = (hipStream_t)stream;

@@ -35,6 +35,7 @@ def _clean_env():
     yield
     os.environ.pop("SS_LM_FLAVOUR", None)
     os.environ.pop("SS_LINEAR_FLAVOUR", None)
+    os.environ.pop("SS_LM_STAGGER", None)
 
 
 @pytest.mark.parametrize("flavour", FLAVOURS)
@@ -84,3 +85,24 @@ def test_top_1_and_top_8(problem, flavour, K):
     assert (np.abs(z_at - o_val)[differs] <= tau).all() and differs.sum() <= 2
     for n in range(idx.shape[0]):
         assert len(set(idx[n].tolist())) == K
+
+
+@pytest.mark.parametrize("stagger", [1, 3, 7])
+@pytest.mark.parametrize("flavour", ["1", "3", "6", "2w", "5w"])
+def test_staggered_starting_blocks(problem, flavour, stagger):
+    # every vocabulary tile walks the 5 feature blocks from its own start and wraps around (the host does this only
+    # for launches with one row chunk; here it is forced for all shapes): same results within the same bounds
+    x, W, ref = problem
+    os.environ["SS_LM_FLAVOUR"] = os.environ["SS_LINEAR_FLAVOUR"] = flavour
+    os.environ["SS_LM_STAGGER"] = str(stagger)
+    y = to_np_f32(api.ss_linear_rows(x, W).cpu()).astype(np.float64)
+    assert (np.abs(y - ref["z"]) <= 2.0 ** -8 * np.abs(ref["z"]) + 1e-5 * ref["S"]).all()
+    lse = api.ss_lm_head_logsumexp(x, W).cpu().numpy()
+    assert (np.abs(lse - ref["lse"]) <= 2e-3 * np.maximum(1.0, np.abs(ref["lse"]))).all()
+    idx, val = api.ss_lm_head_argmax_topk(x, W, 4)
+    idx, val = idx.cpu().numpy(), val.cpu().numpy()
+    tau = 1e-4 * np.abs(ref["z"]).max()
+    z_at = np.take_along_axis(ref["z"], idx.astype(np.int64), axis=1)
+    assert (np.abs(val - z_at) <= tau).all()
+    differs = idx != ref["idx"]
+    assert (np.abs(z_at - ref["val"])[differs] <= tau).all() and differs.sum() <= 1
