@@ -36,10 +36,10 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, vendor figure
 # HBM traffic of one launch of the MSA kernel, from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE; KiB
 # per dispatch), each scaled by what the same counter reads for the 256 MiB device copy of --calibrate-copy
 # (FETCH_SIZE reads half of the bytes the copy fetches: factor 2.0; WRITE_SIZE factor 1.0).  c4, the launch
-# the steps make (two splits merged inside the kernel): 139214 KiB x 2.0 fetched (the cache once + one split's
-# partial rows read back) + 15677 KiB written (both splits' fp32 partials + the output).  Summaries are under
+# the steps make (two splits merged inside the kernel): 139168 KiB x 2.0 fetched (the cache once + one split's
+# partial rows read back) + 15608 KiB written (both splits' fp32 partials + the output).  Summaries are under
 # profiles/.
-MSA_TRAFFIC_BYTES = {"c4": int((139214.0 * 2.0 + 15677.0) * 1024), "c2": None, "c3": None, "c5": None}
+MSA_TRAFFIC_BYTES = {"c4": int((139168.0 * 2.0 + 15608.0) * 1024), "c2": None, "c3": None, "c5": None}
 
 
 def msa_bytes(cfg, seq_lens):
