@@ -53,7 +53,8 @@ def test_fp32_shapes(N, d, V, K):
 
 
 @pytest.mark.parametrize("N,d,V,K", [(80, 512, 3000, 4), (1, 64, 128, 1), (100, 1024, 777, 8), (320, 256, 1000, 2),
-                                      (400, 128, 300, 4), (17, 4096, 500, 4)])
+                                      (400, 128, 300, 4), (17, 4096, 500, 4),
+                                      (50, 128, 700, 4), (64, 192, 520, 3)])    # 2 and 3 feature blocks, one row chunk
 def test_bf16_shapes(N, d, V, K):
     cfg = synth.scaled(synth.CONFIGS["c4"], vocab=V, d_model=d)
     inp = synth.make_lm_head_inputs(cfg, 3, N=N)
