@@ -218,7 +218,7 @@ def main():
     outs = [torch.empty_like(layers[0]["q"]) for _ in range(cfg.n_layers)]
     ws_bytes = api.ss_msa_workspace_bytes(cfg.B, cfg.T, cfg.gamma, cfg.H, cfg.Hkv, cfg.D,
                                           layers[0]["block_table"].shape[1] * cfg.page, api.SS_BF16)
-    msa_ws = torch.empty(max(ws_bytes, 1), dtype=torch.uint8, device=dev)
+    msa_ws = torch.zeros(max(ws_bytes, 1), dtype=torch.uint8, device=dev)
     parent = layers[0]["parent"]
     has_lm = cfg.vocab > 0
     if has_lm:

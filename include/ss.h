@@ -22,8 +22,10 @@
  *    NULL = the default stream).  No call synchronises with the device or reads
  *    device memory on the host, so the whole step can be chained on one stream.
  *  - Return value: SS_OK or an error code; ss_last_error() gives a thread-local
- *    message for the last failing call of the calling thread.  On error nothing
- *    has been enqueued.
+ *    message for the last failing call of the calling thread.  Argument, limit
+ *    and workspace errors are found before anything is enqueued; SS_ERR_HIP
+ *    reports a failed launch, and a call that consists of several kernels may
+ *    then have enqueued the earlier ones.
  *  - Errors that only the device could see (a malformed parent array, a
  *    seq_len beyond the block table) cannot be reported by an asynchronous
  *    call; every kernel clamps such values so that all accesses stay in bounds
@@ -163,10 +165,22 @@ int ss_build_mask(const int32_t* parent, int B, int T, int gamma, uint32_t flags
  * == 0, T <= SS_MAX_T, gamma <= SS_MAX_GAMMA.  scale is the factor applied to
  * the dot products (1/sqrt(D) in the paper's MHA).
  * workspace: device scratch of at least ss_msa_workspace_bytes(...) bytes with
- * max_seq_len = max_pages_per_seq*page_size; contents need not be preserved.
+ * max_seq_len = max_pages_per_seq*page_size.  It holds the per-split partial
+ * results and, when two splits are merged inside the attention kernel (see
+ * ss_msa_set_merge_in_kernel), their arrival counters.  The counters must be
+ * ZERO when a call is enqueued and every call leaves them zero: fill a new
+ * workspace with zeros once (ss_msa_workspace_init, or any memset) and it can
+ * be used for any number of calls of any shape it is large enough for.  A
+ * workspace that was never zeroed gives wrong results for split problems, with
+ * no error.  Calls that may run at the same time (different streams, graphs
+ * replayed on different streams) need a workspace each; calls that follow each
+ * other on one stream can share one.  The library keeps nothing between calls.
  */
 size_t ss_msa_workspace_bytes(int B, int T, int gamma, int H, int Hkv, int D, int max_seq_len,
                               int dtype);
+/* Fills `workspace_bytes` bytes of device memory at `workspace` with zeros by a
+ * kernel on `stream` (safe inside a stream capture). */
+int ss_msa_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
 int ss_msa_attention(const void* q, const void* k_new, const void* v_new, const void* k_cache,
                      const void* v_cache, const int32_t* block_table, int max_pages_per_seq,
                      int num_pages, const int32_t* seq_lens, const int32_t* parent, int B, int T,
@@ -187,8 +201,9 @@ int ss_msa_plan(int B, int T, int gamma, int H, int Hkv, int D, int max_seq_len,
 
 /*
  * Tuning knob for a2: number of cached tokens one workgroup scans (the KV
- * split length).  0 = choose from the problem shape (default).  Values are
- * rounded up to a multiple of 128.  The result of a2 does not depend on it
+ * split length).  0 = choose from the problem shape (default).  Values below
+ * 64 count as 64, and values are rounded up to a multiple of 32 (SS_BF16) or
+ * 64 (SS_F32).  The result of a2 does not depend on it
  * beyond floating-point rounding.  Returns the previous setting.
  */
 int ss_msa_set_split_keys(int split_keys);
@@ -199,11 +214,8 @@ int ss_msa_set_split_keys(int split_keys);
  * split that finishes second adds the other's partial rows to its own and writes
  * `out`; the arithmetic is that of the merge kernel, so the result is the same
  * bit for bit and does not depend on which split finishes first.  The splits
- * find each other through arrival counters that live in the library (one region
- * of 32 per call, taken in turn): at most 32 calls may be in flight on one GPU
- * at the same time with this on.  A call captured into a HIP graph keeps the
- * region it was given at capture; replays of one graph follow each other, so
- * they do not meet themselves.  Returns the previous setting.
+ * find each other through arrival counters at the end of the call's workspace
+ * (see a2 for the zero-fill rule).  Returns the previous setting.
  */
 int ss_msa_set_merge_in_kernel(int on);
 

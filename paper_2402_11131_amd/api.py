@@ -27,7 +27,7 @@ SS_MAX_T, SS_MAX_GAMMA, SS_MAX_K = 64, 8, 8
 
 EXPORTS = (
     "ss_version", "ss_last_error", "ss_probe_hbm_read", "ss_probe_mfma_bf16", "ss_check_tree_host", "ss_build_mask", "ss_msa_workspace_bytes",
-    "ss_msa_attention", "ss_msa_plan", "ss_msa_set_split_keys", "ss_msa_set_merge_in_kernel", "ss_lm_head_workspace_bytes", "ss_lm_head_argmax_topk", "ss_lm_head_verify_draft",
+    "ss_msa_attention", "ss_msa_workspace_init", "ss_msa_plan", "ss_msa_set_split_keys", "ss_msa_set_merge_in_kernel", "ss_lm_head_workspace_bytes", "ss_lm_head_argmax_topk", "ss_lm_head_verify_draft",
     "ss_tree_verify", "ss_tree_draft", "ss_full_tree_template_host", "ss_kv_commit", "ss_linear_rows", "ss_stream_insert", "ss_value_rotate",
     "ss_lm_head_logsumexp", "ss_transition_probs", "ss_tree_prune",
 )
@@ -65,7 +65,9 @@ def load_library() -> ctypes.CDLL:
     lib.ss_msa_plan.restype = i32
     lib.ss_msa_attention.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, i32, i32, i32, i32, i32, i32, i32,
                                      c.c_float, i32, u32, vp, vp, sz, vp]
+    lib.ss_msa_workspace_init.argtypes = [vp, sz, vp]
     lib.ss_msa_set_split_keys.argtypes = [i32]
+    lib.ss_msa_set_merge_in_kernel.argtypes = [i32]
     lib.ss_lm_head_workspace_bytes.argtypes = [i32] * 5
     lib.ss_lm_head_workspace_bytes.restype = sz
     lib.ss_lm_head_argmax_topk.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, sz, vp]
@@ -168,14 +170,21 @@ def ss_msa_set_merge_in_kernel(on: bool) -> bool:
     return bool(load_library().ss_msa_set_merge_in_kernel(1 if on else 0))
 
 
-def ss_msa_attention(q, k_new, v_new, k_cache, v_cache, block_table, seq_lens, parent, gamma: int, scale: float,
-                     flags: int = 0, out: Optional[torch.Tensor] = None,
-                     workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """a2.  q [B,R,H,D]; k_new, v_new [B,R,Hkv,D]; k_cache [P,Hkv,page,D]; v_cache [P,Hkv,D,page];
-    block_table [B,max_pages] int32; seq_lens [B] int32; parent [B,T] int32.  Returns out [B,R,H,D]."""
-    lib = load_library()
-    dt = q.dtype
-    code = _dtype_code(q)
+def ss_msa_workspace(B, T, gamma, H, Hkv, D, max_seq_len, dtype_code, device) -> torch.Tensor:
+    """A zero-filled workspace for ss_msa_attention calls of this shape (the arrival counters of the in-kernel
+    split merge must be zero before the first call; every call leaves them zero)."""
+    need = ss_msa_workspace_bytes(B, T, gamma, H, Hkv, D, max_seq_len, dtype_code)
+    ws = torch.empty(max(need, 1), dtype=torch.uint8, device=device)
+    ss_msa_workspace_init(ws)
+    return ws
+
+
+def ss_msa_workspace_init(workspace: torch.Tensor) -> torch.Tensor:
+    _check(load_library().ss_msa_workspace_init(_dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream()))
+    return workspace
+
+
+def _msa_shapes(q, k_new, v_new, k_cache, v_cache, block_table, seq_lens, parent, gamma):
     B, R, H, D = q.shape
     Hkv = k_new.shape[2]
     T = parent.shape[1]
@@ -186,12 +195,24 @@ def ss_msa_attention(q, k_new, v_new, k_cache, v_cache, block_table, seq_lens, p
         raise ValueError("k_cache must be [P,Hkv,page,D] and v_cache [P,Hkv,D,page]")
     if block_table.shape[0] != B or tuple(seq_lens.shape) != (B,) or parent.shape[0] != B:
         raise ValueError("block_table / seq_lens / parent batch size mismatch")
-    max_pages = block_table.shape[1]
+    return B, R, H, D, Hkv, T, P, page, block_table.shape[1]
+
+
+def ss_msa_attention(q, k_new, v_new, k_cache, v_cache, block_table, seq_lens, parent, gamma: int, scale: float,
+                     flags: int = 0, out: Optional[torch.Tensor] = None,
+                     workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """a2.  q [B,R,H,D]; k_new, v_new [B,R,Hkv,D]; k_cache [P,Hkv,page,D]; v_cache [P,Hkv,D,page];
+    block_table [B,max_pages] int32; seq_lens [B] int32; parent [B,T] int32.  Returns out [B,R,H,D].
+    `workspace`: a tensor from ss_msa_workspace (zero-filled once); made here if not given."""
+    lib = load_library()
+    dt = q.dtype
+    code = _dtype_code(q)
+    B, R, H, D, Hkv, T, P, page, max_pages = _msa_shapes(q, k_new, v_new, k_cache, v_cache, block_table, seq_lens,
+                                                          parent, gamma)
     if out is None:
         out = torch.empty_like(q)
-    need = lib.ss_msa_workspace_bytes(B, T, gamma, H, Hkv, D, max_pages * page, code)
     if workspace is None:
-        workspace = torch.empty(max(need, 1), dtype=torch.uint8, device=q.device)
+        workspace = ss_msa_workspace(B, T, gamma, H, Hkv, D, max_pages * page, code, q.device)
     _check(lib.ss_msa_attention(
         _dev(q, dt, "q"), _dev(k_new, dt, "k_new"), _dev(v_new, dt, "v_new"), _dev(k_cache, dt, "k_cache"),
         _dev(v_cache, dt, "v_cache"), _dev(block_table, torch.int32, "block_table"), max_pages, P,

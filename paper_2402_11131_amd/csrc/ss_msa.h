@@ -21,24 +21,29 @@ struct MsaArgs {
   int B, T, gamma, R, H, Hkv, g, D;
   int page, page_shift, max_pages, num_pages;
   int split_keys;  // cached tokens per split (multiple of 32; of 64 for the fp32 kernel)
+  int split0_keys; // cached tokens of split 0 (MFMA path: shorter, that split also scans the step's own rows)
   int n_splits;    // S: upper bound on splits per sequence
   int n_qc;        // query-row chunks per (sequence, KV head) (MFMA path)
   int groups;      // wave groups per workgroup the plan asks for (MFMA path)
-  int arrive_region;  // MFMA path, split launches: region of the arrival counters for the in-kernel merge, or -1
+  unsigned int* arrive;  // MFMA path, two splits merged inside the kernel: arrival counters [B,Hkv,n_qc,5] in the
+                         // workspace (zero before the call, zero again after it), else NULL
   float scale_log2;  // softmax scale times log2(e)
   uint32_t flags;
 };
 
-// A sequence of L cached tokens has active_splits(L) splits; every sequence has at least one (it
-// also scans the step's new keys).  Split s takes the tokens [s*split_keys, min(L,(s+1)*split_keys)).
+// A sequence of L cached tokens has active_splits(L) splits; every sequence has at least one (split 0, which
+// also scans the step's new keys).  Split 0 takes the tokens [0, min(L, split0_keys)), split s > 0 the
+// tokens [split_begin(s), min(L, split_begin(s) + split_keys)).
 SS_DEV int clamp_len(int L, const MsaArgs& a) { return min(max(L, 0), a.max_pages * a.page); }
-SS_DEV int active_splits(int L, const MsaArgs& a) { return max(1, (L + a.split_keys - 1) / a.split_keys); }
+SS_DEV int active_splits(int L, const MsaArgs& a) {
+  return L <= a.split0_keys ? 1 : 1 + (L - a.split0_keys + a.split_keys - 1) / a.split_keys;
+}
+SS_DEV int split_begin(int s, const MsaArgs& a) { return s == 0 ? 0 : a.split0_keys + (s - 1) * a.split_keys; }
+SS_DEV int split_len(int s, const MsaArgs& a) { return s == 0 ? a.split0_keys : a.split_keys; }
 
-// Arrival counters of the in-kernel split merge: kArriveRegions regions (calls take them in turn, so that calls
-// in flight on different streams do not share one) of kArriveSlots counters, one per (sequence, KV head, row
-// chunk, query tile).
-constexpr int kArriveRegions = 32;
-constexpr int kArriveSlots = 8192;
+// Arrival counters of the in-kernel split merge: one per (sequence, KV head, row chunk, query tile of at most
+// kArriveTiles per chunk).
+constexpr int kArriveTiles = 5;
 
 // MFMA path (bf16, D = 64 or 128).  Returns SS_OK or an error code.
 int launch_msa_bf16(const MsaArgs& a, hipStream_t stream);

@@ -34,8 +34,8 @@ __global__ __launch_bounds__(256) void msa_f32_kernel(MsaArgs a) {
   const int n_active = active_splits(L, a);
   if (s >= n_active) return;
   const bool is_last = (s == n_active - 1);
-  const int k0 = s * a.split_keys;
-  const int n_prefix = max(0, min(L, k0 + a.split_keys) - k0);
+  const int k0 = split_begin(s, a);
+  const int n_prefix = max(0, min(L, k0 + split_len(s, a)) - k0);
   const int n_new = is_last ? a.R : 0;
   const int total = n_prefix + n_new;
   const int r0 = chunk * RC;
@@ -218,24 +218,36 @@ __global__ __launch_bounds__(256) void msa_combine_kernel(MsaArgs a) {
 
 // ------------------------------------------------------------------ planning (host)
 
-static int g_split_keys_override = 0;
+static std::atomic<int> g_split_keys_override{0};
 static std::atomic<int> g_merge_in_kernel{1};
 
 struct MsaPlan {
-  int split_keys, n_splits, n_qc, groups;
-  size_t part_o_bytes, part_lse_bytes, total_bytes;
+  int split_keys, split0_keys, n_splits, n_qc, groups;
+  size_t part_o_bytes, part_lse_bytes, arrive_bytes, total_bytes;
 };
 
 // Chooses the split length from the shape alone (sequence lengths live on the device).  Every split
-// costs a workgroup set-up and fp32 partial results that the merge kernel reads back, so the plan uses
-// as few as fill the chip; no split is shorter than 256 cached tokens.
+// costs a workgroup set-up and fp32 partial results that are read back, so the plan uses as few as fill
+// the chip; no split is shorter than 256 cached tokens.
 //   fp32 kernel: splits for about 512 workgroups.
 //   MFMA kernel: with 512 or more (sequence, KV head, row chunk) items one workgroup of one wave group
 //   each, two resident per compute unit (measured best when lengths vary: the hardware evens them out);
 //   with fewer, three wave groups per workgroup (the prefix split again inside the workgroup and merged
 //   through LDS: 15 waves on a compute unit) and splits for about 256 workgroups; three wave groups also
 //   when a sequence has several row chunks (long GQA trees: the kernel is then bound by the matrix
-//   cores and more waves hide more latency).
+//   cores and more waves hide more latency).  The splits are equal shares of the prefix: the step's own
+//   rows, which split 0 also scans, are hidden in that split's set-up.
+// Tuning aid: blocks' worth of time, beyond its ceil(R/32) blocks, that scanning the step's own rows costs
+// split 0 (SS_MSA_SPLIT0_EXTRA, read once).
+static int split0_extra_blocks() {
+  static const int v = []() {
+    const char* e = getenv("SS_MSA_SPLIT0_EXTRA");
+    const int x = e ? atoi(e) : 2;
+    return x < -64 ? -64 : (x > 64 ? 64 : x);
+  }();
+  return v;
+}
+
 static MsaPlan make_plan(int B, int R, int H, int Hkv, int D, int max_len, int dtype) {
   MsaPlan p;
   const int g = H / Hkv;
@@ -251,53 +263,54 @@ static MsaPlan make_plan(int B, int R, int H, int Hkv, int D, int max_len, int d
   }
   if (base < 1) base = 1;
   const int len = max_len < 1 ? 1 : max_len;
-  int split_keys;
-  if (g_split_keys_override > 0) {
-    split_keys = g_split_keys_override;
-  } else {
-    int want_wgs = 512;
-    if (dtype == SS_BF16) {
-      if (base < 512) {
-        p.groups = 3;
-        want_wgs = 256;
-      } else if (p.n_qc > 1) {
-        p.groups = 3;
-      }
+  const int unit = dtype == SS_BF16 ? 32 : 64;  // the MFMA kernel works in 32-key blocks, the fp32 kernel in 64-key tiles
+  int split_keys = g_split_keys_override.load();
+  const bool overridden = split_keys > 0;
+  int want_wgs = 512;
+  if (dtype == SS_BF16) {
+    if (base < 512) {
+      p.groups = 3;
+      want_wgs = 256;
+    } else if (p.n_qc > 1) {
+      p.groups = 3;
     }
+  }
+  if (split_keys <= 0) {
     int n = ceil_div(want_wgs, base);
     const int n_cap = len / 256 < 1 ? 1 : len / 256;
     if (n > n_cap) n = n_cap;
-    split_keys = ceil_div(len, n);
-    if (dtype == SS_BF16 && n > 1) {
-      // The last split also scans the step's own rows (about ceil(R/32) + 2 blocks' worth of work), so
-      // the others take a little more than an equal share of the prefix; whole iterations of all wave
-      // groups where that still leaves the last split something.
-      const int nu = ceil_div(len, 32), extra = ceil_div(R, 32) + 2;
-      int per = (nu + extra + n / 2) / n;
-      const int whole = ceil_div(per, p.groups) * p.groups;
-      if ((n - 1) * whole < nu) per = whole;
-      while (per > 1 && (n - 1) * per >= nu) --per;
-      split_keys = per * 32;
+    split_keys = ceil_div(ceil_div(len, unit), n) * unit;
+  }
+  split_keys = (int)align_up((size_t)(split_keys < 64 ? 64 : split_keys), unit);
+  p.split_keys = p.split0_keys = split_keys;
+  p.n_splits = ceil_div(len, split_keys);
+  if (dtype == SS_BF16 && p.n_splits > 1 && !overridden) {
+    // Split 0 also scans the step's own rows: masked blocks with transposing reads, about `extra` blocks'
+    // worth of time.  It gets that much less of the prefix; the others take whole iterations of all wave
+    // groups where that leaves split 0 something.
+    const int nu = ceil_div(len, 32), n = p.n_splits, extra = ceil_div(R, 32) + split0_extra_blocks();
+    int rest = (nu + extra + n / 2) / n;
+    rest = (rest + p.groups / 2) / p.groups * p.groups;
+    if (rest >= 2 && nu - (n - 1) * rest >= 1) {
+      p.split_keys = 32 * rest;
+      p.split0_keys = 32 * (nu - (n - 1) * rest);
     }
   }
-  const int unit = dtype == SS_BF16 ? 32 : 64;  // the MFMA kernel works in 32-key blocks, the fp32 kernel in 64-key tiles
-  split_keys = (int)align_up((size_t)(split_keys < 64 ? 64 : split_keys), unit);
-  p.split_keys = split_keys;
-  p.n_splits = ceil_div(len, split_keys);
   if (p.n_splits > 1) {
     p.part_o_bytes = align_up((size_t)B * H * p.n_splits * R * D * sizeof(float), 256);
     p.part_lse_bytes = align_up((size_t)B * H * p.n_splits * R * sizeof(float), 256);
+    p.arrive_bytes = (dtype == SS_BF16 && p.n_splits == 2)
+                         ? align_up((size_t)B * Hkv * p.n_qc * kArriveTiles * sizeof(unsigned int), 256) : 0;
   } else {
-    p.part_o_bytes = p.part_lse_bytes = 0;
+    p.part_o_bytes = p.part_lse_bytes = p.arrive_bytes = 0;
   }
-  p.total_bytes = p.part_o_bytes + p.part_lse_bytes + 256;
+  p.total_bytes = p.part_o_bytes + p.part_lse_bytes + p.arrive_bytes + 256;
   return p;
 }
 
 // Whether a full call folds its two splits inside the attention kernel (see ss_msa_attention).
-static bool merges_in_kernel(const MsaPlan& plan, int B, int Hkv, int dtype) {
-  return g_merge_in_kernel.load() && dtype == SS_BF16 && plan.n_splits == 2 &&
-         (long)B * Hkv * plan.n_qc * 5 <= kArriveSlots;
+static bool merges_in_kernel(const MsaPlan& plan, int dtype) {
+  return g_merge_in_kernel.load() && dtype == SS_BF16 && plan.n_splits == 2;
 }
 
 static int check_shape(const char* fn, int B, int T, int gamma, int H, int Hkv, int D, int dtype) {
@@ -312,43 +325,35 @@ static int check_shape(const char* fn, int B, int T, int gamma, int H, int Hkv, 
   return SS_OK;
 }
 
-}  // namespace ss
-
-extern "C" {
-
-int ss_msa_set_split_keys(int split_keys) {
-  const int prev = ss::g_split_keys_override;
-  ss::g_split_keys_override = split_keys > 0 ? split_keys : 0;
-  return prev;
+// Zero fill by a kernel (a memset node must not be recorded into a captured graph): 16 bytes per thread over
+// the aligned middle, thread 0 also takes the unaligned ends.
+__global__ __launch_bounds__(256) void zero_bytes_kernel(unsigned char* p, size_t head, size_t chunks, size_t tail) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < chunks) reinterpret_cast<uintx4*>(p + head)[i] = uintx4{0u, 0u, 0u, 0u};
+  if (i == 0) {
+    for (size_t j = 0; j < head; ++j) p[j] = 0;
+    for (size_t j = 0; j < tail; ++j) p[head + 16 * chunks + j] = 0;
+  }
+}
+static int zero_bytes(unsigned char* p, size_t bytes, hipStream_t st, const char* fn) {
+  if (bytes == 0) return SS_OK;
+  size_t head = (16 - ((uintptr_t)p & 15)) & 15;
+  if (head > bytes) head = bytes;
+  const size_t chunks = (bytes - head) / 16, tail = bytes - head - 16 * chunks;
+  const size_t blocks = chunks / 256 + 1;
+  SS_REQUIRE(blocks <= 0x7fffffffUL, SS_ERR_UNSUPPORTED, "%s: %zu bytes are too many for one fill", fn, bytes);
+  hipLaunchKernelGGL(zero_bytes_kernel, dim3((unsigned)blocks), dim3(256), 0, st, p, head, chunks, tail);
+  return check_launch(fn);
 }
 
-int ss_msa_set_merge_in_kernel(int on) { return ss::g_merge_in_kernel.exchange(on ? 1 : 0); }
-
-int ss_msa_plan(int B, int T, int gamma, int H, int Hkv, int D, int max_seq_len, int dtype, int* n_splits,
-                int* n_kernels) {
-  ss::clear_error();
-  if (int rc = ss::check_shape("ss_msa_plan", B, T, gamma, H, Hkv, D, dtype)) return rc;
-  if (max_seq_len < 0) max_seq_len = 0;
-  const ss::MsaPlan plan = ss::make_plan(B, T * (1 + gamma), H, Hkv, D, max_seq_len, dtype);
-  if (n_splits) *n_splits = plan.n_splits;
-  if (n_kernels) *n_kernels = (plan.n_splits > 1 && !ss::merges_in_kernel(plan, B, Hkv, dtype)) ? 2 : 1;
-  return SS_OK;
-}
-
-size_t ss_msa_workspace_bytes(int B, int T, int gamma, int H, int Hkv, int D, int max_seq_len, int dtype) {
-  ss::clear_error();
-  if (ss::check_shape("ss_msa_workspace_bytes", B, T, gamma, H, Hkv, D, dtype) != SS_OK) return 0;
-  if (max_seq_len < 0) max_seq_len = 0;
-  return ss::make_plan(B, T * (1 + gamma), H, Hkv, D, max_seq_len, dtype).total_bytes;
-}
-
-int ss_msa_attention(const void* q, const void* k_new, const void* v_new, const void* k_cache, const void* v_cache,
-                     const int32_t* block_table, int max_pages_per_seq, int num_pages, const int32_t* seq_lens,
-                     const int32_t* parent, int B, int T, int gamma, int H, int Hkv, int D, int page_size, float scale,
-                     int dtype, uint32_t flags, void* out, void* workspace, size_t workspace_bytes, void* stream) {
-  using namespace ss;
-  clear_error();
-  const char* fn = "ss_msa_attention";
+// The body of ss_msa_attention and ss_msa_attention_static.  `library_scratch`: the workspace is the library's
+// own array, whose size is a limit of the call (not a caller's mistake) and whose arrival counters are cleared
+// here on every call.
+static int msa_run(const char* fn, const void* q, const void* k_new, const void* v_new, const void* k_cache,
+                   const void* v_cache, const int32_t* block_table, int max_pages_per_seq, int num_pages,
+                   const int32_t* seq_lens, const int32_t* parent, int B, int T, int gamma, int H, int Hkv, int D,
+                   int page_size, float scale, int dtype, uint32_t flags, void* out, void* workspace,
+                   size_t workspace_bytes, bool library_scratch, void* stream) {
   if (int rc = check_shape(fn, B, T, gamma, H, Hkv, D, dtype)) return rc;
   SS_REQUIRE(B == 0 || (q && k_new && v_new && k_cache && v_cache && block_table && seq_lens && parent && out),
              SS_ERR_INVALID_ARG, "%s: NULL tensor argument", fn);
@@ -361,13 +366,21 @@ int ss_msa_attention(const void* q, const void* k_new, const void* v_new, const 
   SS_REQUIRE(scale > 0.f && isfinite(scale), SS_ERR_INVALID_ARG, "%s: scale must be positive and finite", fn);
   SS_REQUIRE((flags & ~(SS_STREAM_EXCLUDE_SELF | SS_MSA_PARTIALS_ONLY | SS_MSA_MERGE_ONLY)) == 0, SS_ERR_INVALID_ARG,
              "%s: unknown flags 0x%x", fn, flags);
+  SS_REQUIRE((flags & (SS_MSA_PARTIALS_ONLY | SS_MSA_MERGE_ONLY)) != (SS_MSA_PARTIALS_ONLY | SS_MSA_MERGE_ONLY),
+             SS_ERR_INVALID_ARG, "%s: SS_MSA_PARTIALS_ONLY and SS_MSA_MERGE_ONLY exclude each other", fn);
   if (B == 0) return SS_OK;
 
   const int R = T * (1 + gamma);
   const int max_len = max_pages_per_seq * page_size;
   const MsaPlan plan = make_plan(B, R, H, Hkv, D, max_len, dtype);
-  SS_REQUIRE(plan.n_splits == 1 || (workspace != nullptr && workspace_bytes >= plan.total_bytes), SS_ERR_WORKSPACE,
-             "%s: workspace of %zu bytes needed, %zu given", fn, plan.total_bytes, workspace_bytes);
+  if (library_scratch) {
+    SS_REQUIRE(plan.total_bytes <= workspace_bytes, SS_ERR_UNSUPPORTED,
+               "%s: this shape needs %zu bytes of scratch memory, the library's array holds %zu; use "
+               "ss_msa_attention with a workspace", fn, plan.total_bytes, workspace_bytes);
+  } else {
+    SS_REQUIRE(plan.n_splits == 1 || (workspace != nullptr && workspace_bytes >= plan.total_bytes), SS_ERR_WORKSPACE,
+               "%s: workspace of %zu bytes needed, %zu given", fn, plan.total_bytes, workspace_bytes);
+  }
 
   MsaArgs a;
   a.q = q; a.k_new = k_new; a.v_new = v_new; a.k_cache = k_cache; a.v_cache = v_cache;
@@ -378,21 +391,19 @@ int ss_msa_attention(const void* q, const void* k_new, const void* v_new, const 
   a.B = B; a.T = T; a.gamma = gamma; a.R = R; a.H = H; a.Hkv = Hkv; a.g = H / Hkv; a.D = D;
   a.page = page_size; a.page_shift = page_size == 16 ? 4 : (page_size == 32 ? 5 : 6);
   a.max_pages = max_pages_per_seq; a.num_pages = num_pages;
-  a.split_keys = plan.split_keys; a.n_splits = plan.n_splits; a.n_qc = plan.n_qc; a.groups = plan.groups;
+  a.split_keys = plan.split_keys; a.split0_keys = plan.split0_keys; a.n_splits = plan.n_splits; a.n_qc = plan.n_qc; a.groups = plan.groups;
   a.scale_log2 = scale * 1.4426950408889634f;
   // In-kernel merge (MFMA path, two splits): the second split of a (sequence, head) to finish adds the other's
   // partial rows to its own and writes the output, which saves the merge kernel and its kernel boundary.  With
   // more splits the partial rows would be fetched one split after the other and the merge kernel is faster.
-  a.arrive_region = -1;
-  if (merges_in_kernel(plan, B, Hkv, dtype) && !(flags & SS_MSA_MERGE_ONLY)) {
-    static std::atomic<unsigned int> next_region{0};
-    a.arrive_region = (int)(next_region.fetch_add(1) % kArriveRegions);
-  }
+  a.arrive = nullptr;
+  if (merges_in_kernel(plan, dtype) && !(flags & SS_MSA_MERGE_ONLY))
+    a.arrive = (unsigned int*)(ws + plan.part_o_bytes + plan.part_lse_bytes);
   a.flags = flags;
   hipStream_t st = (hipStream_t)stream;
 
-  SS_REQUIRE((flags & (SS_MSA_PARTIALS_ONLY | SS_MSA_MERGE_ONLY)) != (SS_MSA_PARTIALS_ONLY | SS_MSA_MERGE_ONLY),
-             SS_ERR_INVALID_ARG, "%s: SS_MSA_PARTIALS_ONLY and SS_MSA_MERGE_ONLY exclude each other", fn);
+  if (library_scratch && a.arrive != nullptr)
+    if (int rc = zero_bytes((unsigned char*)a.arrive, plan.arrive_bytes, st, fn)) return rc;
   if (flags & SS_MSA_MERGE_ONLY) {
     // the attention kernel ran in an earlier call with SS_MSA_PARTIALS_ONLY
   } else if (dtype == SS_F32) {
@@ -404,7 +415,7 @@ int ss_msa_attention(const void* q, const void* k_new, const void* v_new, const 
   } else {
     if (int rc = launch_msa_bf16(a, st)) return rc;
   }
-  if (plan.n_splits > 1 && !(flags & SS_MSA_PARTIALS_ONLY) && a.arrive_region < 0) {
+  if (plan.n_splits > 1 && !(flags & SS_MSA_PARTIALS_ONLY) && a.arrive == nullptr) {
     const long threads = (long)B * R * H * (D / 4);
     dim3 grid((unsigned)((threads + 255) / 256));
     if (dtype == SS_F32) hipLaunchKernelGGL(msa_combine_kernel<false>, grid, dim3(256), 0, st, a);
@@ -412,6 +423,50 @@ int ss_msa_attention(const void* q, const void* k_new, const void* v_new, const 
     if (int rc = check_launch(fn)) return rc;
   }
   return SS_OK;
+}
+
+}  // namespace ss
+
+extern "C" {
+
+int ss_msa_set_split_keys(int split_keys) {
+  return ss::g_split_keys_override.exchange(split_keys > 0 ? split_keys : 0);
+}
+
+int ss_msa_set_merge_in_kernel(int on) { return ss::g_merge_in_kernel.exchange(on ? 1 : 0); }
+
+int ss_msa_plan(int B, int T, int gamma, int H, int Hkv, int D, int max_seq_len, int dtype, int* n_splits,
+                int* n_kernels) {
+  ss::clear_error();
+  if (int rc = ss::check_shape("ss_msa_plan", B, T, gamma, H, Hkv, D, dtype)) return rc;
+  if (max_seq_len < 0) max_seq_len = 0;
+  const ss::MsaPlan plan = ss::make_plan(B, T * (1 + gamma), H, Hkv, D, max_seq_len, dtype);
+  if (n_splits) *n_splits = plan.n_splits;
+  if (n_kernels) *n_kernels = (plan.n_splits > 1 && !ss::merges_in_kernel(plan, dtype)) ? 2 : 1;
+  return SS_OK;
+}
+
+size_t ss_msa_workspace_bytes(int B, int T, int gamma, int H, int Hkv, int D, int max_seq_len, int dtype) {
+  ss::clear_error();
+  if (ss::check_shape("ss_msa_workspace_bytes", B, T, gamma, H, Hkv, D, dtype) != SS_OK) return 0;
+  if (max_seq_len < 0) max_seq_len = 0;
+  return ss::make_plan(B, T * (1 + gamma), H, Hkv, D, max_seq_len, dtype).total_bytes;
+}
+
+int ss_msa_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
+  ss::clear_error();
+  SS_REQUIRE(workspace != nullptr || workspace_bytes == 0, SS_ERR_INVALID_ARG, "ss_msa_workspace_init: NULL workspace");
+  return ss::zero_bytes((unsigned char*)workspace, workspace_bytes, (hipStream_t)stream, "ss_msa_workspace_init");
+}
+
+int ss_msa_attention(const void* q, const void* k_new, const void* v_new, const void* k_cache, const void* v_cache,
+                     const int32_t* block_table, int max_pages_per_seq, int num_pages, const int32_t* seq_lens,
+                     const int32_t* parent, int B, int T, int gamma, int H, int Hkv, int D, int page_size, float scale,
+                     int dtype, uint32_t flags, void* out, void* workspace, size_t workspace_bytes, void* stream) {
+  ss::clear_error();
+  return ss::msa_run("ss_msa_attention", q, k_new, v_new, k_cache, v_cache, block_table, max_pages_per_seq, num_pages,
+                     seq_lens, parent, B, T, gamma, H, Hkv, D, page_size, scale, dtype, flags, out, workspace,
+                     workspace_bytes, false, stream);
 }
 
 }  // extern "C"

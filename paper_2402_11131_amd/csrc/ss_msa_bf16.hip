@@ -44,21 +44,18 @@
 // generated in registers from ancestor bit sets and stream ranges; V rows are
 // token-major there: they are staged row-major and read with the LDS transpose
 // read ds_read_b64_tr_b16, which hands a lane 4 consecutive keys of one feature).
+//
+// Order of work.  The step's own rows belong to split 0, which every sequence has,
+// and are scanned FIRST: their addresses do not depend on the page table, so they
+// are loaded and computed while the table and then the first prefix block are on
+// their way (two dependent memory round trips during which a workgroup has nothing
+// else to do).  The full prefix blocks follow in the pipelined main loop, the
+// ragged block (owned by whichever split holds the end of the sequence) comes last.
 #include <stdlib.h>
 
 #include <type_traits>
 
 #include "ss_msa.h"
-
-// Optional phase timing (development aid, compiled in with -DSS_MSA_TIMING): cycle counts per phase
-// of the key loop, summed per wave, are left behind the split log-sum-exp array in the workspace.
-#ifdef SS_MSA_TIMING
-#define SS_T(i) { const long long t_now_ = clock64(); tacc[i] += t_now_ - t_last; t_last = t_now_; }
-#define SS_KEEP(x) asm volatile("" ::"v"(x))
-#else
-#define SS_T(i)
-#define SS_KEEP(x)
-#endif
 
 namespace ss {
 
@@ -67,42 +64,27 @@ namespace ss {
 // another: no cache-wide write-back or invalidate is then needed around the arrival counter.
 SS_DEV void st16_device(float* p, floatx4 v) { asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory"); }
 SS_DEV void st4_device(float* p, float v) { asm volatile("global_store_dword %0, %1, off sc1" ::"v"(p), "v"(v) : "memory"); }
-// lse and DT 16-byte pieces (64 bytes apart) of one partial row; returns when all have arrived.
+// lse and DT 16-byte pieces (64 bytes apart) of one partial row, as relaxed device-scope loads of 8 bytes each:
+// the compiler knows them as loads, so they can be issued early and are waited for at their first use.
 template <int DT>
 SS_DEV void ld_row_device(const float* lse_p, const float* o_p, float& lse, floatx4 (&o)[DT]) {
-  static_assert(DT == 4 || DT == 8, "D is 64 or 128");
-  if constexpr (DT == 8) {
-    asm volatile(
-        "global_load_dword %0, %9, off sc1\n\t"
-        "global_load_dwordx4 %1, %10, off sc1\n\t"
-        "global_load_dwordx4 %2, %10, off offset:64 sc1\n\t"
-        "global_load_dwordx4 %3, %10, off offset:128 sc1\n\t"
-        "global_load_dwordx4 %4, %10, off offset:192 sc1\n\t"
-        "global_load_dwordx4 %5, %10, off offset:256 sc1\n\t"
-        "global_load_dwordx4 %6, %10, off offset:320 sc1\n\t"
-        "global_load_dwordx4 %7, %10, off offset:384 sc1\n\t"
-        "global_load_dwordx4 %8, %10, off offset:448 sc1\n\t"
-        "s_waitcnt vmcnt(0)"
-        : "=&v"(lse), "=&v"(o[0]), "=&v"(o[1]), "=&v"(o[2]), "=&v"(o[3]), "=&v"(o[4]), "=&v"(o[5]), "=&v"(o[6]), "=&v"(o[7])
-        : "v"(lse_p), "v"(o_p)
-        : "memory");
-  } else {
-    asm volatile(
-        "global_load_dword %0, %5, off sc1\n\t"
-        "global_load_dwordx4 %1, %6, off sc1\n\t"
-        "global_load_dwordx4 %2, %6, off offset:64 sc1\n\t"
-        "global_load_dwordx4 %3, %6, off offset:128 sc1\n\t"
-        "global_load_dwordx4 %4, %6, off offset:192 sc1\n\t"
-        "s_waitcnt vmcnt(0)"
-        : "=&v"(lse), "=&v"(o[0]), "=&v"(o[1]), "=&v"(o[2]), "=&v"(o[3])
-        : "v"(lse_p), "v"(o_p)
-        : "memory");
+  lse = __uint_as_float(__hip_atomic_load(reinterpret_cast<const unsigned int*>(lse_p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt) {
+    const unsigned long long* p8 = reinterpret_cast<const unsigned long long*>(o_p + 16 * dt);
+    const unsigned long long lo = __hip_atomic_load(p8, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const unsigned long long hi = __hip_atomic_load(p8 + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    o[dt] = floatx4{__uint_as_float((unsigned int)lo), __uint_as_float((unsigned int)(lo >> 32)),
+                    __uint_as_float((unsigned int)hi), __uint_as_float((unsigned int)(hi >> 32))};
   }
 }
-
-// Arrival counters of the in-kernel split merge (zero when the library is loaded; the last split to arrive
-// sets its counter back to zero).
-__device__ unsigned int g_msa_arrive[kArriveRegions * kArriveSlots];
+// Arrival counter of the in-kernel split merge, read and written at device scope.
+SS_DEV unsigned int ld_counter_device(const unsigned int* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+SS_DEV void st_counter_device(unsigned int* p, unsigned int v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 
 constexpr float kLazyLog2 = 16.0f;
 constexpr int kMaxGroups = 4;  // wave groups per workgroup
@@ -165,9 +147,6 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
   uint64_t* anc = reinterpret_cast<uint64_t*>(par + SS_MAX_T);
   float* ml = reinterpret_cast<float*>(anc + SS_MAX_T);  // [n_groups][NW][2][16]: max, sum per query
 
-#ifdef SS_MSA_TIMING
-  const long long t_entry = clock64(), r_entry = wall_clock64();
-#endif
   // ---- which piece of work: XCD-aware order.  Workgroup ids go round-robin over
   // the 8 XCDs, so ids that are equal mod 8 share an L2: the query chunks of one
   // (sequence, KV head, split) are given such ids and read K/V through one L2.
@@ -186,11 +165,10 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int grp = w / NW, wt = w % NW;  // wave group, query tile of this wave
   const int R = a.R, T = a.T, F = a.g * R;
-  // Cached tokens [k0, k0 + split_keys) clipped to the sequence; the plan made the splits a little
-  // longer than an equal share, so that the last one, which also scans the step's own rows, has less
-  // of the prefix.  Nothing up to the first loads depends on the sequence length (it is fetched in
-  // parallel with them): page ids and the first block are fetched from clamped, always valid positions.
-  const int k0 = s * a.split_keys;
+  // Cached tokens [k0, k0 + split_keys) clipped to the sequence.  Nothing up to the first loads depends on
+  // the sequence length (it is fetched in parallel with them): page ids and the first block are fetched
+  // from clamped, always valid positions.
+  const int k0 = split_begin(s, a);
   const float c = a.scale_log2;
 
   const uint16_t* q = (const uint16_t*)a.q;
@@ -213,7 +191,7 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
   auto refill_pages = [&](int jbase) {
     const int kb = min(k0 + 32 * (grp + (jbase + lane) * n_groups), key_cap);
     tab_a = min(max(my_table[kb >> a.page_shift], 0), a.num_pages - 1);
-    tab_b = min(max(my_table[(kb + 16) >> a.page_shift], 0), a.num_pages - 1);
+    tab_b = min(max(my_table[min((kb + 16) >> a.page_shift, a.max_pages - 1)], 0), a.num_pages - 1);
   };
   refill_pages(0);
   const int par_v = tid < T ? clamp_parent(a.parent[(size_t)b * T + tid], tid) : 0;
@@ -293,40 +271,85 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
     for (int j = 0; j < KJ; ++j) *reinterpret_cast<uintx4*>(st + v_ldst[j]) = stg[KJ + j];
   };
 
-  // ---- main loop over full blocks of the prefix: while a group computes on one LDS stage, its waves
-  // hold the next unit in registers (loads issued at the top), write it to the other stage after the
-  // compute, and one barrier per unit publishes it.
-  const RowVis no_vis = RowVis{0, 0, 0};
-  // ---- prologue.  First block of this group on its way (harmless if it turns out not to exist);
-  // the tree's ancestor sets into LDS meanwhile; then the sequence length decides what there is to do.
+  // ---- units that are not full prefix blocks: the step's own rows (is_new; base = first row of the
+  // unit) and the ragged last block of the prefix (base = its first cached token).  Addresses are per
+  // lane here, clamped to existing keys / rows; what is read in excess is masked.  The lane id is
+  // laundered wherever addresses are formed, so that none of this arithmetic is kept in registers
+  // across the main loop.
+  auto load_special = [&](uintx4 (&dst)[2 * KJ], bool is_new, int base, int last) {
+    int lane2 = lane;
+    asm volatile("" : "+v"(lane2));
+    const int ril2 = lane2 / CPR, pch2 = lane2 % CPR;
+#pragma unroll
+    for (int j = 0; j < KJ; ++j) {
+      const int sl = wt + LW * j;
+      const int rr = ROWS_PER_SLOT * sl + ril2;
+      const uint16_t *ksrc, *vsrc;
+      if (!is_new) {
+        const int key = min(base + rr, last);
+        const int pg = min(max(my_table[key >> a.page_shift], 0), a.num_pages - 1);
+        ksrc = k_head + (size_t)pg * page_stride + (size_t)(key & pmask) * D;
+        const int half = sl / V_DBLK, dblk = sl % V_DBLK;
+        const int vkey = min(base + 16 * half + (lane2 & 1) * 8, last & ~7);
+        const int vpg = min(max(my_table[vkey >> a.page_shift], 0), a.num_pages - 1);
+        vsrc = v_head + (size_t)vpg * page_stride + (size_t)(dblk * 32 + (lane2 >> 1)) * a.page + (vkey & pmask);
+      } else {
+        const size_t row = ((size_t)b * R + min(base + rr, R - 1)) * a.Hkv + hk;
+        ksrc = k_new + row * D;
+        vsrc = v_new + row * D + pch2 * 8;
+      }
+      dst[j] = ld16(ksrc + ((pch2 ^ k_swz<D>(rr)) * 8));
+      dst[KJ + j] = ld16(vsrc);
+    }
+  };
+  auto store_special = [&](const uintx4 (&src)[2 * KJ], bool is_new, unsigned char* st) {
+    int lane2 = lane;
+    asm volatile("" : "+v"(lane2));
+    const int ril2 = lane2 / CPR, pch2 = lane2 % CPR;
+#pragma unroll
+    for (int j = 0; j < KJ; ++j) {
+      const int sl = wt + LW * j;
+      *reinterpret_cast<uintx4*>(st + sl * 1024 + lane2 * 16) = src[j];
+      if (!is_new) {
+        const int half = sl / V_DBLK, dblk = sl % V_DBLK;
+        const int chunk = (2 * half + (lane2 & 1)) ^ ((lane2 >> 2) & 3);
+        *reinterpret_cast<uintx4*>(st + K_BYTES + (dblk * 32 + (lane2 >> 1)) * VROW + chunk * 16) = src[KJ + j];
+      } else {
+        const int rr = ROWS_PER_SLOT * sl + ril2;
+        *reinterpret_cast<uintx4*>(st + K_BYTES + rr * (2 * D) + ((pch2 ^ (2 * (rr & 3))) * 16)) = src[KJ + j];
+      }
+    }
+  };
+
+  // ---- prologue.  In flight at once: the page ids (issued above), the sequence length, the tree, this
+  // wave's queries, split 0's first block of the step's own rows, and, as soon as the page ids are
+  // here, this group's first block of the prefix (harmless if it turns out not to exist).
+  const int L_raw = a.seq_lens[b];
+  const bool has_new = s == 0;  // every sequence has a split 0
+  const int n_new_units = (R + 31) >> 5;
+  uintx4 stn[2 * KJ];
+  if (has_new && loader && grp < n_new_units) load_special(stn, true, 32 * grp, 0);
   if (loader) load_main(grp, __builtin_amdgcn_readlane(tab_a, 0), __builtin_amdgcn_readlane(tab_b, 0));
   if (tid < T) par[tid] = par_v;
   __syncthreads();
   compute_anc(par, T, anc, tid);
+  __syncthreads();
 
-  const int L = clamp_len(a.seq_lens[b], a);
+  const int L = clamp_len(L_raw, a);
   const int n_active = active_splits(L, a);
   if (s >= n_active) return;
-  const bool is_last = (s == n_active - 1);
-  const int k1 = max(k0, min(L, k0 + a.split_keys));
-  // Units of this split: full 32-key blocks of the prefix, its ragged last block, blocks of the step's
-  // own rows (last split only).  The full blocks go through the pipelined main loop, n_main iterations
-  // with one block per group (in the last iteration some groups may have none); the ragged block and
-  // the step's own rows are handled afterwards.
+  const int k1 = max(k0, min(L, k0 + split_len(s, a)));
+  // Units of this split: full 32-key blocks of the prefix (pipelined main loop, n_main iterations with
+  // one block per group; in the last iteration some groups may have none) and its ragged last block.
   const int n_full = (k1 - k0) >> 5;
   const int tail = (k1 - k0) & 31;
-  const int n_prefix_units = n_full + (tail ? 1 : 0);
-  const int n_units = n_prefix_units + (is_last ? (R + 31) >> 5 : 0);
   const int n_main = (n_full + n_groups - 1) / n_groups;
-#ifdef SS_MSA_TIMING
-  long long tacc[8] = {0, 0, 0, 0, 0, 0, 0, 0}, t_last = 0;
-#endif
+  const RowVis no_vis = RowVis{0, 0, 0};
   // One unit out of an LDS stage: scores, softmax update, O += P V.  `full` (a compile-time flag) is
-  // the unmasked main-loop flavour; otherwise the unit may be ragged or consist of the step's own rows
-  // and `vis` tells which of those this lane's query row may see.
-  auto compute = [&](auto full, int u, const unsigned char* st, const RowVis& vis) {
+  // the unmasked main-loop flavour; otherwise the unit is the ragged block of the prefix, or (is_new)
+  // rows c0.. of the step's own block and `vis` tells which of those this lane's query row may see.
+  auto compute = [&](auto full, bool is_new, int c0, const unsigned char* st, const RowVis& vis) {
     constexpr bool FULL = decltype(full)::value;
-    const bool is_new = !FULL && u >= n_prefix_units;
     // The masked flavours recompute their lane-dependent offsets on every call (the lane id is
     // laundered) instead of keeping them in registers across the loops.
     int ln = lane;
@@ -344,12 +367,8 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
       }
       S[X] = acc;
     }
-    SS_KEEP(S[0]);
-    SS_KEEP(S[1]);
-    SS_T(1);
     // ---- mask (only the ragged prefix block and the new rows)
-    if (!FULL && u >= n_full) {
-      const int c0 = 32 * (u - n_prefix_units);
+    if (!FULL) {
 #pragma unroll
       for (int X = 0; X < 2; ++X)
 #pragma unroll
@@ -386,10 +405,8 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
         P[4 * X + i] = (__bf16)pr;
       }
     l_run += ps;
-    SS_KEEP(P);
-    SS_T(2);
     // ---- O^T += V^T P^T
-    if (FULL || u < n_full) {
+    if (FULL) {
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt) {
         const uintx4 vv = *reinterpret_cast<const uintx4*>(st + v_rd + dt * (16 * VROW));
@@ -421,128 +438,78 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
     }
   };
 
+  // ---- the step's own rows (split 0), through stage 1 of the group while the first prefix block is
+  // still on its way into registers.  One block per group and round.
+  if (has_new) {
+    const RowVis vis = make_row_vis(q_r, T, a.gamma, anc, (a.flags & SS_STREAM_EXCLUDE_SELF) != 0);
+    unsigned char* st1 = my_stages + STAGE_BYTES;
+    for (int jn = 0; jn * n_groups < n_new_units; ++jn) {
+      const int un = jn * n_groups + grp;
+      const bool mine = un < n_new_units;
+      if (jn > 0) __syncthreads();  // the previous round's block has been consumed
+      if (loader && mine) store_special(stn, true, st1);
+      if (loader && un + n_groups < n_new_units) load_special(stn, true, 32 * (un + n_groups), 0);  // next round's
+      __syncthreads();
+      if (mine) compute(std::false_type{}, true, 32 * un, st1, vis);
+    }
+  }
+
+  // ---- main loop over full blocks of the prefix: while a group computes on one LDS stage, its waves
+  // hold the next unit in registers (loads issued at the top), write it to the other stage after the
+  // compute, and one barrier per unit publishes it.
   if (n_main > 0 && loader) store_main(my_stages);
   __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): nothing from the prologue (Q, page ids) is pending inside the loop
   __syncthreads();
-#ifdef SS_MSA_TIMING
-  t_last = clock64();
-  const long long t_loop0 = t_last;
-#endif
   for (int it = 0; it + 1 < n_main; ++it) {
     const int u = grp + it * n_groups;
     const int jn = it + 1;
     if ((jn & 63) == 0) refill_pages(jn);
     if (loader)
       load_main(u + n_groups, __builtin_amdgcn_readlane(tab_a, jn & 63), __builtin_amdgcn_readlane(tab_b, jn & 63));
-    SS_T(0);
-    compute(std::true_type{}, u, my_stages + (it & 1) * STAGE_BYTES, no_vis);
-    SS_KEEP(O[0]);
-    SS_KEEP(O[DT - 1]);
-    SS_T(3);
+    compute(std::true_type{}, false, 0, my_stages + (it & 1) * STAGE_BYTES, no_vis);
     if (loader) store_main(my_stages + (jn & 1) * STAGE_BYTES);
-    SS_T(4);
     __syncthreads();  // the next stage is complete, this one may be overwritten after the next barrier
-    SS_T(5);
   }
-  // (the last main-loop unit is computed below, with the first of the remaining units already in flight)
-#ifdef SS_MSA_TIMING
-  if (lane == 0 && blockIdx.x < 1024) {
-    long long* dbg = (long long*)a.part_lse + 1000000 + (blockIdx.x * 16 + w) * 16;
-    for (int i = 0; i < 6; ++i) dbg[i] = tacc[i];
-    dbg[6] = n_main;
-    dbg[7] = t_loop0 - t_entry;
-    dbg[8] = t_entry;
-    dbg[9] = clock64();
-    dbg[10] = __builtin_amdgcn_s_getreg(4 | (31 << 11));
-    dbg[11] = __builtin_amdgcn_s_getreg(20 | (31 << 11));
-  }
-#endif
+  // (the last main-loop unit is computed below, with the ragged block, if any, already in flight)
 
-  // ---- the remaining units (the ragged block, the step's own rows), pipelined
-  // the same way.  Addresses are per lane here, clamped to existing keys / rows; what is read in
-  // excess is masked.  The lane id is laundered wherever addresses are formed, so that none of this
-  // arithmetic is kept in registers across the loops.
-  const int u_odd0 = n_full;
-  const int n_odd_iter = (n_units - u_odd0 + n_groups - 1) / n_groups;
+  // ---- the ragged last block of the prefix: group 0's, loaded while the last main-loop unit is computed
   {
-    auto load_odd = [&](int u) {
-      int lane2 = lane;
-      asm volatile("" : "+v"(lane2));
-      const int ril2 = lane2 / CPR, pch2 = lane2 % CPR;
-      const bool is_new = u >= n_prefix_units;
-      const int kb = k0 + 32 * u, last = k1 - 1;  // prefix units
-      const int c0 = 32 * (u - n_prefix_units);   // units of new rows
-#pragma unroll
-      for (int j = 0; j < KJ; ++j) {
-        const int sl = wt + LW * j;
-        const int rr = ROWS_PER_SLOT * sl + ril2;
-        const uint16_t *ksrc, *vsrc;
-        if (!is_new) {
-          const int key = min(kb + rr, last);
-          const int pg = min(max(my_table[key >> a.page_shift], 0), a.num_pages - 1);
-          ksrc = k_head + (size_t)pg * page_stride + (size_t)(key & pmask) * D;
-          const int half = sl / V_DBLK, dblk = sl % V_DBLK;
-          const int vkey = min(kb + 16 * half + (lane2 & 1) * 8, last & ~7);
-          const int vpg = min(max(my_table[vkey >> a.page_shift], 0), a.num_pages - 1);
-          vsrc = v_head + (size_t)vpg * page_stride + (size_t)(dblk * 32 + (lane2 >> 1)) * a.page + (vkey & pmask);
-        } else {
-          const size_t row = ((size_t)b * R + min(c0 + rr, R - 1)) * a.Hkv + hk;
-          ksrc = k_new + row * D;
-          vsrc = v_new + row * D + pch2 * 8;
-        }
-        stg[j] = ld16(ksrc + ((pch2 ^ k_swz<D>(rr)) * 8));
-        stg[KJ + j] = ld16(vsrc);
-      }
-    };
-    auto store_odd = [&](int u, unsigned char* st) {
-      int lane2 = lane;
-      asm volatile("" : "+v"(lane2));
-      const int ril2 = lane2 / CPR, pch2 = lane2 % CPR;
-      const bool is_new = u >= n_prefix_units;
-#pragma unroll
-      for (int j = 0; j < KJ; ++j) {
-        const int sl = wt + LW * j;
-        *reinterpret_cast<uintx4*>(st + sl * 1024 + lane2 * 16) = stg[j];
-        if (!is_new) {
-          const int half = sl / V_DBLK, dblk = sl % V_DBLK;
-          const int chunk = (2 * half + (lane2 & 1)) ^ ((lane2 >> 2) & 3);
-          *reinterpret_cast<uintx4*>(st + K_BYTES + (dblk * 32 + (lane2 >> 1)) * VROW + chunk * 16) = stg[KJ + j];
-        } else {
-          const int rr = ROWS_PER_SLOT * sl + ril2;
-          *reinterpret_cast<uintx4*>(st + K_BYTES + rr * (2 * D) + ((pch2 ^ (2 * (rr & 3))) * 16)) = stg[KJ + j];
-        }
-      }
-    };
-    const bool odd_first = loader && u_odd0 + grp < n_units;
-    if (odd_first) load_odd(u_odd0 + grp);  // in flight while the last main-loop unit is computed
+    const bool rag_mine = tail != 0 && grp == 0;
+    const int rag_base = k0 + 32 * n_full;
+    if (rag_mine && loader) load_special(stg, false, rag_base, k1 - 1);
     if (n_main > 0) {
       const int u_last = grp + (n_main - 1) * n_groups;
-      if (u_last < n_full) compute(std::true_type{}, u_last, my_stages + ((n_main - 1) & 1) * STAGE_BYTES, no_vis);
-      __syncthreads();  // the stages are free for what follows
+      if (u_last < n_full) compute(std::true_type{}, false, 0, my_stages + ((n_main - 1) & 1) * STAGE_BYTES, no_vis);
     }
-    if (n_odd_iter > 0) {
-      const RowVis vis = is_last ? make_row_vis(q_r, T, a.gamma, anc, (a.flags & SS_STREAM_EXCLUDE_SELF) != 0) : no_vis;
-      if (odd_first) store_odd(u_odd0 + grp, my_stages);
+    if (tail != 0) {
+      __syncthreads();  // the stages are free
+      if (rag_mine && loader) store_special(stg, false, my_stages);
       __syncthreads();
-      for (int jo = 0; jo < n_odd_iter; ++jo) {
-        const int u = u_odd0 + jo * n_groups + grp, un = u + n_groups;
-        if (loader && un < n_units) load_odd(un);
-        if (u < n_units) compute(std::false_type{}, u, my_stages + (jo & 1) * STAGE_BYTES, vis);
-        if (loader && un < n_units) store_odd(un, my_stages + ((jo + 1) & 1) * STAGE_BYTES);
-        __syncthreads();
-      }
+      if (rag_mine) compute(std::false_type{}, false, 0, my_stages, no_vis);
     }
   }
 
-#ifdef SS_MSA_TIMING
-  const long long t_odd = clock64();
-#endif
   // ---- merge the groups.  Every wave reduces its sum over the four lane groups; groups > 0 leave
   // (max, sum, O) in LDS; group 0 brings everything to a common maximum, adds and stores.
+  const bool split_launch = a.n_splits > 1;
+  const bool merge_here = split_launch && a.arrive != nullptr && !(a.flags & SS_MSA_PARTIALS_ONLY);
+  // In-kernel merge of two splits.  Every query tile of a split has an arrival counter.  A tile that finds
+  // the other split's tile already arrived (or the sequence too short to have another split) takes that
+  // split's partial rows from memory, folds them with what it holds in registers and writes the final rows.
+  // Otherwise it stores its own partial rows, announces itself, and does the same only if the other tile
+  // arrived in between.  Nothing waits for anything.  The counter is read early, before the wave groups are
+  // merged, so that the other split's rows travel while that happens.
+  unsigned int* ctr = nullptr;
+  unsigned int early = 0;
+  if (merge_here && grp == 0) {
+    ctr = a.arrive + (((size_t)b * a.Hkv + hk) * a.n_qc + qc) * kArriveTiles + wt;
+    early = ld_counter_device(ctr);
+  }
   l_run += __shfl_xor(l_run, 16, 64);
   l_run += __shfl_xor(l_run, 32, 64);
   floatx4* obuf = reinterpret_cast<floatx4*>(stages);  // [(grp-1)*NW + wt][DT][64]
   float* my_ml = ml + (grp * NW + wt) * 32;
+  __syncthreads();  // every group is done with its stages (the merge buffer overlays them)
   if (grp > 0) {
     if (lg == 0) {
       my_ml[lq] = m_run;
@@ -553,6 +520,15 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
   }
   __syncthreads();
   if (grp > 0) return;
+
+  // rows of the other split, on their way during the merge of the groups
+  const int s_other = 1 - s;
+  const bool others_ready = merge_here && early + 1 == (unsigned)n_active;  // n_active is 1 or 2 here
+  const bool prefetched = others_ready && n_active == 2 && f_valid;
+  float l_other = -INFINITY;
+  floatx4 o_other[DT];
+  const size_t pr_other = (((size_t)b * a.H + q_h) * a.n_splits + s_other) * R + q_r;
+  if (prefetched) ld_row_device<DT>(a.part_lse + pr_other, a.part_o + pr_other * D + 4 * lg, l_other, o_other);
 
   float mm = m_run;
   for (int g2 = 1; g2 < n_groups; ++g2) mm = fmaxf(mm, ml[(g2 * NW + wt) * 32 + lq]);
@@ -573,89 +549,67 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
   // ---- normalise and store.  A lane holds features 16*dt + 4*lg .. +3 of its query row.
   if (!f_valid) return;
   const float inv = l_run > 0.f ? 1.f / l_run : 0.f;
-  if (a.n_splits == 1) {
-    uint16_t* op = (uint16_t*)a.out + (((size_t)b * R + q_r) * a.H + q_h) * D + 4 * lg;
+  uint16_t* outp = (uint16_t*)a.out + (((size_t)b * R + q_r) * a.H + q_h) * D + 4 * lg;
+  if (!split_launch) {
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) {
       const floatx4 v = O[dt] * inv;
-      *reinterpret_cast<uintx2*>(op + 16 * dt) = uintx2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+      *reinterpret_cast<uintx2*>(outp + 16 * dt) = uintx2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
     }
-  } else {
-    const size_t pr = (((size_t)b * a.H + q_h) * a.n_splits + s) * R + q_r;
-    float* op = a.part_o + pr * D + 4 * lg;
-    const float my_lse = mm * c + __log2f(l_run);
-    const bool merge_here = a.arrive_region >= 0 && !(a.flags & SS_MSA_PARTIALS_ONLY);
-    if (!merge_here) {
+    return;
+  }
+  const size_t pr = (((size_t)b * a.H + q_h) * a.n_splits + s) * R + q_r;
+  float* op = a.part_o + pr * D + 4 * lg;
+  const float my_lse = mm * c + __log2f(l_run);
 #pragma unroll
-      for (int dt = 0; dt < DT; ++dt) *reinterpret_cast<floatx4*>(op + 16 * dt) = O[dt] * inv;
-      if (lg == 0) a.part_lse[pr] = my_lse;
-    } else {
-      // In-kernel merge of the splits: every query tile of every split announces itself once its partial
-      // result is in memory; the one that finds all others there (none waits for any) adds them to what it
-      // still holds in registers and writes the final rows.  The splits run on different XCDs: the partial
-      // rows are stored and loaded coherently at device scope, and a wave announces itself only when its
-      // stores have completed.
+  for (int dt = 0; dt < DT; ++dt) O[dt] *= inv;
+  if (!merge_here) {
 #pragma unroll
-      for (int dt = 0; dt < DT; ++dt) st16_device(op + 16 * dt, O[dt] * inv);
-      if (lg == 0) st4_device(a.part_lse + pr, my_lse);
-      __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's partial rows are where every XCD reads them
-      unsigned int* ctr = g_msa_arrive + (size_t)a.arrive_region * kArriveSlots +
-                          (((size_t)b * a.Hkv + hk) * a.n_qc + qc) * NW + wt;
-      unsigned int seen = 0;
-      if (lane == 0) seen = atomicAdd(ctr, 1u);  // lane 0 holds the tile's first row: valid whenever any is
-      seen = __builtin_amdgcn_readfirstlane(seen);
-      if (seen + 1 == (unsigned)n_active) {
-        // the splits in index order with the arithmetic of the merge kernel, so that the result does not
-        // depend on which split came last (its own rows are taken from registers, the others' from memory)
-        floatx4 mine[DT], acc[DT];
+    for (int dt = 0; dt < DT; ++dt) *reinterpret_cast<floatx4*>(op + 16 * dt) = O[dt];
+    if (lg == 0) a.part_lse[pr] = my_lse;
+    return;
+  }
+  bool fold_now = others_ready;
+  if (!others_ready) {
+    // The splits run on different XCDs: the partial rows are stored coherently at device scope, and a
+    // wave announces itself only when its stores have completed.
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-          mine[dt] = O[dt] * inv;
-          acc[dt] = floatx4{0.f, 0.f, 0.f, 0.f};
-        }
-        float M = -INFINITY, wsum = 0.f;
-        auto fold = [&](float l2, const floatx4 (&o2)[DT]) {
-          if (l2 > -INFINITY) {
-            const float m_new = fmaxf(M, l2);
-            const float keep = exp2f(M - m_new), w2 = exp2f(l2 - m_new);
+    for (int dt = 0; dt < DT; ++dt) st16_device(op + 16 * dt, O[dt]);
+    if (lg == 0) st4_device(a.part_lse + pr, my_lse);
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's partial rows are where every XCD reads them
+    unsigned int seen = 0;
+    if (lane == 0) seen = atomicAdd(ctr, 1u);  // lane 0 holds the tile's first row: valid whenever any is
+    seen = __builtin_amdgcn_readfirstlane(seen);
+    fold_now = seen + 1 == (unsigned)n_active;
+    if (fold_now) ld_row_device<DT>(a.part_lse + pr_other, a.part_o + pr_other * D + 4 * lg, l_other, o_other);
+  }
+  if (!fold_now) return;
+  // the splits in index order with the arithmetic of the merge kernel, so that the result does not depend
+  // on which split came last (its own rows are taken from registers, the other's from memory)
+  floatx4 acc[DT];
 #pragma unroll
-            for (int dt = 0; dt < DT; ++dt) acc[dt] = merge_step(acc[dt], keep, o2[dt], w2);
-            wsum = __builtin_fmaf(wsum, keep, w2);
-            M = m_new;
-          }
-        };
-        auto fold_from_memory = [&](int s2) {
-          const size_t pr2 = (((size_t)b * a.H + q_h) * a.n_splits + s2) * R + q_r;
-          float l2;
-          floatx4 o2[DT];
-          ld_row_device<DT>(a.part_lse + pr2, a.part_o + pr2 * D + 4 * lg, l2, o2);
-          fold(l2, o2);
-        };
-        for (int s2 = 0; s2 < s; ++s2) fold_from_memory(s2);
-        fold(my_lse, mine);
-        for (int s2 = s + 1; s2 < n_active; ++s2) fold_from_memory(s2);
+  for (int dt = 0; dt < DT; ++dt) acc[dt] = floatx4{0.f, 0.f, 0.f, 0.f};
+  float M = -INFINITY, wsum = 0.f;
+  auto fold = [&](float l2, const floatx4 (&o2)[DT]) {
+    if (l2 > -INFINITY) {
+      const float m_new = fmaxf(M, l2);
+      const float keep = exp2f(M - m_new), w2 = exp2f(l2 - m_new);
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) O[dt] = acc[dt];
-        const float inv2 = wsum > 0.f ? 1.f / wsum : 0.f;
-        uint16_t* outp = (uint16_t*)a.out + (((size_t)b * R + q_r) * a.H + q_h) * D + 4 * lg;
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-          const floatx4 v = O[dt] * inv2;
-          *reinterpret_cast<uintx2*>(outp + 16 * dt) = uintx2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
-        }
-        if (lane == 0) *ctr = 0;  // for the next call that gets this region
-      }
+      for (int dt = 0; dt < DT; ++dt) acc[dt] = merge_step(acc[dt], keep, o2[dt], w2);
+      wsum = __builtin_fmaf(wsum, keep, w2);
+      M = m_new;
     }
+  };
+  if (n_active == 2 && s_other == 0) fold(l_other, o_other);
+  fold(my_lse, O);
+  if (n_active == 2 && s_other == 1) fold(l_other, o_other);
+  const float inv2 = wsum > 0.f ? 1.f / wsum : 0.f;
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt) {
+    const floatx4 v = acc[dt] * inv2;
+    *reinterpret_cast<uintx2*>(outp + 16 * dt) = uintx2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
   }
-#ifdef SS_MSA_TIMING
-  if (lane == 0 && blockIdx.x < 1024) {
-    long long* dbg = (long long*)a.part_lse + 1000000 + (blockIdx.x * 16 + w) * 16;
-    dbg[12] = clock64();
-    dbg[13] = t_odd;
-    dbg[14] = wall_clock64() - r_entry;
-    dbg[15] = r_entry;
-  }
-#endif
+  if (lane == 0) st_counter_device(ctr, 0u);  // the next call finds the counters zero again
 }
 
 // Folded query rows one workgroup takes (a multiple of 16, at most 80).

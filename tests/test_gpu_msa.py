@@ -186,7 +186,7 @@ def test_attention_kernel_and_split_merge_as_two_calls():
     try:
         need = api.ss_msa_workspace_bytes(cfg.B, cfg.T, cfg.gamma, cfg.H, cfg.Hkv, cfg.D,
                                           inp["block_table"].shape[1] * cfg.page, api.SS_BF16)
-        ws = torch.empty(need, dtype=torch.uint8, device=DEV)
+        ws = torch.zeros(need, dtype=torch.uint8, device=DEV)
         full = api.ss_msa_attention(*args, workspace=ws).clone()
         out = torch.zeros_like(full)
         api.ss_msa_attention(*args, flags=api.SS_MSA_PARTIALS_ONLY, out=out, workspace=ws)
@@ -254,7 +254,7 @@ def test_two_split_merge_in_kernel_over_shapes(case):
     prev_keys = api.ss_msa_set_split_keys(max(64, (max_len // 2 + 31) // 32 * 32))
     prev = api.ss_msa_set_merge_in_kernel(False)
     try:
-        ws = torch.empty(api.ss_msa_workspace_bytes(B, T, gamma, H, Hkv, D, max_len, api.SS_BF16), dtype=torch.uint8,
+        ws = torch.zeros(api.ss_msa_workspace_bytes(B, T, gamma, H, Hkv, D, max_len, api.SS_BF16), dtype=torch.uint8,
                          device=DEV)
         ref = api.ss_msa_attention(*args, workspace=ws).clone()
         api.ss_msa_set_merge_in_kernel(True)

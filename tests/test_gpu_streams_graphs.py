@@ -17,7 +17,7 @@ def _setup(seed):
     W = synth.make_lm_head_inputs(cfg, seed, device=DEV)["W"]
     tok = torch.from_numpy(synth.make_draft_tokens(seed, lay["parent"].cpu().numpy(), cfg.vocab)).to(DEV)
     max_len = lay["block_table"].shape[1] * cfg.page
-    ws = torch.empty(api.ss_msa_workspace_bytes(cfg.B, cfg.T, cfg.gamma, cfg.H, cfg.Hkv, cfg.D, max_len, api.SS_BF16),
+    ws = torch.zeros(api.ss_msa_workspace_bytes(cfg.B, cfg.T, cfg.gamma, cfg.H, cfg.Hkv, cfg.D, max_len, api.SS_BF16),
                      dtype=torch.uint8, device=DEV)
     lm_ws = torch.empty(api.ss_lm_head_workspace_bytes(cfg.B * cfg.R, cfg.d_model, cfg.vocab, cfg.K, api.SS_BF16),
                         dtype=torch.uint8, device=DEV)
