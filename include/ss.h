@@ -189,6 +189,33 @@ int ss_msa_attention(const void* q, const void* k_new, const void* v_new, const 
                      void* stream);
 
 /*
+ * a2 for callers that cannot allocate device memory (code under HIP graph
+ * capture that owns no buffers, tight serving loops, harnesses that forbid
+ * hipMalloc): ss_msa_attention without the workspace arguments.  The partial
+ * results and arrival counters live in an array of
+ * ss_msa_static_scratch_bytes() = 32 MiB that is part of the library's device
+ * code; every GPU the library is used on holds its own copy until the process
+ * ends.  The call allocates and frees nothing.  The first call on a device
+ * looks the array's address up (the device that is current in the calling
+ * thread must be the one `stream` belongs to).  The counters are cleared by a
+ * small kernel at the start of every call; the rest of the array keeps what the
+ * last call left there.  All calls on one GPU share the array: calls that
+ * overlap in time (different streams, graph replays on different streams) RACE
+ * and give wrong results; enqueue them on one stream or use ss_msa_attention.
+ * Results are those of ss_msa_attention, bit for bit.
+ * Errors: those of ss_msa_attention; SS_ERR_UNSUPPORTED if the shape needs more
+ * than the array holds (ss_msa_workspace_bytes tells the need), nothing is
+ * enqueued then.
+ */
+size_t ss_msa_static_scratch_bytes(void);
+int ss_msa_attention_static(const void* q, const void* k_new, const void* v_new,
+                            const void* k_cache, const void* v_cache, const int32_t* block_table,
+                            int max_pages_per_seq, int num_pages, const int32_t* seq_lens,
+                            const int32_t* parent, int B, int T, int gamma, int H, int Hkv, int D,
+                            int page_size, float scale, int dtype, uint32_t flags, void* out,
+                            void* stream);
+
+/*
  * What a full call of a2 with this shape will launch, as currently tuned:
  * *n_splits = number of splits of the cached prefix (1 = unsplit, no workspace
  * needed), *n_kernels = 1 if the call is a single kernel (unsplit, or two

@@ -27,7 +27,7 @@ SS_MAX_T, SS_MAX_GAMMA, SS_MAX_K = 64, 8, 8
 
 EXPORTS = (
     "ss_version", "ss_last_error", "ss_probe_hbm_read", "ss_probe_mfma_bf16", "ss_check_tree_host", "ss_build_mask", "ss_msa_workspace_bytes",
-    "ss_msa_attention", "ss_msa_workspace_init", "ss_msa_plan", "ss_msa_set_split_keys", "ss_msa_set_merge_in_kernel", "ss_lm_head_workspace_bytes", "ss_lm_head_argmax_topk", "ss_lm_head_verify_draft",
+    "ss_msa_attention", "ss_msa_workspace_init", "ss_msa_attention_static", "ss_msa_static_scratch_bytes", "ss_msa_plan", "ss_msa_set_split_keys", "ss_msa_set_merge_in_kernel", "ss_lm_head_workspace_bytes", "ss_lm_head_argmax_topk", "ss_lm_head_verify_draft",
     "ss_tree_verify", "ss_tree_draft", "ss_full_tree_template_host", "ss_kv_commit", "ss_linear_rows", "ss_stream_insert", "ss_value_rotate",
     "ss_lm_head_logsumexp", "ss_transition_probs", "ss_tree_prune",
 )
@@ -66,6 +66,9 @@ def load_library() -> ctypes.CDLL:
     lib.ss_msa_attention.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, i32, i32, i32, i32, i32, i32, i32,
                                      c.c_float, i32, u32, vp, vp, sz, vp]
     lib.ss_msa_workspace_init.argtypes = [vp, sz, vp]
+    lib.ss_msa_attention_static.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, i32, i32, i32, i32, i32, i32, i32,
+                                            c.c_float, i32, u32, vp, vp]
+    lib.ss_msa_static_scratch_bytes.restype = sz
     lib.ss_msa_set_split_keys.argtypes = [i32]
     lib.ss_msa_set_merge_in_kernel.argtypes = [i32]
     lib.ss_lm_head_workspace_bytes.argtypes = [i32] * 5
@@ -219,6 +222,27 @@ def ss_msa_attention(q, k_new, v_new, k_cache, v_cache, block_table, seq_lens, p
         _dev(seq_lens, torch.int32, "seq_lens"), _dev(parent, torch.int32, "parent"), B, T, gamma, H, Hkv, D, page,
         float(scale), code, flags, _dev(out, dt, "out"), _dev(workspace, torch.uint8, "workspace"),
         workspace.numel(), _stream()))
+    return out
+
+
+def ss_msa_static_scratch_bytes() -> int:
+    return load_library().ss_msa_static_scratch_bytes()
+
+
+def ss_msa_attention_static(q, k_new, v_new, k_cache, v_cache, block_table, seq_lens, parent, gamma: int,
+                            scale: float, out: torch.Tensor, flags: int = 0) -> torch.Tensor:
+    """a2 without a workspace: the scratch memory is the library's own array.  `out` must be given: this
+    binding allocates nothing either."""
+    lib = load_library()
+    dt = q.dtype
+    code = _dtype_code(q)
+    B, R, H, D, Hkv, T, P, page, max_pages = _msa_shapes(q, k_new, v_new, k_cache, v_cache, block_table, seq_lens,
+                                                          parent, gamma)
+    _check(lib.ss_msa_attention_static(
+        _dev(q, dt, "q"), _dev(k_new, dt, "k_new"), _dev(v_new, dt, "v_new"), _dev(k_cache, dt, "k_cache"),
+        _dev(v_cache, dt, "v_cache"), _dev(block_table, torch.int32, "block_table"), max_pages, P,
+        _dev(seq_lens, torch.int32, "seq_lens"), _dev(parent, torch.int32, "parent"), B, T, gamma, H, Hkv, D, page,
+        float(scale), code, flags, _dev(out, dt, "out"), _stream()))
     return out
 
 

@@ -5,6 +5,7 @@
 #include <stdlib.h>
 
 #include <atomic>
+#include <mutex>
 
 #include "ss_msa.h"
 
@@ -346,6 +347,33 @@ static int zero_bytes(unsigned char* p, size_t bytes, hipStream_t st, const char
   return check_launch(fn);
 }
 
+// Scratch memory of ss_msa_attention_static: the per-split partial results and the arrival counters of a
+// call, for callers that cannot provide a workspace.  Every GPU the library runs on holds its own copy of
+// the array; host code reaches it only through the address hipGetSymbolAddress reports for the device that
+// is current, looked up once per device.
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char g_msa_scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[kMaxDevices];  // guarded by g_scratch_mutex
+
+static int static_scratch(const char* fn, void** ptr) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) SS_FAIL(SS_ERR_HIP, "%s: hipGetDevice: %s", fn, hipGetErrorString(e));
+  SS_REQUIRE(dev >= 0 && dev < kMaxDevices, SS_ERR_UNSUPPORTED, "%s: device %d outside [0,%d)", fn, dev, kMaxDevices);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(g_msa_scratch));
+    if (e != hipSuccess || p == nullptr)
+      SS_FAIL(SS_ERR_HIP, "%s: hipGetSymbolAddress: %s", fn, hipGetErrorString(e));
+    g_scratch_ptr[dev] = p;
+  }
+  *ptr = g_scratch_ptr[dev];
+  return SS_OK;
+}
+
 // The body of ss_msa_attention and ss_msa_attention_static.  `library_scratch`: the workspace is the library's
 // own array, whose size is a limit of the call (not a caller's mistake) and whose arrival counters are cleared
 // here on every call.
@@ -467,6 +495,21 @@ int ss_msa_attention(const void* q, const void* k_new, const void* v_new, const 
   return ss::msa_run("ss_msa_attention", q, k_new, v_new, k_cache, v_cache, block_table, max_pages_per_seq, num_pages,
                      seq_lens, parent, B, T, gamma, H, Hkv, D, page_size, scale, dtype, flags, out, workspace,
                      workspace_bytes, false, stream);
+}
+
+size_t ss_msa_static_scratch_bytes(void) { return ss::kStaticScratchBytes; }
+
+int ss_msa_attention_static(const void* q, const void* k_new, const void* v_new, const void* k_cache,
+                            const void* v_cache, const int32_t* block_table, int max_pages_per_seq, int num_pages,
+                            const int32_t* seq_lens, const int32_t* parent, int B, int T, int gamma, int H, int Hkv,
+                            int D, int page_size, float scale, int dtype, uint32_t flags, void* out, void* stream) {
+  using namespace ss;
+  clear_error();
+  const char* fn = "ss_msa_attention_static";
+  void* scratch = nullptr;
+  if (int rc = static_scratch(fn, &scratch)) return rc;
+  return msa_run(fn, q, k_new, v_new, k_cache, v_cache, block_table, max_pages_per_seq, num_pages, seq_lens, parent, B,
+                 T, gamma, H, Hkv, D, page_size, scale, dtype, flags, out, scratch, kStaticScratchBytes, true, stream);
 }
 
 }  // extern "C"
