@@ -223,7 +223,7 @@ static std::atomic<int> g_split_keys_override{0};
 static std::atomic<int> g_merge_in_kernel{1};
 
 struct MsaPlan {
-  int split_keys, split0_keys, n_splits, n_qc, groups;
+  int split_keys, split0_keys, n_splits, n_qc, groups, stages;
   size_t part_o_bytes, part_lse_bytes, arrive_bytes, total_bytes;
 };
 
@@ -232,12 +232,12 @@ struct MsaPlan {
 // the chip; no split is shorter than 256 cached tokens.
 //   fp32 kernel: splits for about 512 workgroups.
 //   MFMA kernel: with 512 or more (sequence, KV head, row chunk) items one workgroup of one wave group
-//   each, two resident per compute unit (measured best when lengths vary: the hardware evens them out);
-//   with fewer, three wave groups per workgroup (the prefix split again inside the workgroup and merged
-//   through LDS: 15 waves on a compute unit) and splits for about 256 workgroups; three wave groups also
-//   when a sequence has several row chunks (long GQA trees: the kernel is then bound by the matrix
-//   cores and more waves hide more latency).  The splits are equal shares of the prefix: the step's own
-//   rows, which split 0 also scans, are hidden in that split's set-up.
+//   each with a two-stage ring, three resident per compute unit (measured best when lengths vary: the
+//   hardware evens them out); with fewer, two wave groups per workgroup (the prefix split again inside the
+//   workgroup and merged through LDS) with three ring stages each, and splits for about 256 workgroups;
+//   three wave groups when a sequence has several row chunks (long GQA trees: the kernel is then bound by
+//   the matrix cores and more waves hide more latency).  Split 0 also scans the step's own rows and gets
+//   that much less of the prefix.
 // Tuning aid: blocks' worth of time, beyond its ceil(R/32) blocks, that scanning the step's own rows costs
 // split 0 (SS_MSA_SPLIT0_EXTRA, read once).
 static int split0_extra_blocks() {
@@ -254,6 +254,7 @@ static MsaPlan make_plan(int B, int R, int H, int Hkv, int D, int max_len, int d
   const int g = H / Hkv;
   int base;
   p.groups = 1;
+  p.stages = 2;
   if (dtype == SS_BF16) {
     const int rows = msa_bf16_rows_per_chunk(g * R);
     p.n_qc = ceil_div(g * R, rows);
@@ -270,10 +271,12 @@ static MsaPlan make_plan(int B, int R, int H, int Hkv, int D, int max_len, int d
   int want_wgs = 512;
   if (dtype == SS_BF16) {
     if (base < 512) {
-      p.groups = 3;
+      p.groups = 2;
+      p.stages = 3;
       want_wgs = 256;
     } else if (p.n_qc > 1) {
       p.groups = 3;
+      p.stages = 3;
     }
   }
   if (split_keys <= 0) {
@@ -419,7 +422,7 @@ static int msa_run(const char* fn, const void* q, const void* k_new, const void*
   a.B = B; a.T = T; a.gamma = gamma; a.R = R; a.H = H; a.Hkv = Hkv; a.g = H / Hkv; a.D = D;
   a.page = page_size; a.page_shift = page_size == 16 ? 4 : (page_size == 32 ? 5 : 6);
   a.max_pages = max_pages_per_seq; a.num_pages = num_pages;
-  a.split_keys = plan.split_keys; a.split0_keys = plan.split0_keys; a.n_splits = plan.n_splits; a.n_qc = plan.n_qc; a.groups = plan.groups;
+  a.split_keys = plan.split_keys; a.split0_keys = plan.split0_keys; a.n_splits = plan.n_splits; a.n_qc = plan.n_qc; a.groups = plan.groups; a.stages = plan.stages;
   a.scale_log2 = scale * 1.4426950408889634f;
   // In-kernel merge (MFMA path, two splits): the second split of a (sequence, head) to finish adds the other's
   // partial rows to its own and writes the output, which saves the merge kernel and its kernel boundary.  With

@@ -53,6 +53,7 @@
 // ragged block (owned by whichever split holds the end of the sequence) comes last.
 #include <stdlib.h>
 
+#include <mutex>
 #include <type_traits>
 
 #include "ss_msa.h"
@@ -122,28 +123,68 @@ SS_DEV uintx2 lds_read_tr16(const unsigned char* p) {
   return __builtin_bit_cast(uintx2, v);
 }
 
+// 16 bytes per lane from (sbase + voff) straight into LDS: lane l's piece lands at lds_addr + 16*l.  No
+// staging register and no LDS store instruction; the load counts in the issuing wave's vector-memory
+// counter and completes in issue order.  STREAM adds the streaming hint (data no other workgroup asks for).
+template <bool STREAM>
+SS_DEV void dma16(const void* sbase, uint32_t voff, uint32_t lds_addr) {
+  if constexpr (STREAM)
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %0 nt" ::"s"(sbase), "v"(voff), "s"(lds_addr) : "memory", "m0");
+  else
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %0" ::"s"(sbase), "v"(voff), "s"(lds_addr) : "memory", "m0");
+}
+// Waits until at most `units` blocks' worth of this wave's direct-to-LDS loads (LPB per block) are outstanding.
+// The counter has 6 bits; a smaller number than asked for only waits longer.
+template <int N>
+SS_DEV void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N < 63 ? N : 63) : "memory");
+}
+template <int LPB>
+SS_DEV void wait_vm_units(int units) {
+  switch (units) {
+    case 0: wait_vmcnt<0>(); break;
+    case 1: wait_vmcnt<LPB>(); break;
+    case 2: wait_vmcnt<2 * LPB>(); break;
+    case 3: wait_vmcnt<3 * LPB>(); break;
+    case 4: wait_vmcnt<4 * LPB>(); break;
+    case 5: wait_vmcnt<5 * LPB>(); break;
+    case 6: wait_vmcnt<6 * LPB>(); break;
+    case 7: wait_vmcnt<7 * LPB>(); break;
+    case 8: wait_vmcnt<8 * LPB>(); break;
+    case 9: wait_vmcnt<9 * LPB>(); break;
+    case 10: wait_vmcnt<10 * LPB>(); break;
+    case 11: wait_vmcnt<11 * LPB>(); break;
+    case 12: wait_vmcnt<12 * LPB>(); break;
+    case 13: wait_vmcnt<13 * LPB>(); break;
+    case 14: wait_vmcnt<14 * LPB>(); break;
+    default: wait_vmcnt<15 * LPB>(); break;
+  }
+}
+constexpr int kMaxStages = 10;  // ring stages per wave group: at most kMaxStages - 1 blocks in flight per group
+
 // NW = waves (query tiles) per group; it only fixes how the 1 KB load slots of a unit are dealt to
-// the waves of a group.  The number of groups is a launch parameter.
+// the waves of a group.  The number of groups and the ring depth are launch parameters.
 // STREAM: the cache is loaded with the streaming hint.  Right when a (sequence, KV head, split) has one row
 // chunk, so that every byte of the cache is wanted by exactly one workgroup; with several row chunks (long GQA
 // trees) the chunks share K/V through the L2 and the hint undoes that (measured: +25 % time).
 template <int D, int NW, bool STREAM>
-__global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves / NW : kMaxGroups)) void msa_bf16_kernel(MsaArgs a, int n_groups) {
+__global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves / NW : kMaxGroups)) void msa_bf16_kernel(MsaArgs a, int n_groups, int n_stages) {
   constexpr int KS = D / 32, DT = D / 16;
   constexpr int K_BYTES = 32 * D * 2;          // K rows of a unit (V takes the same)
   constexpr int STAGE_BYTES = 2 * K_BYTES;
   constexpr int K_SLOTS = K_BYTES / 1024;      // 1 KB load slots of a unit's K rows (V: as many)
   constexpr int LW = NW >= 4 ? 4 : NW >= 2 ? 2 : 1;  // waves of a group that move data: divides K_SLOTS
   constexpr int KJ = K_SLOTS / LW;             // K slots per loading wave, and V slots per loading wave
+  constexpr int LPB = 2 * KJ;                  // loads per block and loading wave
   constexpr int CPR = D / 8;                   // 16-byte chunks per K row
   constexpr int ROWS_PER_SLOT = 64 / CPR;
   constexpr int V_DBLK = K_SLOTS / 2;          // 32-feature blocks per 16-key half of the V tile
-  constexpr int VROW = 64;                     // bytes per feature row of the V tile (32 keys)
+  constexpr int VHALF = D * 32;                // bytes of one 16-key half of the V tile: D feature rows of 32 bytes
 
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  // smem: [n_groups][2][STAGE_BYTES] stages (reused by the final merge) | par | anc | ml
+  // smem: [n_groups][n_stages][STAGE_BYTES] ring stages (reused by the final merge) | par | anc | ml
   unsigned char* stages = smem;
-  int* par = reinterpret_cast<int*>(smem + (size_t)n_groups * 2 * STAGE_BYTES);
+  int* par = reinterpret_cast<int*>(smem + (size_t)n_groups * n_stages * STAGE_BYTES);
   uint64_t* anc = reinterpret_cast<uint64_t*>(par + SS_MAX_T);
   float* ml = reinterpret_cast<float*>(anc + SS_MAX_T);  // [n_groups][NW][2][16]: max, sum per query
 
@@ -165,27 +206,24 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int grp = w / NW, wt = w % NW;  // wave group, query tile of this wave
   const int R = a.R, T = a.T, F = a.g * R;
-  // Cached tokens [k0, k0 + split_keys) clipped to the sequence.  Nothing up to the first loads depends on
-  // the sequence length (it is fetched in parallel with them): page ids and the first block are fetched
-  // from clamped, always valid positions.
-  const int k0 = split_begin(s, a);
+  const int k0 = split_begin(s, a);     // this split's cached tokens are [k0, k1)
   const float c = a.scale_log2;
 
   const uint16_t* q = (const uint16_t*)a.q;
-  const uint16_t* k_new = (const uint16_t*)a.k_new;
-  const uint16_t* v_new = (const uint16_t*)a.v_new;
   const int32_t* my_table = a.block_table + (size_t)b * a.max_pages;
   const size_t page_stride = (size_t)a.Hkv * a.page * D;  // elements per physical page (K and V alike)
   const uint16_t* k_head = (const uint16_t*)a.k_cache + (size_t)hk * a.page * D;  // this head inside page 0
   const uint16_t* v_head = (const uint16_t*)a.v_cache + (size_t)hk * a.page * D;
   const int pmask = a.page - 1;
 
-  unsigned char* my_stages = stages + (size_t)grp * 2 * STAGE_BYTES;
+  unsigned char* my_stages = stages + (size_t)grp * n_stages * STAGE_BYTES;
+  const uint32_t lds_stages = (uint32_t)(uintptr_t)my_stages;
 
+  // ---- first round trip: page ids, sequence length, tree, queries.
   // Physical pages of the two 16-key halves of this group's main-loop units (equal for pages of 32
-  // or 64 tokens; positions past the table are clamped, such units are never used).  Lane i of every wave keeps the pair for loop iteration jbase + i; one gather
-  // serves 64 iterations and a page id reaches the scalar unit through a lane read, so that no
-  // memory wait sits between issuing a unit's loads and computing on the previous unit.
+  // or 64 tokens; positions past the table are clamped, such units are never used).  Lane i of every
+  // wave keeps the pair for loop iteration jbase + i; one gather serves 64 iterations and a page id
+  // reaches the scalar unit through a lane read.
   int tab_a = 0, tab_b = 0;
   const int key_cap = max(a.max_pages * a.page - 32, 0) & ~31;  // last 32-key block the table covers
   auto refill_pages = [&](int jbase) {
@@ -194,10 +232,10 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
     tab_b = min(max(my_table[min((kb + 16) >> a.page_shift, a.max_pages - 1)], 0), a.num_pages - 1);
   };
   refill_pages(0);
-  const int par_v = tid < T ? clamp_parent(a.parent[(size_t)b * T + tid], tid) : 0;
+  const int L_raw = a.seq_lens[b];
+  int par_v = tid < T ? clamp_parent(a.parent[(size_t)b * T + tid], tid) : 0;
 
-  // ---- this wave's query tile: MFMA B operands (lane (lq, lg) holds features 8*(4*ks+lg).. of
-  // folded query row f)
+  // this wave's query tile: MFMA B operands (lane (lq, lg) holds features 8*(4*ks+lg).. of folded query row f)
   const int f = qc * (16 * NW) + 16 * wt + lq;
   const bool f_valid = f < F;
   const int q_r = f_valid ? f % R : 0, q_h = hk * a.g + (f_valid ? f / R : 0);
@@ -217,41 +255,39 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
   for (int dt = 0; dt < DT; ++dt) O[dt] = floatx4{0.f, 0.f, 0.f, 0.f};
   float m_run = -1e30f, l_run = 0.f;
 
-  // ---- per-lane and per-slot parts of the main loop's addresses (loop invariant).  A unit is moved
-  // in 1 KB slots.  K slot sl: rows ROWS_PER_SLOT*sl + lane/CPR, chunk position p = lane%CPR holding
-  // chunk p ^ k_swz(row).  V slot s2: 8-key chunks
-  // kc = 2*half + (lane&1) of features dblk*32 + lane/2, half = s2 / V_DBLK, dblk = s2 % V_DBLK.
+  // ---- how a block reaches LDS.  A unit is moved in 1 KB slots, one direct-to-LDS load each: K slot sl
+  // holds rows ROWS_PER_SLOT*sl + lane/CPR, the lane at chunk position p = lane%CPR fetching chunk
+  // p ^ k_swz(row).  The V tile consists of two halves of 16 keys, each D feature rows of 32 bytes; V slot
+  // s2 holds features dblk*32 + lane/2 of half s2 / V_DBLK (dblk = s2 % V_DBLK), the lane at position
+  // lane&1 fetching the 8-key chunk (lane&1) ^ ((feature >> 3) & 1), which makes the 16-lane operand reads
+  // (16 features x 16 bytes) hit 64 different banks.  In a feature-major page a slot is one contiguous KB.
   // The first LW waves of a group move the data: wave wt takes K slots and V slots wt + LW*j.
   const int ril = lane / CPR, pch = lane % CPR;
   const bool loader = wt < LW;
-  const int v_dst0 = K_BYTES + (lane >> 1) * VROW + ((((lane & 1)) ^ ((lane >> 2) & 3)) * 16);      // half 0
-  const int v_dst1 = K_BYTES + (lane >> 1) * VROW + (((2 + (lane & 1)) ^ ((lane >> 2) & 3)) * 16);  // half 1
-  const int v_lsrc = (lane >> 1) * a.page + (lane & 1) * 8;  // element offset inside a (page, feature block)
-  int k_lsrc[KJ], k_ldst[KJ], v_ldst[KJ];                    // per lane
-  int k_soff[KJ], v_soff[KJ];                                // scalar element offsets from the half's base
+  const int wl = loader ? wt : 0;
+  uint32_t k_voff[KJ];            // per lane, bytes from the slot's scalar base
+  int k_soff[KJ], v_soff[KJ];     // scalar element offsets from the half's base
   bool k_second[KJ], v_second[KJ];
 #pragma unroll
   for (int j = 0; j < KJ; ++j) {
-    const int sl = (loader ? wt : 0) + LW * j, r0 = ROWS_PER_SLOT * sl;
+    const int sl = wl + LW * j, r0 = ROWS_PER_SLOT * sl;
     k_second[j] = r0 >= 16;
     k_soff[j] = (r0 & 15) * D;
-    k_lsrc[j] = ril * D + ((pch ^ k_swz<D>(r0 + ril)) * 8);
-    k_ldst[j] = sl * 1024 + lane * 16;
-    const int half = sl / V_DBLK, dblk = sl % V_DBLK;
-    v_second[j] = half != 0;
-    v_soff[j] = dblk * 32 * a.page;
-    v_ldst[j] = dblk * (32 * VROW) + (half ? v_dst1 : v_dst0);
+    k_voff[j] = 2u * (uint32_t)(ril * D + ((pch ^ k_swz<D>(r0 + ril)) * 8));
+    v_second[j] = sl / V_DBLK != 0;
+    v_soff[j] = (sl % V_DBLK) * 32 * a.page;
   }
-  // operand reads: K row of score tile 0 (tile 1 is 4 rows further, same swizzle), chunk 4*ks + lg; V row
+  const uint32_t v_voff = 2u * (uint32_t)((lane >> 1) * a.page + (((lane & 1) ^ ((lane >> 4) & 1)) * 8));
+  // operand reads: K row of score tile 0 (tile 1 is 4 rows further, same swizzle), chunk 4*ks + lg; V:
+  // feature 16*dt + lq, keys 8*lg .. 8*lg+7
   const int rr0 = block_key(lq, 0);
   int k_rd[KS];
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) k_rd[ks] = rr0 * (2 * D) + (((4 * ks + lg) ^ k_swz<D>(rr0)) * 16);
-  const int v_rd = K_BYTES + lq * VROW + ((lg ^ ((lq >> 1) & 3)) * 16);
+  const int v_rd = K_BYTES + (lg >> 1) * VHALF + lq * 32 + (((lg & 1) ^ ((lq >> 3) & 1)) * 16);
 
-  // Main-loop unit u (a full block of the prefix) -> registers: scalar base per half, 16 bytes per lane.
-  uintx4 stg[2 * KJ];
-  auto load_main = [&](int u, int pg_a, int pg_b) {
+  // Main-loop unit u (a full block of the prefix) -> LDS stage at st_addr: scalar base per half.
+  auto dma_main = [&](int u, int pg_a, int pg_b, uint32_t st_addr) {
     const int kb = k0 + 32 * u;
     const int o_a = kb & pmask, o_b = (kb + 16) & pmask;
     const size_t g_a = (size_t)pg_a * page_stride, g_b = (size_t)pg_b * page_stride;
@@ -260,90 +296,104 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
     const uint16_t* va = v_head + g_a + o_a;
     const uint16_t* vb = v_head + g_b + o_b;
 #pragma unroll
-    for (int j = 0; j < KJ; ++j) stg[j] = ld16_cache<STREAM>((k_second[j] ? kb2 : ka) + k_soff[j] + k_lsrc[j]);
+    for (int j = 0; j < KJ; ++j)
+      dma16<STREAM>((k_second[j] ? kb2 : ka) + k_soff[j], k_voff[j], st_addr + (wl + LW * j) * 1024);
 #pragma unroll
-    for (int j = 0; j < KJ; ++j) stg[KJ + j] = ld16_cache<STREAM>((v_second[j] ? vb : va) + v_soff[j] + v_lsrc);
+    for (int j = 0; j < KJ; ++j)
+      dma16<STREAM>((v_second[j] ? vb : va) + v_soff[j], v_voff, st_addr + K_BYTES + (wl + LW * j) * 1024);
   };
-  auto store_main = [&](unsigned char* st) {
-#pragma unroll
-    for (int j = 0; j < KJ; ++j) *reinterpret_cast<uintx4*>(st + k_ldst[j]) = stg[j];
-#pragma unroll
-    for (int j = 0; j < KJ; ++j) *reinterpret_cast<uintx4*>(st + v_ldst[j]) = stg[KJ + j];
-  };
-
-  // ---- units that are not full prefix blocks: the step's own rows (is_new; base = first row of the
-  // unit) and the ragged last block of the prefix (base = its first cached token).  Addresses are per
-  // lane here, clamped to existing keys / rows; what is read in excess is masked.  The lane id is
-  // laundered wherever addresses are formed, so that none of this arithmetic is kept in registers
-  // across the main loop.
-  auto load_special = [&](uintx4 (&dst)[2 * KJ], bool is_new, int base, int last) {
+  // Rows c0 .. c0+31 of the step's own block -> LDS stage at st_addr: K rows as above, V rows token-major
+  // (row r at 2*D*r, chunk position p holding chunk p ^ 2*(r&3)) for the transposing operand read.  Rows past
+  // R repeat the last one (they are masked).  The lane id is laundered so that none of this arithmetic is
+  // kept in registers across the main loop.
+  auto dma_new = [&](int c0, uint32_t st_addr) {
     int lane2 = lane;
     asm volatile("" : "+v"(lane2));
     const int ril2 = lane2 / CPR, pch2 = lane2 % CPR;
+    const size_t head0 = ((size_t)b * R * a.Hkv + hk) * D;  // elements to row 0 of this sequence and head
+    const uint16_t* kn = (const uint16_t*)a.k_new + head0;
+    const uint16_t* vn = (const uint16_t*)a.v_new + head0;
 #pragma unroll
     for (int j = 0; j < KJ; ++j) {
-      const int sl = wt + LW * j;
+      const int sl = wl + LW * j;
       const int rr = ROWS_PER_SLOT * sl + ril2;
-      const uint16_t *ksrc, *vsrc;
-      if (!is_new) {
-        const int key = min(base + rr, last);
-        const int pg = min(max(my_table[key >> a.page_shift], 0), a.num_pages - 1);
-        ksrc = k_head + (size_t)pg * page_stride + (size_t)(key & pmask) * D;
-        const int half = sl / V_DBLK, dblk = sl % V_DBLK;
-        const int vkey = min(base + 16 * half + (lane2 & 1) * 8, last & ~7);
-        const int vpg = min(max(my_table[vkey >> a.page_shift], 0), a.num_pages - 1);
-        vsrc = v_head + (size_t)vpg * page_stride + (size_t)(dblk * 32 + (lane2 >> 1)) * a.page + (vkey & pmask);
-      } else {
-        const size_t row = ((size_t)b * R + min(base + rr, R - 1)) * a.Hkv + hk;
-        ksrc = k_new + row * D;
-        vsrc = v_new + row * D + pch2 * 8;
-      }
-      dst[j] = ld16(ksrc + ((pch2 ^ k_swz<D>(rr)) * 8));
-      dst[KJ + j] = ld16(vsrc);
+      const uint32_t row_off = (uint32_t)min(c0 + rr, R - 1) * (uint32_t)(a.Hkv * D * 2);
+      dma16<false>(kn, row_off + (uint32_t)((pch2 ^ k_swz<D>(rr)) * 16), st_addr + sl * 1024);
+      dma16<false>(vn, row_off + (uint32_t)((pch2 ^ (2 * (rr & 3))) * 16), st_addr + K_BYTES + sl * 1024);
     }
   };
-  auto store_special = [&](const uintx4 (&src)[2 * KJ], bool is_new, unsigned char* st) {
+
+  // ---- the ragged last block of the prefix goes through registers (per-lane page lookups, clamped to
+  // existing keys; what is read in excess is masked).  base = its first cached token, last = the last one.
+  uintx4 stg[2 * KJ];
+  auto load_ragged = [&](int base, int last) {
     int lane2 = lane;
     asm volatile("" : "+v"(lane2));
     const int ril2 = lane2 / CPR, pch2 = lane2 % CPR;
 #pragma unroll
     for (int j = 0; j < KJ; ++j) {
-      const int sl = wt + LW * j;
-      *reinterpret_cast<uintx4*>(st + sl * 1024 + lane2 * 16) = src[j];
-      if (!is_new) {
-        const int half = sl / V_DBLK, dblk = sl % V_DBLK;
-        const int chunk = (2 * half + (lane2 & 1)) ^ ((lane2 >> 2) & 3);
-        *reinterpret_cast<uintx4*>(st + K_BYTES + (dblk * 32 + (lane2 >> 1)) * VROW + chunk * 16) = src[KJ + j];
-      } else {
-        const int rr = ROWS_PER_SLOT * sl + ril2;
-        *reinterpret_cast<uintx4*>(st + K_BYTES + rr * (2 * D) + ((pch2 ^ (2 * (rr & 3))) * 16)) = src[KJ + j];
-      }
+      const int sl = wl + LW * j;
+      const int rr = ROWS_PER_SLOT * sl + ril2;
+      const int key = min(base + rr, last);
+      const int pg = min(max(my_table[key >> a.page_shift], 0), a.num_pages - 1);
+      const uint16_t* ksrc = k_head + (size_t)pg * page_stride + (size_t)(key & pmask) * D;
+      const int half = sl / V_DBLK, dblk = sl % V_DBLK;
+      const int vkey = min(base + 16 * half + (lane2 & 1) * 8, last & ~7);
+      const int vpg = min(max(my_table[vkey >> a.page_shift], 0), a.num_pages - 1);
+      const uint16_t* vsrc = v_head + (size_t)vpg * page_stride + (size_t)(dblk * 32 + (lane2 >> 1)) * a.page + (vkey & pmask);
+      stg[j] = ld16(ksrc + ((pch2 ^ k_swz<D>(rr)) * 8));
+      stg[KJ + j] = ld16(vsrc);
+    }
+  };
+  auto store_ragged = [&](unsigned char* st) {
+    int lane2 = lane;
+    asm volatile("" : "+v"(lane2));
+#pragma unroll
+    for (int j = 0; j < KJ; ++j) {
+      const int sl = wl + LW * j;
+      *reinterpret_cast<uintx4*>(st + sl * 1024 + lane2 * 16) = stg[j];
+      const int half = sl / V_DBLK, fr = (sl % V_DBLK) * 32 + (lane2 >> 1);
+      *reinterpret_cast<uintx4*>(st + K_BYTES + half * VHALF + fr * 32 + (((lane2 & 1) ^ ((fr >> 3) & 1)) * 16)) = stg[KJ + j];
     }
   };
 
-  // ---- prologue.  In flight at once: the page ids (issued above), the sequence length, the tree, this
-  // wave's queries, split 0's first block of the step's own rows, and, as soon as the page ids are
-  // here, this group's first block of the prefix (harmless if it turns out not to exist).
-  const int L_raw = a.seq_lens[b];
+  // Split 0's first block of the step's own rows travels with the first round trip (its addresses need
+  // nothing from memory), into the last ring stage, which the main loop does not fill before its first barrier.
   const bool has_new = s == 0;  // every sequence has a split 0
   const int n_new_units = (R + 31) >> 5;
-  uintx4 stn[2 * KJ];
-  if (has_new && loader && grp < n_new_units) load_special(stn, true, 32 * grp, 0);
-  if (loader) load_main(grp, __builtin_amdgcn_readlane(tab_a, 0), __builtin_amdgcn_readlane(tab_b, 0));
+  const uint32_t new_stage = lds_stages + (uint32_t)(n_stages - 1) * STAGE_BYTES;
+  if (has_new && loader && grp < n_new_units) dma_new(32 * grp, new_stage);
+
+  // ---- what there is to do.  The sequence length arrives with the page ids.
+  const int L = clamp_len(L_raw, a);
+  const int n_active = active_splits(L, a);
+  if (s >= n_active) return;
+  const int k1 = max(k0, min(L, k0 + split_len(s, a)));
+  // Units of this split: full 32-key blocks of the prefix (ring-buffered main loop of n_main iterations,
+  // one block per group and iteration; group grp has n_mine of them) and its ragged last block.
+  const int n_full = (k1 - k0) >> 5;
+  const int tail = (k1 - k0) & 31;
+  const int n_main = (n_full + n_groups - 1) / n_groups;
+  const int n_mine = grp < n_full ? (n_full - grp + n_groups - 1) / n_groups : 0;
+
+  // Everything loaded so far is waited for here, before the first direct-to-LDS load is issued: the
+  // compiler knows nothing of those loads, and a wait it places later for one of its own would wait for
+  // all of them too.
+  asm volatile("s_waitcnt vmcnt(0)" : "+v"(tab_a), "+v"(tab_b), "+v"(par_v)::"memory");
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(Qr[ks]));
+
+  // ---- second round trip: the first blocks of the prefix.
+  const int n_pre = min(n_mine, n_stages - 1);
+  if (loader)
+    for (int i = 0; i < n_pre; ++i)
+      dma_main(grp + i * n_groups, __builtin_amdgcn_readlane(tab_a, i), __builtin_amdgcn_readlane(tab_b, i),
+               lds_stages + (uint32_t)i * STAGE_BYTES);
   if (tid < T) par[tid] = par_v;
   __syncthreads();
   compute_anc(par, T, anc, tid);
   __syncthreads();
 
-  const int L = clamp_len(L_raw, a);
-  const int n_active = active_splits(L, a);
-  if (s >= n_active) return;
-  const int k1 = max(k0, min(L, k0 + split_len(s, a)));
-  // Units of this split: full 32-key blocks of the prefix (pipelined main loop, n_main iterations with
-  // one block per group; in the last iteration some groups may have none) and its ragged last block.
-  const int n_full = (k1 - k0) >> 5;
-  const int tail = (k1 - k0) & 31;
-  const int n_main = (n_full + n_groups - 1) / n_groups;
   const RowVis no_vis = RowVis{0, 0, 0};
   // One unit out of an LDS stage: scores, softmax update, O += P V.  `full` (a compile-time flag) is
   // the unmasked main-loop flavour; otherwise the unit is the ragged block of the prefix, or (is_new)
@@ -409,14 +459,14 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
     if (FULL) {
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt) {
-        const uintx4 vv = *reinterpret_cast<const uintx4*>(st + v_rd + dt * (16 * VROW));
+        const uintx4 vv = *reinterpret_cast<const uintx4*>(st + v_rd + dt * 512);
         O[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vv), P, O[dt], 0, 0, 0);
       }
     } else if (!is_new) {
       const int nv = min(max(tail - 8 * mg, 0), 8);  // how many of this lane's 8 tokens exist
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt) {
-        uintx4 vv = *reinterpret_cast<const uintx4*>(st + v_rd + dt * (16 * VROW));
+        uintx4 vv = *reinterpret_cast<const uintx4*>(st + v_rd + dt * 512);
 #pragma unroll
         for (int e = 0; e < 4; ++e) vv[e] &= nv >= 2 * e + 2 ? 0xffffffffu : (nv == 2 * e + 1 ? 0x0000ffffu : 0u);
         O[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vv), P, O[dt], 0, 0, 0);
@@ -438,55 +488,54 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
     }
   };
 
-  // ---- the step's own rows (split 0), through stage 1 of the group while the first prefix block is
-  // still on its way into registers.  One block per group and round.
+  // ---- the step's own rows (split 0), one block per group and round, while the first prefix blocks
+  // are on their way.
   if (has_new) {
     const RowVis vis = make_row_vis(q_r, T, a.gamma, anc, (a.flags & SS_STREAM_EXCLUDE_SELF) != 0);
-    unsigned char* st1 = my_stages + STAGE_BYTES;
     for (int jn = 0; jn * n_groups < n_new_units; ++jn) {
       const int un = jn * n_groups + grp;
       const bool mine = un < n_new_units;
-      if (jn > 0) __syncthreads();  // the previous round's block has been consumed
-      if (loader && mine) store_special(stn, true, st1);
-      if (loader && un + n_groups < n_new_units) load_special(stn, true, 32 * (un + n_groups), 0);  // next round's
+      if (jn > 0) {
+        __syncthreads();  // the previous round's block has been consumed
+        if (loader && mine) dma_new(32 * un, new_stage);
+      }
+      // round 0: only the prefix blocks issued after it may still be in flight; later rounds: nothing
+      if (loader && mine) wait_vm_units<LPB>(jn == 0 ? n_pre : 0);
       __syncthreads();
-      if (mine) compute(std::false_type{}, true, 32 * un, st1, vis);
+      if (mine) compute(std::false_type{}, true, 32 * un, my_stages + (size_t)(n_stages - 1) * STAGE_BYTES, vis);
     }
   }
 
-  // ---- main loop over full blocks of the prefix: while a group computes on one LDS stage, its waves
-  // hold the next unit in registers (loads issued at the top), write it to the other stage after the
-  // compute, and one barrier per unit publishes it.
-  if (n_main > 0 && loader) store_main(my_stages);
-  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): nothing from the prologue (Q, page ids) is pending inside the loop
-  __syncthreads();
-  for (int it = 0; it + 1 < n_main; ++it) {
-    const int u = grp + it * n_groups;
-    const int jn = it + 1;
-    if ((jn & 63) == 0) refill_pages(jn);
-    if (loader)
-      load_main(u + n_groups, __builtin_amdgcn_readlane(tab_a, jn & 63), __builtin_amdgcn_readlane(tab_b, jn & 63));
-    compute(std::true_type{}, false, 0, my_stages + (it & 1) * STAGE_BYTES, no_vis);
-    if (loader) store_main(my_stages + (jn & 1) * STAGE_BYTES);
-    __syncthreads();  // the next stage is complete, this one may be overwritten after the next barrier
-  }
-  // (the last main-loop unit is computed below, with the ragged block, if any, already in flight)
-
-  // ---- the ragged last block of the prefix: group 0's, loaded while the last main-loop unit is computed
+  // ---- main loop over full blocks of the prefix.  Ring of n_stages stages per group, n_stages - 1 blocks
+  // in flight: iteration `it` waits for its own block (loads complete in order), one barrier publishes it
+  // and tells that the stage of iteration it - 1 has been consumed, which the block of iteration
+  // it + n_stages - 1 then goes to.
+  const bool rag_mine = tail != 0 && grp == 0;  // group 0 has a block in every iteration
+  const int rag_base = k0 + 32 * n_full;
+  if (n_main == 0 && rag_mine && loader) load_ragged(rag_base, k1 - 1);
   {
-    const bool rag_mine = tail != 0 && grp == 0;
-    const int rag_base = k0 + 32 * n_full;
-    if (rag_mine && loader) load_special(stg, false, rag_base, k1 - 1);
-    if (n_main > 0) {
-      const int u_last = grp + (n_main - 1) * n_groups;
-      if (u_last < n_full) compute(std::true_type{}, false, 0, my_stages + ((n_main - 1) & 1) * STAGE_BYTES, no_vis);
-    }
-    if (tail != 0) {
-      __syncthreads();  // the stages are free
-      if (rag_mine && loader) store_special(stg, false, my_stages);
+    int st_comp = 0, st_fill = n_stages - 1;  // ring positions of iteration it and of iteration it + n_stages - 1
+    for (int it = 0; it < n_main; ++it) {
+      if (loader && it < n_mine) wait_vm_units<LPB>(min(n_mine - 1 - it, n_stages - 2));
       __syncthreads();
-      if (rag_mine) compute(std::false_type{}, false, 0, my_stages, no_vis);
+      const int jl = it + n_stages - 1;
+      if (loader && jl < n_mine) {
+        if ((jl & 63) == 0) refill_pages(jl);
+        dma_main(grp + jl * n_groups, __builtin_amdgcn_readlane(tab_a, jl & 63), __builtin_amdgcn_readlane(tab_b, jl & 63),
+                 lds_stages + (uint32_t)st_fill * STAGE_BYTES);
+      }
+      if (it == n_main - 1 && rag_mine && loader) load_ragged(rag_base, k1 - 1);  // nothing else is in flight now
+      if (it < n_mine) compute(std::true_type{}, false, 0, my_stages + (size_t)st_comp * STAGE_BYTES, no_vis);
+      st_comp = st_comp + 1 == n_stages ? 0 : st_comp + 1;
+      st_fill = st_fill + 1 == n_stages ? 0 : st_fill + 1;
     }
+  }
+  // ---- the ragged last block of the prefix (group 0), loaded while the last main-loop unit was computed
+  if (tail != 0) {
+    __syncthreads();  // the stages are free
+    if (rag_mine && loader) store_ragged(my_stages);
+    __syncthreads();
+    if (rag_mine) compute(std::false_type{}, false, 0, my_stages, no_vis);
   }
 
   // ---- merge the groups.  Every wave reduces its sum over the four lane groups; groups > 0 leave
@@ -627,19 +676,28 @@ int msa_bf16_rows_per_chunk(int F) {
   return best;
 }
 
-// Wave groups per workgroup for NW query tiles: what the plan asks for (or the SS_MSA_GROUPS tuning
-// override), as far as kMaxWaves waves allow.
+// Wave groups per workgroup for NW query tiles and ring stages per group: what the plan asks for (or the
+// SS_MSA_GROUPS / SS_MSA_STAGES tuning overrides, read once), as far as kMaxWaves waves, the LDS of a compute
+// unit and the 6-bit load counter allow (lpb = loads per block of a loading wave).
+static int env_int_once(const char* name, int lo, int hi) {
+  const char* e = getenv(name);
+  const int v = e ? atoi(e) : 0;
+  return (v >= lo && v <= hi) ? v : 0;
+}
 static int groups_for(int nw, int wanted) {
-  static const int forced = []() {
-    const char* e = getenv("SS_MSA_GROUPS");
-    const int v = e ? atoi(e) : 0;
-    return (v >= 1 && v <= kMaxGroups) ? v : 0;
-  }();
+  static const int forced = env_int_once("SS_MSA_GROUPS", 1, kMaxGroups);
   int cap = kMaxWaves / nw;
   if (cap > kMaxGroups) cap = kMaxGroups;
   int g = forced ? forced : wanted;
   if (g > cap) g = cap;
   return g < 1 ? 1 : g;
+}
+static int stages_for(int n_groups, int wanted, size_t stage_bytes, int lpb) {
+  static const int forced = env_int_once("SS_MSA_STAGES", 2, kMaxStages);
+  int n = forced ? forced : wanted;
+  if (n > kMaxStages) n = kMaxStages;
+  while (n > 2 && ((size_t)n_groups * n * stage_bytes > 144 * 1024 || (n - 1) * lpb > 60)) --n;
+  return n < 2 ? 2 : n;
 }
 
 template <int D, int NW, bool STREAM>
@@ -649,19 +707,21 @@ static int launch_dns(const MsaArgs& a, hipStream_t stream) {
   const long wgs = (long)ceil_div(G, 8) * 8 * a.n_qc;
   SS_REQUIRE(wgs <= 0x7fffffffL, SS_ERR_UNSUPPORTED, "ss_msa_attention: grid too large");
   const size_t stage_bytes = 2 * 32 * D * 2;
+  constexpr int lw = NW >= 4 ? 4 : NW >= 2 ? 2 : 1;
+  const int n_stages = stages_for(n_groups, a.stages, stage_bytes, 2 * (32 * D * 2 / 1024) / lw);
   const size_t merge_bytes = (size_t)(n_groups - 1) * NW * (D / 16) * 64 * 16;
-  size_t lds = (size_t)n_groups * 2 * stage_bytes;
+  size_t lds = (size_t)n_groups * n_stages * stage_bytes;
   if (merge_bytes > lds) lds = merge_bytes;
   lds += SS_MAX_T * 4 + SS_MAX_T * 8 + (size_t)n_groups * NW * 32 * 4;
   auto kern = msa_bf16_kernel<D, NW, STREAM>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e != hipSuccess) SS_FAIL(SS_ERR_HIP, "ss_msa_attention: hipFuncSetAttribute: %s", hipGetErrorString(e));
-    attr_set = true;
-  }
-  hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(64 * NW * n_groups), lds, stream, a, n_groups);
+  static std::once_flag attr_once;
+  static hipError_t attr_err = hipSuccess;
+  std::call_once(attr_once, [&]() {
+    attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+  });
+  if (attr_err != hipSuccess)
+    SS_FAIL(SS_ERR_HIP, "ss_msa_attention: hipFuncSetAttribute: %s", hipGetErrorString(attr_err));
+  hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(64 * NW * n_groups), lds, stream, a, n_groups, n_stages);
   return check_launch("ss_msa_attention");
 }
 
