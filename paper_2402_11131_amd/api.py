@@ -273,28 +273,32 @@ def ss_lm_head_argmax_topk(hidden, W, K: int, idx=None, val=None, workspace=None
 
 
 def ss_tree_verify(tok, parent, main_argmax, max_depth: int, batch_stride: Optional[int] = None,
-                   node_stride: Optional[int] = None, offset: int = 0) -> dict:
+                   node_stride: Optional[int] = None, offset: int = 0, out: Optional[dict] = None) -> dict:
     """a4.  tok, parent [B,T] int32.  main_argmax: int32 GPU tensor; the arg-max token of main row i
     of sequence b is element offset + b*batch_stride + i*node_stride of its storage (defaults: a
-    contiguous [B,T] tensor)."""
+    contiguous [B,T] tensor).  `out` (the dict of an earlier call of the same shape) is reused if given."""
     lib = load_library()
     B, T = tok.shape
     if batch_stride is None:
         batch_stride, node_stride = T, 1
     dev = tok.device
     i32 = torch.int32
-    res = dict(n_accept=torch.empty(B, dtype=i32, device=dev), last=torch.empty(B, dtype=i32, device=dev),
-               bonus=torch.empty(B, dtype=i32, device=dev),
-               path=torch.empty((B, max_depth + 1), dtype=i32, device=dev),
-               out_tokens=torch.empty((B, max_depth + 1), dtype=i32, device=dev))
+    if out is None:
+        out = dict(n_accept=torch.empty(B, dtype=i32, device=dev), last=torch.empty(B, dtype=i32, device=dev),
+                   bonus=torch.empty(B, dtype=i32, device=dev),
+                   path=torch.empty((B, max_depth + 1), dtype=i32, device=dev),
+                   out_tokens=torch.empty((B, max_depth + 1), dtype=i32, device=dev))
+    elif out["n_accept"].shape != (B,) or out["path"].shape != (B, max_depth + 1) or out["out_tokens"].shape != (B, max_depth + 1):
+        raise ValueError("`out` was made for another shape")
+    res = out
     need = offset + (B - 1) * batch_stride + (T - 1) * node_stride + 1 if B > 0 else 0
     if main_argmax.numel() < need:
         raise ValueError("main_argmax too small for the given strides")
     _check(lib.ss_tree_verify(_dev(tok, i32, "tok"), _dev(parent, i32, "parent"),
                               _dev(main_argmax, i32, "main_argmax") + 4 * offset, batch_stride, node_stride, B, T,
-                              max_depth, res["n_accept"].data_ptr(), res["last"].data_ptr(),
-                              res["bonus"].data_ptr(), res["path"].data_ptr(), res["out_tokens"].data_ptr(),
-                              _stream()))
+                              max_depth, _dev(res["n_accept"], i32, "n_accept"), _dev(res["last"], i32, "last"),
+                              _dev(res["bonus"], i32, "bonus"), _dev(res["path"], i32, "path"),
+                              _dev(res["out_tokens"], i32, "out_tokens"), _stream()))
     return res
 
 
@@ -314,11 +318,11 @@ def ss_full_tree_template_host(branching: Sequence[int], capacity: int = SS_MAX_
 
 def ss_tree_draft(stream_topk, K: int, last, bonus, T: int, gamma: int, tmpl_parent=None, tmpl_rank=None,
                   branching: Optional[Sequence[int]] = None, T2: Optional[int] = None,
-                  batch_stride: Optional[int] = None, offset: int = 0):
+                  batch_stride: Optional[int] = None, offset: int = 0, out=None):
     """a5.  stream_topk: int32 GPU tensor; rank-th token of stream j of node i of sequence b is element
     offset + b*batch_stride + ((i*gamma)+(j-1))*K + rank (default: contiguous [B,T,gamma,K]).
     Template: device tensors tmpl_parent/tmpl_rank [T2], or per-level `branching`.
-    Returns (next_tok [B,T2], next_parent [T2])."""
+    Returns (next_tok [B,T2], next_parent [T2]); `out` (the pair of an earlier call) is reused if given."""
     lib = load_library()
     B = last.shape[0]
     i32 = torch.int32
@@ -340,8 +344,13 @@ def ss_tree_draft(stream_topk, K: int, last, bonus, T: int, gamma: int, tmpl_par
     else:
         T2 = tmpl_parent.shape[0]
     dev = last.device
-    next_tok = torch.empty((B, T2), dtype=i32, device=dev)
-    next_parent = torch.empty(T2, dtype=i32, device=dev)
+    if out is None:
+        next_tok = torch.empty((B, T2), dtype=i32, device=dev)
+        next_parent = torch.empty(T2, dtype=i32, device=dev)
+    else:
+        next_tok, next_parent = out
+        if next_tok.shape != (B, T2) or next_parent.shape != (T2,):
+            raise ValueError("`out` was made for another shape")
     need = offset + (B - 1) * batch_stride + T * gamma * K if B > 0 else 0
     if stream_topk.numel() < need:
         raise ValueError("stream_topk too small for the given strides")
@@ -349,7 +358,7 @@ def ss_tree_draft(stream_topk, K: int, last, bonus, T: int, gamma: int, tmpl_par
                              _dev(last, i32, "last"), _dev(bonus, i32, "bonus"),
                              None if tmpl_parent is None else _dev(tmpl_parent, i32, "tmpl_parent"),
                              None if tmpl_rank is None else _dev(tmpl_rank, i32, "tmpl_rank"), br_ptr, B, T, gamma,
-                             T2, next_tok.data_ptr(), next_parent.data_ptr(), _stream()))
+                             T2, _dev(next_tok, i32, "next_tok"), _dev(next_parent, i32, "next_parent"), _stream()))
     return next_tok, next_parent
 
 
