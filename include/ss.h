@@ -262,6 +262,22 @@ int ss_lm_head_argmax_topk(const void* hidden, const void* W, int N, int d, int 
                            void* stream);
 
 /*
+ * Tuning knobs for a3 / n1 / n2 (bf16 path), never needed for normal use; results
+ * do not depend on them beyond floating-point summation order.
+ * ss_lm_set_flavour: the kernel shape of the LM head and log-sum-exp (linear ==
+ *  0) or of ss_linear_rows (linear != 0): row_tiles tiles of 32 rows per workgroup
+ *  with the 4-wave kernel (wide == 0, 1..6 tiles) or the 8-wave kernel (wide != 0,
+ *  1..5 tiles); row_tiles outside that range = choose from the shape (default).
+ * ss_lm_set_stagger: feature blocks between the starting blocks of neighbouring
+ *  vocabulary tiles, 0..1024; negative = automatic (default).
+ * Both return the previous setting.  Initial values can be given by the
+ * environment variables SS_LM_FLAVOUR / SS_LINEAR_FLAVOUR ("3" or "3w") and
+ * SS_LM_STAGGER, which are read once per process.
+ */
+int ss_lm_set_flavour(int linear, int row_tiles, int wide);
+int ss_lm_set_stagger(int blocks);
+
+/*
  * n1. Dense projection of the step's rows (Sec. 3.1: queries, keys and values
  * are H.W^Q, H.W^K, H.W^V of the hidden states H of main and stream rows; the
  * output projection and the feed-forward maps of a layer have the same form):

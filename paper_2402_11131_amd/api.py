@@ -27,7 +27,7 @@ SS_MAX_T, SS_MAX_GAMMA, SS_MAX_K = 64, 8, 8
 
 EXPORTS = (
     "ss_version", "ss_last_error", "ss_probe_hbm_read", "ss_probe_mfma_bf16", "ss_check_tree_host", "ss_build_mask", "ss_msa_workspace_bytes",
-    "ss_msa_attention", "ss_msa_workspace_init", "ss_msa_attention_static", "ss_msa_static_scratch_bytes", "ss_msa_plan", "ss_msa_set_split_keys", "ss_msa_set_merge_in_kernel", "ss_lm_head_workspace_bytes", "ss_lm_head_argmax_topk", "ss_lm_head_verify_draft",
+    "ss_msa_attention", "ss_msa_workspace_init", "ss_msa_attention_static", "ss_msa_static_scratch_bytes", "ss_msa_plan", "ss_msa_set_split_keys", "ss_msa_set_merge_in_kernel", "ss_lm_head_workspace_bytes", "ss_lm_set_flavour", "ss_lm_set_stagger", "ss_lm_head_argmax_topk", "ss_lm_head_verify_draft",
     "ss_tree_verify", "ss_tree_draft", "ss_full_tree_template_host", "ss_kv_commit", "ss_linear_rows", "ss_stream_insert", "ss_value_rotate",
     "ss_lm_head_logsumexp", "ss_transition_probs", "ss_tree_prune",
 )
@@ -72,6 +72,8 @@ def load_library() -> ctypes.CDLL:
     lib.ss_msa_set_split_keys.argtypes = [i32]
     lib.ss_msa_set_merge_in_kernel.argtypes = [i32]
     lib.ss_lm_head_workspace_bytes.argtypes = [i32] * 5
+    lib.ss_lm_set_flavour.argtypes = [i32, i32, i32]
+    lib.ss_lm_set_stagger.argtypes = [i32]
     lib.ss_lm_head_workspace_bytes.restype = sz
     lib.ss_lm_head_argmax_topk.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, sz, vp]
     lib.ss_tree_verify.argtypes = [vp, vp, vp, lng, lng, i32, i32, i32, vp, vp, vp, vp, vp, vp]
@@ -248,6 +250,21 @@ def ss_msa_attention_static(q, k_new, v_new, k_cache, v_cache, block_table, seq_
 
 def ss_lm_head_workspace_bytes(N, d, V, K, dtype_code) -> int:
     return load_library().ss_lm_head_workspace_bytes(N, d, V, K, dtype_code)
+
+
+def ss_lm_set_flavour(linear: bool, flavour) -> int:
+    """Tuning knob: kernel shape of the LM head (linear=False) or of ss_linear_rows (linear=True): "<row tiles>"
+    (4 waves, 1..6 tiles of 32 rows per workgroup), "<row tiles>w" (8 waves, 1..5) or None (automatic)."""
+    if flavour is None:
+        return load_library().ss_lm_set_flavour(1 if linear else 0, 0, 0)
+    f = str(flavour)
+    wide = f.endswith("w")
+    return load_library().ss_lm_set_flavour(1 if linear else 0, int(f[:-1] if wide else f), 1 if wide else 0)
+
+
+def ss_lm_set_stagger(blocks: int) -> int:
+    """Tuning knob: feature blocks between the starting blocks of neighbouring vocabulary tiles (-1 = automatic)."""
+    return load_library().ss_lm_set_stagger(int(blocks))
 
 
 def ss_lm_head_argmax_topk(hidden, W, K: int, idx=None, val=None, workspace=None):

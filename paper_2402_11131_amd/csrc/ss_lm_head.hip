@@ -8,6 +8,9 @@
 #include <math.h>
 #include <stdlib.h>
 
+#include <atomic>
+#include <mutex>
+
 #include "ss_common.h"
 #include "ss_tree.h"
 
@@ -180,11 +183,11 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 
 // 16 bytes per lane from (sbase + voff) to LDS address lds_addr + 16*lane.
 SS_DEV void load_to_lds16(const void* sbase, uint32_t voff, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %0" ::"s"(sbase), "v"(voff), "s"(lds_addr) : "memory");
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %0" ::"s"(sbase), "v"(voff), "s"(lds_addr) : "memory", "m0");
 }
 // The same with the streaming hint, for data that no other workgroup will ask for.
 SS_DEV void load_to_lds16_stream(const void* sbase, uint32_t voff, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %0 nt" ::"s"(sbase), "v"(voff), "s"(lds_addr) : "memory");
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %0 nt" ::"s"(sbase), "v"(voff), "s"(lds_addr) : "memory", "m0");
 }
 
 // The KT best (logit, id) pairs of candidates that arrive in increasing id order: an equal logit
@@ -587,6 +590,34 @@ __global__ __launch_bounds__(1024) void lm_tail_kernel(TailArgs t) {
   draft_sequence(tid, b, tp, trank, topk, t.K, bonus_tok, t.gamma, t.T2, t.next_tok, t.next_parent, dpar);
 }
 
+// Tuning aids: a flavour (32-row tiles per workgroup, 8-wave kernel or not) that replaces the chosen one for
+// the LM head or for the projections, and the stagger of the starting blocks.  Set through ss_lm_set_flavour /
+// ss_lm_set_stagger; their initial values come from SS_LM_FLAVOUR / SS_LINEAR_FLAVOUR ("<row tiles>" or
+// "<row tiles>w") and SS_LM_STAGGER, read once per process.
+struct LmTuning {
+  std::atomic<int> flavour[2];  // [LM head, projection]: row tiles | wide << 8, 0 = automatic
+  std::atomic<int> stagger;     // feature blocks between neighbouring tiles' starts, -1 = automatic
+};
+static int flavour_code(long want, int wide) { return (want < 1 || want > (wide ? 5 : 6)) ? 0 : (int)want | (wide ? 256 : 0); }
+static int flavour_from_env(const char* var) {
+  const char* e = getenv(var);
+  if (!e) return 0;
+  char* end = nullptr;
+  const long want = strtol(e, &end, 10);
+  return flavour_code(want, end && *end == 'w');
+}
+static LmTuning& tuning() {
+  static LmTuning t;
+  static std::once_flag once;
+  std::call_once(once, []() {
+    t.flavour[0] = flavour_from_env("SS_LM_FLAVOUR");
+    t.flavour[1] = flavour_from_env("SS_LINEAR_FLAVOUR");
+    const char* e = getenv("SS_LM_STAGGER");
+    const int v = e ? atoi(e) : -1;
+    t.stagger = v < 0 ? -1 : (v > 1024 ? 1024 : v);
+  });
+  return t;
+}
 struct LmFlavour {
   int nrt;   // 32-row tiles per workgroup
   int wide;  // 0: 4 waves, tile of 128 ids, nrt <= 6; 1: 8 waves, tile of 256 ids, nrt <= 5
@@ -616,17 +647,18 @@ static int launch_lm_bf16_rk(hipStream_t st, const LmArgs& a) {
     kern = a.n_chunks == 1 ? lm_head_bf16_kernel<NRT, KT, 4, 4, true> : lm_head_bf16_kernel<NRT, KT, 4, 4, false>;
     lds = 4 * ((size_t)(32 * NRT) * 128 + 128 * 128);
   }
-  static bool attr_set[2] = {false, false};  // [W streamed]
+  // one attribute call per kernel instantiation (this function template has one pair of flags per <NRT, KT, WIDE>)
+  static std::once_flag attr_once[2];  // [W streamed]
+  static hipError_t attr_err[2] = {hipSuccess, hipSuccess};
   const int variant = (WIDE == 0 && a.n_chunks == 1) ? 1 : 0;
-  if (!attr_set[variant]) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)lds);
-    if (e != hipSuccess) SS_FAIL(SS_ERR_HIP, "lm_head_bf16_kernel: hipFuncSetAttribute: %s", hipGetErrorString(e));
-    attr_set[variant] = true;
-  }
+  std::call_once(attr_once[variant], [&]() {
+    attr_err[variant] = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  });
+  if (attr_err[variant] != hipSuccess)
+    SS_FAIL(SS_ERR_HIP, "lm_head_bf16_kernel: hipFuncSetAttribute: %s", hipGetErrorString(attr_err[variant]));
   const dim3 grid(8 * a.n_chunks * ceil_div(a.n_tiles, 8));
   hipLaunchKernelGGL(kern, grid, dim3(threads), lds, st, a);
-  return SS_OK;
+  return check_launch("lm_head_bf16_kernel");
 }
 template <int NRT, int WIDE>
 static int launch_lm_bf16_r(int KT, hipStream_t st, const LmArgs& a) {
@@ -646,7 +678,8 @@ static int launch_lm_bf16(LmFlavour f, int KT, hipStream_t st, const LmArgs& arg
   // row chunks the chunks of a tile walk together either way and the gain is within the noise.
   LmArgs a = args;
   a.k_stagger = a.n_chunks == 1 ? 1 : 0;
-  if (const char* e = getenv("SS_LM_STAGGER")) a.k_stagger = atoi(e) < 0 ? 0 : (atoi(e) > 1024 ? 1024 : atoi(e));  // tuning aid
+  const int forced_stagger = tuning().stagger.load();
+  if (forced_stagger >= 0) a.k_stagger = forced_stagger;
   if (f.wide) {
     switch (f.nrt) {
       case 1: return launch_lm_bf16_r<1, 1>(KT, st, a);
@@ -696,16 +729,12 @@ static LmFlavour lm_choose(int N, int V, LmArgs* a) {
   return f;
 }
 
-// Tuning aid: "<row tiles>" or "<row tiles>w" in the environment variable replaces the chosen flavour.
-static void lm_flavour_override(const char* var, int N, int V, LmFlavour* f, LmArgs* a) {
-  const char* e = getenv(var);
-  if (!e) return;
-  char* end = nullptr;
-  const long want = strtol(e, &end, 10);
-  const int wide = end && *end == 'w';
-  if (want < 1 || want > (wide ? 5 : 6)) return;
+static void lm_flavour_override(bool linear, int N, int V, LmFlavour* f, LmArgs* a) {
+  const int code = tuning().flavour[linear ? 1 : 0].load();
+  if (code == 0) return;
+  const int want = code & 255, wide = code >> 8;
   const int n32 = ceil_div(N, 32);
-  a->n_chunks = ceil_div(n32, (int)want);
+  a->n_chunks = ceil_div(n32, want);
   f->nrt = ceil_div(n32, a->n_chunks);
   f->wide = wide;
   a->n_tiles = ceil_div(V, wide ? 256 : 128);
@@ -733,6 +762,14 @@ static int gemm_check(const char* fn, int N, int d, int V, int dtype) {
 
 extern "C" {
 
+int ss_lm_set_flavour(int linear, int row_tiles, int wide) {
+  return ss::tuning().flavour[linear ? 1 : 0].exchange(ss::flavour_code(row_tiles, wide != 0));
+}
+
+int ss_lm_set_stagger(int blocks) {
+  return ss::tuning().stagger.exchange(blocks < 0 ? -1 : (blocks > 1024 ? 1024 : blocks));
+}
+
 size_t ss_lm_head_workspace_bytes(int N, int d, int V, int K, int dtype) {
   ss::clear_error();
   if (ss::lm_check("ss_lm_head_workspace_bytes", N, d, V, K, dtype) != SS_OK) return 0;
@@ -759,7 +796,7 @@ static int lm_candidates(const char* fn, const void* hidden, const void* W, int 
     hipLaunchKernelGGL(lm_head_f32_kernel<0>, grid, dim3(256), 0, st, a);
   } else {
     LmFlavour f = lm_choose(N, V, &a);
-    lm_flavour_override("SS_LM_FLAVOUR", N, V, &f, &a);
+    lm_flavour_override(false, N, V, &f, &a);
     SS_REQUIRE((long)a.n_chunks * (a.n_tiles + 7) < (1L << 27), SS_ERR_UNSUPPORTED, "%s: N x V too large", fn);
     const int KT = K == 1 ? 1 : (K <= 4 ? 4 : 8);
     if (int rc = launch_lm_bf16(f, KT, st, a)) return rc;
@@ -860,7 +897,7 @@ int ss_lm_head_logsumexp(const void* hidden, const void* W, int N, int d, int V,
     hipLaunchKernelGGL(lm_head_f32_kernel<2>, grid, dim3(256), 0, st, a);
   } else {
     LmFlavour f = lm_choose(N, V, &a);
-    lm_flavour_override("SS_LM_FLAVOUR", N, V, &f, &a);
+    lm_flavour_override(false, N, V, &f, &a);
     SS_REQUIRE((long)a.n_chunks * (a.n_tiles + 7) < (1L << 27), SS_ERR_UNSUPPORTED, "%s: N x V too large", fn);
     if (int rc = launch_lm_bf16(f, -1, st, a)) return rc;
   }
@@ -891,7 +928,7 @@ int ss_linear_rows(const void* x, const void* W, int N, int d, int V, int dtype,
     hipLaunchKernelGGL(lm_head_f32_kernel<1>, grid, dim3(256), 0, st, a);
   } else {
     LmFlavour f = lm_choose(N, V, &a);
-    lm_flavour_override("SS_LINEAR_FLAVOUR", N, V, &f, &a);
+    lm_flavour_override(true, N, V, &f, &a);
     SS_REQUIRE((long)a.n_chunks * (a.n_tiles + 7) < (1L << 27), SS_ERR_UNSUPPORTED, "%s: N x V too large", fn);
     if (int rc = launch_lm_bf16(f, 0, st, a)) return rc;
   }

@@ -1,7 +1,6 @@
 """Every shape of the MFMA LM-head kernel (4 waves x 1..6 row tiles, 8 waves x 1..5 row tiles) behind its three
 epilogues, forced through the tuning variables, against the oracle.  The host plan picks only some of them for
 the sizes the other tests use; this one makes sure all are right.  Tolerances as in the tests of the entry points."""
-import os
 
 import numpy as np
 import pytest
@@ -31,17 +30,17 @@ def problem():
 
 
 @pytest.fixture(autouse=True)
-def _clean_env():
+def _automatic_again():
     yield
-    os.environ.pop("SS_LM_FLAVOUR", None)
-    os.environ.pop("SS_LINEAR_FLAVOUR", None)
-    os.environ.pop("SS_LM_STAGGER", None)
+    api.ss_lm_set_flavour(False, None)
+    api.ss_lm_set_flavour(True, None)
+    api.ss_lm_set_stagger(-1)
 
 
 @pytest.mark.parametrize("flavour", FLAVOURS)
 def test_projection(problem, flavour):
     x, W, ref = problem
-    os.environ["SS_LINEAR_FLAVOUR"] = flavour
+    api.ss_lm_set_flavour(True, flavour)
     y = to_np_f32(api.ss_linear_rows(x, W).cpu()).astype(np.float64)
     assert (np.abs(y - ref["z"]) <= 2.0 ** -8 * np.abs(ref["z"]) + 1e-5 * ref["S"]).all()
 
@@ -49,7 +48,7 @@ def test_projection(problem, flavour):
 @pytest.mark.parametrize("flavour", FLAVOURS)
 def test_top_k(problem, flavour):
     x, W, ref = problem
-    os.environ["SS_LM_FLAVOUR"] = flavour
+    api.ss_lm_set_flavour(False, flavour)
     idx, val = api.ss_lm_head_argmax_topk(x, W, 4)
     torch.cuda.synchronize()
     idx, val = idx.cpu().numpy(), val.cpu().numpy()
@@ -63,7 +62,7 @@ def test_top_k(problem, flavour):
 @pytest.mark.parametrize("flavour", FLAVOURS)
 def test_log_sum_exp(problem, flavour):
     x, W, ref = problem
-    os.environ["SS_LM_FLAVOUR"] = flavour
+    api.ss_lm_set_flavour(False, flavour)
     lse = api.ss_lm_head_logsumexp(x, W).cpu().numpy()
     assert (np.abs(lse - ref["lse"]) <= 2e-3 * np.maximum(1.0, np.abs(ref["lse"]))).all()
 
@@ -73,7 +72,7 @@ def test_log_sum_exp(problem, flavour):
 def test_top_1_and_top_8(problem, flavour, K):
     # the other two widths of the candidate lists (K = 1 and K = 5..8) in both shapes
     x, W, ref = problem
-    os.environ["SS_LM_FLAVOUR"] = flavour
+    api.ss_lm_set_flavour(False, flavour)
     idx, val = api.ss_lm_head_argmax_topk(x, W, K)
     torch.cuda.synchronize()
     idx, val = idx.cpu().numpy(), val.cpu().numpy()
@@ -93,8 +92,9 @@ def test_staggered_starting_blocks(problem, flavour, stagger):
     # every vocabulary tile walks the 5 feature blocks from its own start and wraps around (the host does this only
     # for launches with one row chunk; here it is forced for all shapes): same results within the same bounds
     x, W, ref = problem
-    os.environ["SS_LM_FLAVOUR"] = os.environ["SS_LINEAR_FLAVOUR"] = flavour
-    os.environ["SS_LM_STAGGER"] = str(stagger)
+    api.ss_lm_set_flavour(False, flavour)
+    api.ss_lm_set_flavour(True, flavour)
+    api.ss_lm_set_stagger(stagger)
     y = to_np_f32(api.ss_linear_rows(x, W).cpu()).astype(np.float64)
     assert (np.abs(y - ref["z"]) <= 2.0 ** -8 * np.abs(ref["z"]) + 1e-5 * ref["S"]).all()
     lse = api.ss_lm_head_logsumexp(x, W).cpu().numpy()
