@@ -251,7 +251,10 @@ int ss_msa_set_merge_in_kernel(int on);
  * predicts y_t, stream j predicts y_{t+j}; Sec. 3.2.2: top-k tokens per stream).
  *    z[n,v] = sum_d hidden[n,d] * W[v,d]          (never written to memory)
  *    idx[n,0..K) = the K largest z[n,:] in decreasing order, ties -> lower v;
- *    val[n,0..K) = those logits (fp32).
+ *    val[n,0..K) = those logits (fp32).  The SS_BF16 path selects on the fp32
+ *    logits with their five lowest mantissa bits set aside (2^-18 of a logit's
+ *    magnitude): logits closer than that are ordered by token id, and val
+ *    carries those five bits cleared.
  *  hidden [N,d], W [V,d] (dtype SS_F32 or SS_BF16), idx [N,K] int32, val [N,K] f32.
  * Limits: 1 <= K <= SS_MAX_K, K <= V, d % 64 == 0 for SS_BF16.
  * workspace: at least ss_lm_head_workspace_bytes(...) bytes.

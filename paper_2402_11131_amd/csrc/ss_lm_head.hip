@@ -217,6 +217,13 @@ struct TopAsc {
   }
 };
 
+// Median of three unsigned numbers (one instruction on this hardware).
+SS_DEV uint32_t umed3(uint32_t a, uint32_t b, uint32_t c) {
+  const uint32_t lo = a < b ? a : b, hi = a < b ? b : a;
+  const uint32_t m = hi < c ? hi : c;
+  return lo > m ? lo : m;
+}
+
 template <int KT>
 struct TopList {  // the KT best keys seen so far, best first
   uint64_t k[KT];
@@ -302,47 +309,78 @@ SS_DEV void lm_epilogue(const LmArgs& a, floatx16 (&acc)[NRT], unsigned char* hb
     }
     return;
   } else {
-  // Per row: this lane's 16 candidates go into a K-entry list, the two lanes of a row merge theirs,
-  // the four waves' lists meet in LDS, and one thread per row leaves the workgroup's K best as the
-  // part of this vocabulary tile.
+  // Per row: the KT best of this lane's 16 logits, then of the row's two lanes (32 token ids), are found on
+  // 32-bit keys: the logit's order-preserving pattern with its five lowest bits replaced by 31 - (position of
+  // the id among the wave's 32), so that one unsigned maximum / median per list entry inserts a candidate
+  // (equal patterns -> lower id first) and no index travels beside the value.  The five bits cost 2^-18 of a
+  // logit's magnitude in resolution: logits closer than that are ordered by id, and the values reported
+  // carry those bits cleared.  The waves' lists (64-bit keys from here on: pattern, complement of the id) meet
+  // in LDS, and one thread per row merges them by taking the best head KT times (every list is sorted).
   uint64_t* lists = reinterpret_cast<uint64_t*>(hbuf);  // [ROWS][NW waves][KT]
 #pragma unroll
   for (int rt = 0; rt < NRT; ++rt) {
-    TopAsc<KT> asc;  // this lane's candidates come in increasing id order
-    asc.clear();
+    uint32_t top[KT];
+#pragma unroll
+    for (int k = 0; k < KT; ++k) top[k] = 0;  // ranks below every real candidate
+    auto insert = [&](uint32_t x) {
+#pragma unroll
+      for (int k = KT - 1; k >= 1; --k) top[k] = umed3(top[k - 1], top[k], x);
+      top[0] = top[0] > x ? top[0] : x;
+    };
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
-      const int id = v0 + 8 * (e >> 2) + 4 * lh + (e & 3);
-      asc.insert(id < a.V ? acc[rt][e] : -INFINITY, id);
+      const int off = 8 * (e >> 2) + 4 * lh + (e & 3);
+      const uint32_t u = __float_as_uint(acc[rt][e] + 0.f);  // -0 -> +0, so that the two zeros tie
+      const uint32_t o = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+      insert(v0 + off < a.V ? ((o & ~31u) | (uint32_t)(31 - off)) : 0u);
     }
-    TopList<KT> top;
+    uint32_t other[KT];
 #pragma unroll
-    for (int k = 0; k < KT; ++k) top.k[k] = asc.i[k] == INT_MAX ? 0 : cand_key(asc.v[k], asc.i[k]);  // unused slots rank last
-    uint64_t other[KT];
+    for (int k = 0; k < KT; ++k) other[k] = __shfl_xor(top[k], 32, 64);
 #pragma unroll
-    for (int k = 0; k < KT; ++k) {
-      const uint32_t lo = __shfl_xor((uint32_t)top.k[k], 32, 64), hi = __shfl_xor((uint32_t)(top.k[k] >> 32), 32, 64);
-      other[k] = ((uint64_t)hi << 32) | lo;
-    }
-#pragma unroll
-    for (int k = 0; k < KT; ++k) top.insert(other[k]);
+    for (int k = 0; k < KT; ++k) insert(other[k]);
     if (lh == 0) {
 #pragma unroll
-      for (int k = 0; k < KT; ++k) lists[((32 * rt + ln) * NW + w) * KT + k] = top.k[k];
+      for (int k = 0; k < KT; ++k)
+        lists[((32 * rt + ln) * NW + w) * KT + k] =
+            top[k] == 0 ? 0 : (((uint64_t)(top[k] & ~31u) << 32) | (uint32_t)(0xffffffffu - (uint32_t)(v0 + 31 - (int)(top[k] & 31u))));
     }
   }
   __syncthreads();
   for (int r = tid; r < ROWS; r += 64 * NW) {
-    TopList<KT> top;
-    top.clear();
-#pragma unroll 16
-    for (int j = 0; j < NW * KT; ++j) top.insert(lists[r * NW * KT + j]);
-    const int row = row0 + r;
-    if (row < a.N) {
-      const size_t o = ((size_t)row * a.n_tiles + tile) * a.K;
+    const uint64_t* L = lists + (size_t)r * NW * KT;
+    uint64_t head[NW];
+    int pos[NW];
 #pragma unroll
-      for (int k = 0; k < KT; ++k)
-        if (k < a.K) a.cand_key[o + k] = top.k[k];
+    for (int j = 0; j < NW; ++j) {
+      head[j] = L[j * KT];
+      pos[j] = 0;
+    }
+    const int row = row0 + r;
+    const size_t o = ((size_t)row * a.n_tiles + tile) * a.K;
+#pragma unroll
+    for (int k = 0; k < KT; ++k) {
+      uint64_t best = head[0];
+      int bw = 0;
+#pragma unroll
+      for (int j = 1; j < NW; ++j) {
+        const bool up = head[j] > best;
+        best = up ? head[j] : best;
+        bw = up ? j : bw;
+      }
+      if (row < a.N && k < a.K) a.cand_key[o + k] = best;
+      if (k + 1 < KT) {
+        // the winner's list moves on (lists are distinct ids, so the winner is unique unless all heads are empty)
+        int np = 0;
+#pragma unroll
+        for (int j = 0; j < NW; ++j) {
+          pos[j] += (j == bw) ? 1 : 0;
+          np = (j == bw) ? pos[j] : np;
+        }
+        const uint64_t nh = np < KT ? L[bw * KT + np] : 0;
+#pragma unroll
+        for (int j = 0; j < NW; ++j) head[j] = (j == bw) ? nh : head[j];
+      }
     }
   }
   }
