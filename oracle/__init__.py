@@ -253,3 +253,15 @@ def kv_commit(k_new, v_new, k_cache, v_cache, block_table, seq_lens, path, n_acc
     _load().ora_kv_commit(_p(k_new), _p(v_new), _p(kc), _p(vc), _p(bt), bt.shape[1], _p(sl), _p(path), _p(na),
                           B, R, Hkv, D, page, path.shape[1] - 1, _p(new_lens))
     return kc, vc, new_lens
+
+
+def kv_alloc_pages(block_table, seq_lens, n_accept, page, max_depth, free_pages, free_count):
+    """n3, page allocation.  Returns (block_table with the new pages written in, free_count left, n_commit [B])."""
+    bt = _i32(block_table).copy()
+    sl, na, fp = _i32(seq_lens), _i32(n_accept), _i32(free_pages)
+    B, max_pages = bt.shape
+    assert sl.shape == (B,) and na.shape == (B,) and 0 <= free_count <= fp.size
+    cnt = np.array([free_count], np.int32)
+    n_commit = np.zeros(B, np.int32)
+    _load().ora_kv_alloc_pages(_p(bt), max_pages, _p(sl), _p(na), B, page, max_depth, _p(fp), _p(cnt), _p(n_commit))
+    return bt, int(cnt[0]), n_commit

@@ -501,7 +501,8 @@ void ora_tree_prune(const int32_t* tok, const int32_t* parent, const float* prob
  * (Appendix A.1): of the step's own rows only the main rows of the accepted path stay, appended in
  * path order behind the L cached tokens.  Caches are updated in place; new_len = L + n_accept + 1.
  * Layouts as in a2: k_cache [P][Hkv][page][D], v_cache [P][Hkv][D][page], k_new/v_new [B][R][Hkv][D].
- * A position past the block table's capacity is dropped.
+ * A position past the block table's capacity is dropped; n_accept[b] < 0 means that nothing of sequence b is
+ * appended (what ora_kv_alloc_pages reports when not even the first row has a page).
  */
 void ora_kv_commit(const float* k_new, const float* v_new, float* k_cache, float* v_cache,
                    const int32_t* block_table, int max_pages, const int32_t* seq_lens, const int32_t* path,
@@ -527,3 +528,37 @@ void ora_kv_commit(const float* k_new, const float* v_new, float* k_cache, float
   }
 }
 
+
+/*
+ * n3, page allocation (Appendix A.1: the cache grows by the accepted tokens after every generation step;
+ * Sec. 3.2.1: only main-stream keys/values are cached).  Sequence b holds L = seq_lens[b] tokens in its
+ * first ceil(L/page) logical pages; the accepted path adds the positions L .. L + n_accept[b].  Logical
+ * pages those positions need beyond the mapped ones are taken from the top of a stack of free physical
+ * pages, sequence after sequence in batch order, page after page in logical order, and written into the
+ * block table.  A sequence stops growing at the table's capacity (max_pages*page tokens) or when the stack
+ * is empty; n_commit[b] is then n_accept[b] clipped to the rows that have a page (-1: none).  *free_count
+ * is lowered by the pages handed out.
+ */
+void ora_kv_alloc_pages(int32_t* block_table, int max_pages, const int32_t* seq_lens, const int32_t* n_accept,
+                        int B, int page, int max_depth, const int32_t* free_pages, int32_t* free_count,
+                        int32_t* n_commit) {
+  int left = *free_count;
+  for (int b = 0; b < B; b++) {
+    int L = seq_lens[b];
+    int acc = n_accept[b] > max_depth ? max_depth : n_accept[b];
+    int mapped = (L + page - 1) / page; /* logical pages in use */
+    int fit = -1;                       /* last path position that has a page */
+    for (int j = 0; j <= acc; j++) {
+      int lp = (L + j) / page;
+      if (lp >= max_pages) break;
+      if (lp >= mapped) {
+        if (left == 0) break;
+        block_table[(size_t)b * max_pages + lp] = free_pages[--left];
+        mapped = lp + 1;
+      }
+      fit = j;
+    }
+    n_commit[b] = fit;
+  }
+  *free_count = left;
+}
