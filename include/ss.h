@@ -476,14 +476,46 @@ int ss_full_tree_template_host(const int32_t* branching, int gamma, int capacity
  *  new_seq_lens [B] int32 out, or NULL: seq_lens[b] + number of rows appended
  *          (n_accept[b] + 1 unless the table's capacity cut it).  Must not be
  *          the seq_lens array itself.
- * Node ids outside [0,T), page ids outside [0,num_pages) and n_accept outside
- * [0,max_depth] are clamped into range.
+ * Node ids outside [0,T) and page ids outside [0,num_pages) are clamped into
+ * range, n_accept above max_depth counts as max_depth, and a negative n_accept
+ * means that nothing of that sequence is appended (new_seq_lens[b] =
+ * seq_lens[b]): what ss_kv_alloc_pages reports for a sequence without a page.
  */
 int ss_kv_commit(const void* k_new, const void* v_new, void* k_cache, void* v_cache,
                  const int32_t* block_table, int max_pages_per_seq, int num_pages,
                  const int32_t* seq_lens, const int32_t* path, const int32_t* n_accept, int B, int T,
                  int gamma, int Hkv, int D, int page_size, int max_depth, int dtype,
                  int32_t* new_seq_lens, void* stream);
+
+/*
+ * n3, page allocation (Appendix A.1: the cache grows by the accepted tokens
+ * after every generation step).  Sequence b uses the first
+ * ceil(seq_lens[b]/page_size) entries of its block-table row; its accepted path
+ * adds the positions seq_lens[b] .. seq_lens[b] + n_accept[b].  The logical
+ * pages those positions need beyond the ones in use are taken from the top of a
+ * stack of free physical pages and written into block_table: sequences are
+ * served in batch order, pages in logical order, so the result is that of a
+ * sequential allocator and does not depend on scheduling.  One call per step
+ * serves all layers when they share one table (each layer's caches are indexed
+ * by the same page ids); ss_kv_commit per layer follows with n_commit in place
+ * of n_accept.
+ *
+ *  block_table [B,max_pages_per_seq] int32 in/out.
+ *  seq_lens, n_accept [B] int32 in (n_accept as ss_tree_verify returns it;
+ *          values above max_depth count as max_depth, negative = no rows).
+ *  free_pages [*free_count ..] int32 in: the stack, top at index *free_count-1.
+ *  free_count [1] int32 in/out (DEVICE): lowered by the pages handed out.
+ *  n_commit [B] int32 out: n_accept[b] clipped to the path rows that have a
+ *          page; smaller than n_accept[b] when the table's capacity
+ *          (max_pages_per_seq*page_size tokens) or an empty stack stopped the
+ *          sequence; -1 when not even the first row has one.
+ * One small kernel on `stream`; B == 0 is a no-op.  Calls that share a stack must
+ * follow each other on one stream.
+ */
+int ss_kv_alloc_pages(int32_t* block_table, int max_pages_per_seq, const int32_t* seq_lens,
+                      const int32_t* n_accept, int B, int page_size, int max_depth,
+                      const int32_t* free_pages, int32_t* free_count, int32_t* n_commit,
+                      void* stream);
 
 #ifdef __cplusplus
 }

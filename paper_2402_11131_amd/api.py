@@ -28,7 +28,7 @@ SS_MAX_T, SS_MAX_GAMMA, SS_MAX_K = 64, 8, 8
 EXPORTS = (
     "ss_version", "ss_last_error", "ss_probe_hbm_read", "ss_probe_mfma_bf16", "ss_check_tree_host", "ss_build_mask", "ss_msa_workspace_bytes",
     "ss_msa_attention", "ss_msa_workspace_init", "ss_msa_attention_static", "ss_msa_static_scratch_bytes", "ss_msa_plan", "ss_msa_set_split_keys", "ss_msa_set_merge_in_kernel", "ss_lm_head_workspace_bytes", "ss_lm_set_flavour", "ss_lm_set_stagger", "ss_lm_head_argmax_topk", "ss_lm_head_verify_draft",
-    "ss_tree_verify", "ss_tree_draft", "ss_full_tree_template_host", "ss_kv_commit", "ss_linear_rows", "ss_stream_insert", "ss_value_rotate",
+    "ss_tree_verify", "ss_tree_draft", "ss_full_tree_template_host", "ss_kv_commit", "ss_kv_alloc_pages", "ss_linear_rows", "ss_stream_insert", "ss_value_rotate",
     "ss_lm_head_logsumexp", "ss_transition_probs", "ss_tree_prune",
 )
 
@@ -81,6 +81,7 @@ def load_library() -> ctypes.CDLL:
     lib.ss_tree_draft.argtypes = [vp, lng, i32, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, vp]
     lib.ss_full_tree_template_host.argtypes = [vp, i32, i32, vp, vp, vp]
     lib.ss_kv_commit.argtypes = [vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp, vp]
+    lib.ss_kv_alloc_pages.argtypes = [vp, i32, vp, vp, i32, i32, i32, vp, vp, vp, vp]
     lib.ss_linear_rows.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp]
     lib.ss_stream_insert.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp, vp]
     lib.ss_value_rotate.argtypes = [vp, i32, i32, i32, i32, i32, c.c_float, i32, vp]
@@ -461,6 +462,24 @@ def ss_kv_commit(k_new, v_new, k_cache, v_cache, block_table, seq_lens, path, n_
                             None if new_seq_lens is None else _dev(new_seq_lens, i32, "new_seq_lens"), _stream()))
     return new_seq_lens
 
+
+
+def ss_kv_alloc_pages(block_table, seq_lens, n_accept, page: int, max_depth: int, free_pages, free_count,
+                      n_commit: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """n3, page allocation.  block_table [B,max_pages] int32 is updated IN PLACE with pages popped from the stack
+    free_pages (int32, top at index free_count-1; free_count: int32 GPU tensor of one element, lowered in place).
+    Returns n_commit [B] int32: n_accept clipped to the path rows that have a page."""
+    lib = load_library()
+    i32 = torch.int32
+    B, max_pages = block_table.shape
+    if tuple(seq_lens.shape) != (B,) or tuple(n_accept.shape) != (B,) or free_count.numel() != 1:
+        raise ValueError("seq_lens / n_accept must be [B], free_count one element")
+    if n_commit is None:
+        n_commit = torch.empty(B, dtype=i32, device=block_table.device)
+    _check(lib.ss_kv_alloc_pages(_dev(block_table, i32, "block_table"), max_pages, _dev(seq_lens, i32, "seq_lens"),
+                                 _dev(n_accept, i32, "n_accept"), B, page, max_depth, _dev(free_pages, i32, "free_pages"),
+                                 _dev(free_count, i32, "free_count"), _dev(n_commit, i32, "n_commit"), _stream()))
+    return n_commit
 
 
 def ss_linear_rows(x: torch.Tensor, W: torch.Tensor, y: Optional[torch.Tensor] = None) -> torch.Tensor:
