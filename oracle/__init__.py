@@ -265,3 +265,18 @@ def kv_alloc_pages(block_table, seq_lens, n_accept, page, max_depth, free_pages,
     n_commit = np.zeros(B, np.int32)
     _load().ora_kv_alloc_pages(_p(bt), max_pages, _p(sl), _p(na), B, page, max_depth, _p(fp), _p(cnt), _p(n_commit))
     return bt, int(cnt[0]), n_commit
+
+
+def stream_insert_linear(M, P, W, fM=None):
+    """n4 + n1: the rows of Eq. 3 through a dense map, Y [B,R,V] float64 = (rows of stream_insert) . W^T with
+    nothing rounded in between.  M [B,T,d], P [gamma,d], W [V,d], fM = f(M) or None."""
+    M, P, W = _f32(M), _f32(P), _f32(W)
+    B, T, d = M.shape
+    gamma, V = P.shape[0], W.shape[0]
+    assert P.shape == (gamma, d) and W.shape == (V, d)
+    if fM is not None:
+        fM = _f32(fM)
+        assert fM.shape == M.shape
+    Y = np.zeros((B, T * (1 + gamma), V), np.float64)
+    _load().ora_stream_insert_linear(_p(M), _p(fM), _p(P), _p(W), B, T, gamma, d, V, _p(Y))
+    return Y

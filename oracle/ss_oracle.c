@@ -562,3 +562,35 @@ void ora_kv_alloc_pages(int32_t* block_table, int max_pages, const int32_t* seq_
   }
   *free_count = left;
 }
+
+/*
+ * n4 + n1 as one operation: the rows of Eq. 3 entering a dense map of the first multi-stream layer
+ * (Sec. 3.1: queries, keys and values are H.W^Q, H.W^K, H.W^V of the rows' hidden states H).
+ *   Y[b, r, v] = sum_e X[b, r, e] * W[v, e]   with X the rows of Eq. 3 (ora_stream_insert), never rounded:
+ * the sum of Eq. 3 and the products are formed in double from the stored M, f(M), P and W.
+ * Y [B,R,V] in the row order stated above.
+ */
+void ora_stream_insert_linear(const float* M, const float* fM, const float* P, const float* W, int B, int T,
+                              int gamma, int d, int V, double* Y) {
+  const int R = T * (1 + gamma);
+  const float* src = fM ? fM : M;
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int b = 0; b < B; b++)
+    for (int r = 0; r < R; r++) {
+      int i = r, j = 0; /* node, stream (0 = main row) */
+      if (r >= T) {
+        i = (r - T) / gamma;
+        j = (r - T) % gamma + 1;
+      }
+      const float* m = (j == 0 ? M : src) + ((size_t)b * T + i) * d;
+      for (int v = 0; v < V; v++) {
+        double acc = 0.0;
+        for (int e = 0; e < d; e++) {
+          double x = (double)m[e];
+          if (j > 0) x += (double)P[(size_t)(j - 1) * d + e];
+          acc += x * (double)W[(size_t)v * d + e];
+        }
+        Y[((size_t)b * R + r) * V + v] = acc;
+      }
+    }
+}

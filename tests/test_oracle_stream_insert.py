@@ -2,7 +2,10 @@
 import numpy as np
 
 import oracle
+import pytest
+
 from helpers import rows_of
+from paper_2402_11131_amd import synth
 
 
 def _rand(B, T, gamma, d, seed):
@@ -68,3 +71,55 @@ def test_gamma_zero_and_empty_batch():
     X = oracle.stream_insert(M, np.zeros((0, 4), np.float32))
     np.testing.assert_array_equal(X, M)
     assert oracle.stream_insert(np.zeros((0, 3, 4), np.float32), np.zeros((2, 4), np.float32)).shape == (0, 9, 4)
+
+
+# ---------------------------------------------------------------- Eq. 3 followed by a dense map (n4 + n1)
+def _sil_case(seed, B=2, T=5, gamma=3, d=12, V=7, with_f=True):
+    rng = synth.rng_for(seed)
+    M = rng.standard_normal((B, T, d)).astype(np.float32)
+    P = rng.standard_normal((gamma, d)).astype(np.float32)
+    W = rng.standard_normal((V, d)).astype(np.float32)
+    fM = rng.standard_normal((B, T, d)).astype(np.float32) if with_f else None
+    return M, P, W, fM
+
+
+@pytest.mark.parametrize("with_f", [False, True])
+def test_insert_then_project_equals_numpy_on_rows_built_by_indexing(with_f):
+    M, P, W, fM = _sil_case(3, with_f=with_f)
+    B, T, d = M.shape
+    gamma = P.shape[0]
+    Y = oracle.stream_insert_linear(M, P, W, fM)
+    src = (fM if with_f else M).astype(np.float64)
+    X = np.concatenate([M.astype(np.float64), (src[:, :, None, :] + P.astype(np.float64)[None, None]).reshape(B, T * gamma, d)], axis=1)
+    assert np.allclose(Y, X @ W.astype(np.float64).T, rtol=1e-13, atol=1e-13)
+
+
+def test_insert_then_project_is_linear_in_its_parts():
+    # main rows are M.W^T, and a stream row minus its node's f(M).W^T is P_j.W^T whatever the node
+    M, P, W, fM = _sil_case(4)
+    B, T, d = M.shape
+    gamma, V = P.shape[0], W.shape[0]
+    Y = oracle.stream_insert_linear(M, P, W, fM)
+    YM = oracle.linear_rows(M.reshape(B * T, d), W).reshape(B, T, V)
+    YF = oracle.linear_rows(fM.reshape(B * T, d), W).reshape(B, T, V)
+    YP = oracle.linear_rows(P, W)
+    assert np.allclose(Y[:, :T], YM, rtol=1e-13, atol=1e-13)
+    S = Y[:, T:].reshape(B, T, gamma, V)
+    assert np.allclose(S - YF[:, :, None, :], np.broadcast_to(YP, (B, T, gamma, V)), rtol=1e-12, atol=1e-12)
+
+
+def test_insert_then_project_special_cases():
+    M, P, W, fM = _sil_case(5)
+    B, T, d = M.shape
+    gamma, V = P.shape[0], W.shape[0]
+    # zero embeddings and identity f: every stream row equals its node's main row
+    Y0 = oracle.stream_insert_linear(M, np.zeros_like(P), W)
+    assert np.array_equal(Y0[:, T:].reshape(B, T, gamma, V), np.broadcast_to(Y0[:, :T, None, :], (B, T, gamma, V)))
+    # identity weights: the rows of Eq. 3 themselves come out
+    I = np.eye(d, dtype=np.float32)
+    assert np.allclose(oracle.stream_insert_linear(M, P, I, fM), oracle.stream_insert(M, P, fM), rtol=0, atol=1e-15)
+    # a transposed W would not have W's shape: a non-square W with one hot row picks one feature of the rows
+    W1 = np.zeros((3, d), np.float32)
+    W1[1, 4] = 2.0
+    Y1 = oracle.stream_insert_linear(M, P, W1, fM)
+    assert np.array_equal(Y1[..., 0], np.zeros_like(Y1[..., 0])) and np.allclose(Y1[..., 1], 2.0 * oracle.stream_insert(M, P, fM)[..., 4])
