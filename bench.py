@@ -246,6 +246,21 @@ def time_rows_after_hot_path(api, synth, torch, cfg, dev, N, lm, lm_ws, tok, par
     P_emb = synth.make_lm_head_inputs(synth.scaled(cfg, vocab=64, d_model=dm), 61, device=dev, N=cfg.gamma)["hidden"]
     X_rows = torch.empty(cfg.B, cfg.R, dm, dtype=hm.dtype, device=dev)
     extra["stream_insert_us"] = round(kernel_timed(lambda i: api.ss_stream_insert(hm, P_emb, X=X_rows), torch), 2)
+    # ... and Eq. 3 through the QKV projection of the first multi-stream layer: rows written out and projected, against
+    # the one call that projects the B*T states and the gamma embeddings only and adds the results
+    dq = 3 * cfg.H * cfg.D
+    wq = [synth.make_lm_head_inputs(synth.scaled(cfg, vocab=dq, d_model=dm), 62 + j, device=dev, N=8)["W"] for j in range(2)]
+    Yq = torch.empty(cfg.B, cfg.R, dq, dtype=hm.dtype, device=dev)
+    sil_ws = torch.empty(api.load_library().ss_stream_insert_linear_workspace_bytes(cfg.B, cfg.T, cfg.gamma, dm, dq, api.SS_BF16, 0),
+                         dtype=torch.uint8, device=dev)
+
+    def unfused(i):
+        api.ss_stream_insert(hm, P_emb, X=X_rows)
+        api.ss_linear_rows(X_rows.view(cfg.B * cfg.R, dm), wq[i & 1], Yq.view(cfg.B * cfg.R, dq))
+    extra["stream_insert_qkv"] = {
+        "insert_then_project_us": round(kernel_timed(unfused, torch), 2),
+        "one_call_us": round(kernel_timed(lambda i: api.ss_stream_insert_linear(hm, P_emb, wq[i & 1], Y=Yq, workspace=sil_ws), torch), 2)}
+    del wq, Yq
     # The appendix's value-rotation variant on one layer's value block [B,R,Hkv,D], in place
     v_blk = X_rows.view(cfg.B, cfg.R, cfg.Hkv, dm // cfg.Hkv) if dm % cfg.Hkv == 0 and (dm // cfg.Hkv) % 2 == 0 else None
     if v_blk is not None:

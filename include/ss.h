@@ -312,6 +312,29 @@ int ss_stream_insert(const void* M, const void* fM, const void* P, int B, int T,
                      int dtype, void* X, void* stream);
 
 /*
+ * n4 + n1 as one call: the rows of Eq. 3 through a dense map of the first
+ * multi-stream layer (Sec. 3.1: queries, keys and values are H.W^Q, H.W^K, H.W^V
+ * of the rows' hidden states), without ever forming the rows:
+ *    Y[b, i]                 = M[b,i] . W^T
+ *    Y[b, T + i*gamma + j-1] = (f(M)[b,i] + P[j-1]) . W^T = f(M)[b,i].W^T + P[j-1].W^T
+ * The map is linear, so it is applied to the B*T main-stream states (twice if
+ * fM is given) and the gamma embeddings in ONE pass over W, 1+gamma times fewer
+ * rows than the step has, and the step's rows are sums of those results.
+ *  M, fM (or NULL = identity), P as for ss_stream_insert; W [V,d]; Y [B,R,V];
+ *  all of type dtype.  Limits of ss_linear_rows (d % 64 == 0 for SS_BF16).
+ *  The three partial results are rounded to dtype before they are added (bf16:
+ *  at most three roundings of 2^-9 per element instead of the one of
+ *  ss_stream_insert + ss_linear_rows, which rounds the rows instead).
+ *  workspace: at least ss_stream_insert_linear_workspace_bytes(...) bytes
+ *  (with_f != 0 if fM is given).  Three kernels on `stream`.
+ */
+size_t ss_stream_insert_linear_workspace_bytes(int B, int T, int gamma, int d, int V, int dtype,
+                                               int with_f);
+int ss_stream_insert_linear(const void* M, const void* fM, const void* P, const void* W, int B, int T,
+                            int gamma, int d, int V, int dtype, void* Y, void* workspace,
+                            size_t workspace_bytes, void* stream);
+
+/*
  * Value rotation, the appendix's alternative to stream embeddings (ablation
  * "Value Rotation"): streams start from the main-stream state (ss_stream_insert
  * with P = 0) and, in every multi-stream layer, the value projection of stream n

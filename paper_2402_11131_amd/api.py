@@ -28,7 +28,7 @@ SS_MAX_T, SS_MAX_GAMMA, SS_MAX_K = 64, 8, 8
 EXPORTS = (
     "ss_version", "ss_last_error", "ss_probe_hbm_read", "ss_probe_mfma_bf16", "ss_check_tree_host", "ss_build_mask", "ss_msa_workspace_bytes",
     "ss_msa_attention", "ss_msa_workspace_init", "ss_msa_attention_static", "ss_msa_static_scratch_bytes", "ss_msa_plan", "ss_msa_set_split_keys", "ss_msa_set_merge_in_kernel", "ss_lm_head_workspace_bytes", "ss_lm_set_flavour", "ss_lm_set_stagger", "ss_lm_head_argmax_topk", "ss_lm_head_verify_draft",
-    "ss_tree_verify", "ss_tree_draft", "ss_full_tree_template_host", "ss_kv_commit", "ss_kv_alloc_pages", "ss_linear_rows", "ss_stream_insert", "ss_value_rotate",
+    "ss_tree_verify", "ss_tree_draft", "ss_full_tree_template_host", "ss_kv_commit", "ss_kv_alloc_pages", "ss_linear_rows", "ss_stream_insert", "ss_stream_insert_linear", "ss_stream_insert_linear_workspace_bytes", "ss_value_rotate",
     "ss_lm_head_logsumexp", "ss_transition_probs", "ss_tree_prune",
 )
 
@@ -84,6 +84,9 @@ def load_library() -> ctypes.CDLL:
     lib.ss_kv_alloc_pages.argtypes = [vp, i32, vp, vp, i32, i32, i32, vp, vp, vp, vp]
     lib.ss_linear_rows.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp]
     lib.ss_stream_insert.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp, vp]
+    lib.ss_stream_insert_linear_workspace_bytes.argtypes = [i32] * 7
+    lib.ss_stream_insert_linear_workspace_bytes.restype = sz
+    lib.ss_stream_insert_linear.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, sz, vp]
     lib.ss_value_rotate.argtypes = [vp, i32, i32, i32, i32, i32, c.c_float, i32, vp]
     lib.ss_lm_head_logsumexp.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, sz, vp]
     lib.ss_transition_probs.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp]
@@ -519,6 +522,32 @@ def ss_stream_insert(M: torch.Tensor, P: torch.Tensor, fM: Optional[torch.Tensor
     _check(lib.ss_stream_insert(_dev(M, dt, "M"), None if fM is None else _dev(fM, dt, "fM"), _dev(P, dt, "P"),
                                 B, T, gamma, d, code, _dev(X, dt, "X"), _stream()))
     return X
+
+
+def ss_stream_insert_linear(M: torch.Tensor, P: torch.Tensor, W: torch.Tensor, fM: Optional[torch.Tensor] = None,
+                            Y: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """n4 + n1 (Eq. 3 through a dense map).  M [B,T,d], P [gamma,d], W [V,d], fM = f(M) or None -> Y [B, T*(1+gamma), V]."""
+    lib = load_library()
+    code = _dtype_code(M)
+    dt = M.dtype
+    B, T, d = M.shape
+    gamma, V = P.shape[0], W.shape[0]
+    if tuple(P.shape) != (gamma, d) or tuple(W.shape) != (V, d):
+        raise ValueError("P must be [gamma,%d] and W [V,%d]" % (d, d))
+    if fM is not None and tuple(fM.shape) != (B, T, d):
+        raise ValueError("fM must have M's shape")
+    R = T * (1 + gamma)
+    if Y is None:
+        Y = torch.empty(B, R, V, dtype=dt, device=M.device)
+    elif tuple(Y.shape) != (B, R, V):
+        raise ValueError("Y must be [%d,%d,%d]" % (B, R, V))
+    need = lib.ss_stream_insert_linear_workspace_bytes(B, T, gamma, d, V, code, 0 if fM is None else 1)
+    if workspace is None:
+        workspace = torch.empty(max(need, 1), dtype=torch.uint8, device=M.device)
+    _check(lib.ss_stream_insert_linear(_dev(M, dt, "M"), None if fM is None else _dev(fM, dt, "fM"), _dev(P, dt, "P"),
+                                       _dev(W, dt, "W"), B, T, gamma, d, V, code, _dev(Y, dt, "Y"),
+                                       _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream()))
+    return Y
 
 
 def ss_value_rotate(v_new: torch.Tensor, T: int, gamma: int, eps: float) -> torch.Tensor:

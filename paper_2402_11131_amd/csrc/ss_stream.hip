@@ -60,6 +60,63 @@ __global__ __launch_bounds__(256) void stream_insert_kernel(StreamArgs a) {
   }
 }
 
+// Eq. 3 followed by a dense map, by linearity: (f(M_i) + P_j).W^T = f(M_i).W^T + P_j.W^T, so the map is applied
+// to the B*T main-stream states (and to f(M) if it is not the identity) and to the gamma embeddings only, 1+gamma
+// times fewer rows than the step has, and the step's rows are put together from the results.  pack_rows_kernel
+// gathers [M; f(M); P] into one row block for a single pass over W; expand_rows_kernel writes
+//   Y[b, i] = Z[b*T + i],   Y[b, T + i*gamma + j-1] = Zf[b*T + i] + Zp[j-1]   (sum in fp32, rounded once).
+struct PackArgs {
+  const void *M, *fM, *P;
+  void* out;   // [2*BT or BT, then gamma][d]
+  int BT, gamma, d;
+};
+template <bool BF16>
+__global__ __launch_bounds__(256) void pack_rows_kernel(PackArgs a) {
+  constexpr int ES = BF16 ? 2 : 4;
+  const int n = blockIdx.x, nf = a.fM ? a.BT : 0;
+  const unsigned char* src;
+  if (n < a.BT) src = (const unsigned char*)a.M + (size_t)n * a.d * ES;
+  else if (n < a.BT + nf) src = (const unsigned char*)a.fM + (size_t)(n - a.BT) * a.d * ES;
+  else src = (const unsigned char*)a.P + (size_t)(n - a.BT - nf) * a.d * ES;
+  unsigned char* dst = (unsigned char*)a.out + (size_t)n * a.d * ES;
+  const size_t bytes = (size_t)a.d * ES;
+  if ((bytes & 15) == 0 && ((((uintptr_t)src | (uintptr_t)dst)) & 15) == 0) {
+    for (size_t c = threadIdx.x; c < bytes / 16; c += 256)
+      reinterpret_cast<uintx4*>(dst)[c] = reinterpret_cast<const uintx4*>(src)[c];
+  } else {
+    for (size_t c = threadIdx.x; c < bytes; c += 256) dst[c] = src[c];
+  }
+}
+
+struct ExpandArgs {
+  const void* Z;  // [BT (+BT) + gamma][V]
+  void* Y;        // [B,R,V]
+  int T, gamma, V, BT, has_f;
+};
+template <bool BF16>
+__global__ __launch_bounds__(256) void expand_rows_kernel(ExpandArgs a) {
+  const int R = a.T * (1 + a.gamma);
+  const int b = blockIdx.x / R, r = blockIdx.x % R;
+  int node, strm;
+  row_split(r, a.T, a.gamma, node, strm);
+  const size_t zm = (size_t)b * a.T + node;
+  const size_t zf = a.has_f ? a.BT + zm : zm, zp = (size_t)a.BT * (a.has_f ? 2 : 1) + (strm > 0 ? strm - 1 : 0);
+  const size_t yo = ((size_t)b * R + r) * a.V;
+  for (int v = threadIdx.x; v < a.V; v += 256) {
+    if constexpr (BF16) {
+      const uint16_t* Z = (const uint16_t*)a.Z;
+      uint16_t* Y = (uint16_t*)a.Y;
+      Y[yo + v] = strm == 0 ? Z[zm * a.V + v]
+                            : (uint16_t)f32_to_bf16_bits(bf16_bits_to_f32(Z[zf * a.V + v]) + bf16_bits_to_f32(Z[zp * a.V + v]));
+    } else {
+      const float* Z = (const float*)a.Z;
+      ((float*)a.Y)[yo + v] = strm == 0 ? Z[zm * a.V + v] : Z[zf * a.V + v] + Z[zp * a.V + v];
+    }
+  }
+}
+
+static size_t sil_rows(int B, int T, int gamma, bool has_f) { return (size_t)B * T * (has_f ? 2 : 1) + gamma; }
+
 // Value rotation (appendix ablation): stream n of node i takes the node's main-row value times e^{i eps n}.
 // Features (2m, 2m+1) are (Re, Im); cos and sin of eps*n come from the host in a table (gamma <= 8 angles).
 // One workgroup per stream row; a thread turns one pair at a time (bf16: one 32-bit word).
@@ -142,5 +199,51 @@ extern "C" int ss_stream_insert(const void* M, const void* fM, const void* P, in
   const dim3 grid((unsigned)(B * T * (1 + gamma)));
   if (dtype == SS_F32) hipLaunchKernelGGL(stream_insert_kernel<false>, grid, dim3(256), 0, (hipStream_t)stream, a);
   else hipLaunchKernelGGL(stream_insert_kernel<true>, grid, dim3(256), 0, (hipStream_t)stream, a);
+  return check_launch(fn);
+}
+
+extern "C" size_t ss_stream_insert_linear_workspace_bytes(int B, int T, int gamma, int d, int V, int dtype, int with_f) {
+  ss::clear_error();
+  if (B < 0 || T < 1 || gamma < 0 || d < 1 || V < 1 || (dtype != SS_F32 && dtype != SS_BF16)) return 0;
+  const size_t n = ss::sil_rows(B, T, gamma, with_f != 0), es = dtype == SS_BF16 ? 2 : 4;
+  return ss::align_up(n * d * es, 256) + ss::align_up(n * V * es, 256) + 256;
+}
+
+extern "C" int ss_stream_insert_linear(const void* M, const void* fM, const void* P, const void* W, int B, int T,
+                                       int gamma, int d, int V, int dtype, void* Y, void* workspace,
+                                       size_t workspace_bytes, void* stream) {
+  using namespace ss;
+  clear_error();
+  const char* fn = "ss_stream_insert_linear";
+  SS_REQUIRE(B >= 0 && d >= 1 && V >= 1, SS_ERR_INVALID_ARG, "%s: B=%d d=%d V=%d", fn, B, d, V);
+  SS_REQUIRE(T >= 1 && T <= SS_MAX_T, SS_ERR_UNSUPPORTED, "%s: T=%d outside [1,%d]", fn, T, SS_MAX_T);
+  SS_REQUIRE(gamma >= 0 && gamma <= SS_MAX_GAMMA, SS_ERR_UNSUPPORTED, "%s: gamma=%d outside [0,%d]", fn, gamma,
+             SS_MAX_GAMMA);
+  SS_REQUIRE(dtype == SS_F32 || dtype == SS_BF16, SS_ERR_UNSUPPORTED, "%s: dtype %d", fn, dtype);
+  SS_REQUIRE(dtype != SS_BF16 || d % 64 == 0, SS_ERR_UNSUPPORTED, "%s: bf16 path needs d %% 64 == 0 (d=%d)", fn, d);
+  SS_REQUIRE(B == 0 || (M && W && Y && (P || gamma == 0)), SS_ERR_INVALID_ARG, "%s: NULL tensor argument", fn);
+  SS_REQUIRE((long)B * T * (1 + gamma) <= 0x7fffffffL && (long)B * T * (1 + gamma) * (long)V < (1L << 31), SS_ERR_UNSUPPORTED,
+             "%s: too large", fn);
+  const size_t need = ss_stream_insert_linear_workspace_bytes(B, T, gamma, d, V, dtype, fM != nullptr);
+  SS_REQUIRE(B == 0 || (workspace != nullptr && workspace_bytes >= need), SS_ERR_WORKSPACE,
+             "%s: workspace of %zu bytes needed, %zu given", fn, need, workspace_bytes);
+  if (B == 0) return SS_OK;
+  const bool has_f = fM != nullptr;
+  const size_t n = sil_rows(B, T, gamma, has_f), es = dtype == SS_BF16 ? 2 : 4;
+  char* ws = (char*)(((uintptr_t)workspace + 255) & ~(uintptr_t)255);
+  void* zin = ws;
+  void* z = ws + align_up(n * d * es, 256);
+  hipStream_t st = (hipStream_t)stream;
+  PackArgs p;
+  p.M = M; p.fM = fM; p.P = P ? P : M; p.out = zin; p.BT = B * T; p.gamma = gamma; p.d = d;
+  if (dtype == SS_F32) hipLaunchKernelGGL(pack_rows_kernel<false>, dim3((unsigned)n), dim3(256), 0, st, p);
+  else hipLaunchKernelGGL(pack_rows_kernel<true>, dim3((unsigned)n), dim3(256), 0, st, p);
+  if (int rc = check_launch(fn)) return rc;
+  if (int rc = ss_linear_rows(zin, W, (int)n, d, V, dtype, z, stream)) return rc;
+  ExpandArgs e;
+  e.Z = z; e.Y = Y; e.T = T; e.gamma = gamma; e.V = V; e.BT = B * T; e.has_f = has_f ? 1 : 0;
+  const dim3 grid((unsigned)(B * T * (1 + gamma)));
+  if (dtype == SS_F32) hipLaunchKernelGGL(expand_rows_kernel<false>, grid, dim3(256), 0, st, e);
+  else hipLaunchKernelGGL(expand_rows_kernel<true>, grid, dim3(256), 0, st, e);
   return check_launch(fn);
 }

@@ -90,3 +90,61 @@ def test_empty_batch_and_bad_shapes():
         api.ss_stream_insert(torch.zeros(1, 4, 16, device=DEV), torch.zeros(2, 8, device=DEV))
     with pytest.raises(api.SSError):      # T above the tree limit
         api.ss_stream_insert(torch.zeros(1, 65, 16, device=DEV), torch.zeros(2, 16, device=DEV))
+
+
+# ---------------------------------------------------------------- Eq. 3 through a dense map in one call (n4 + n1)
+def _check_linear(B, T, gamma, d, V, dtype, seed, with_f):
+    M, P, fM = _inputs(B, T, gamma, d, dtype, seed, with_f)
+    W = _normal(synth.rng_for(seed + 1000), (V, d), 0.02 if dtype == torch.bfloat16 else 0.2).to(dtype)
+    dev = lambda t: None if t is None else t.to(DEV)
+    Y = api.ss_stream_insert_linear(dev(M), dev(P), dev(W), dev(fM))
+    # the unfused pair of calls: rows of Eq. 3 written out, then the projection
+    Y2 = api.ss_linear_rows(api.ss_stream_insert(dev(M), dev(P), dev(fM)).view(B * T * (1 + gamma), d), dev(W))
+    torch.cuda.synchronize()
+    assert Y.dtype == dtype and tuple(Y.shape) == (B, T * (1 + gamma), V)
+    f = lambda t: None if t is None else to_np_f32(t)
+    ref = oracle.stream_insert_linear(f(M), f(P), f(W), f(fM))
+    # What the call rounds: the partial results f(M).W^T and P.W^T (to the storage type), then their sum.  With
+    # fp32 accumulation on top (1e-5 of sum |x_e||w_e| bounds it generously):
+    #   |got - ref| <= u (|f(M).W^T| + |P.W^T| + |ref|) + 1e-5 S,   u = 2^-8 for bf16 (one rounding is 2^-9), 0 for fp32
+    src = f(fM) if with_f else f(M)
+    ZF = oracle.linear_rows(src.reshape(B * T, d), f(W)).reshape(B, T, 1, V)
+    ZP = oracle.linear_rows(f(P), f(W))[None, None]
+    part = np.concatenate([np.zeros((B, T, V)), (np.abs(ZF) + np.abs(ZP)).reshape(B, T * gamma, V)], axis=1)
+    S_main = oracle.linear_rows(np.abs(f(M)).reshape(B * T, d), np.abs(f(W))).reshape(B, T, V)
+    S_str = oracle.linear_rows(np.abs(src).reshape(B * T, d), np.abs(f(W))).reshape(B, T, 1, V) + oracle.linear_rows(np.abs(f(P)), np.abs(f(W)))[None, None]
+    S = np.concatenate([S_main, S_str.reshape(B, T * gamma, V)], axis=1)
+    got = to_np_f32(Y.cpu()).astype(np.float64)
+    u = 0.0 if dtype == torch.float32 else 2.0 ** -8
+    assert (np.abs(got - ref) <= u * (part + np.abs(ref)) + 1e-5 * S).all()
+    # and it agrees with the unfused pair of calls to within the roundings both make (that pair rounds the rows of
+    # Eq. 3 to the storage type before the projection: u S bounds the effect)
+    assert (np.abs(got - to_np_f32(Y2.cpu()).reshape(got.shape)) <= u * (part + 2 * np.abs(ref)) + (u + 2e-5) * S).all()
+    # main rows are exactly what the projection alone gives for M
+    Ym = api.ss_linear_rows(dev(M).view(B * T, d), dev(W))
+    torch.cuda.synchronize()
+    assert torch.equal(Y[:, :T].reshape(B * T, V), Ym)
+
+
+@pytest.mark.parametrize("with_f", [False, True])
+def test_insert_linear_bf16(with_f):
+    _check_linear(3, 7, 3, 320, 1000, torch.bfloat16, 11, with_f)
+
+
+@pytest.mark.parametrize("with_f", [False, True])
+def test_insert_linear_fp32(with_f):
+    _check_linear(2, 5, 2, 40, 77, torch.float32, 12, with_f)
+
+
+def test_insert_linear_c4_qkv_shape():
+    cfg = synth.CONFIGS["c4"]
+    _check_linear(cfg.B, cfg.T, cfg.gamma, cfg.d_model, 3 * cfg.H * cfg.D, torch.bfloat16, 13, False)
+
+
+def test_insert_linear_gamma_zero_and_workspace_check():
+    M, P, fM = _inputs(2, 4, 1, 64, torch.bfloat16, 14)
+    W = _normal(synth.rng_for(15), (128, 64), 0.05).to(torch.bfloat16)
+    Y = api.ss_stream_insert_linear(M.to(DEV), P[:0].to(DEV), W.to(DEV))           # no streams: the projection of M
+    assert torch.equal(Y.view(8, 128), api.ss_linear_rows(M.to(DEV).view(8, 64), W.to(DEV)))
+    with pytest.raises(api.SSError):
+        api.ss_stream_insert_linear(M.to(DEV), P.to(DEV), W.to(DEV), workspace=torch.empty(16, dtype=torch.uint8, device=DEV))
