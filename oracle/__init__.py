@@ -280,3 +280,65 @@ def stream_insert_linear(M, P, W, fM=None):
     Y = np.zeros((B, T * (1 + gamma), V), np.float64)
     _load().ora_stream_insert_linear(_p(M), _p(fM), _p(P), _p(W), B, T, gamma, d, V, _p(Y))
     return Y
+
+
+# ------------------------------------------------------------------ pruned trees (Sec. 3.2.3)
+# After pruning, sequence b keeps the nodes 0 .. n_nodes[b]-1 of its (compacted) tree; the other entries of the
+# T-node arrays are padding.  The step on a pruned tree IS the step on the smaller tree: these functions cut every
+# sequence down to its kept nodes, run the definitions above on that, and put the rows back where the T-node row
+# order has them; rows of padding nodes come back as zeros.
+
+def live_rows(n_nodes, T: int, gamma: int):
+    """Row numbers b*R + r (ascending) of the rows whose node is kept: main rows r = i and stream rows
+    r = T + i*gamma + (j-1) of the nodes i < n_nodes[b]."""
+    R = T * (1 + gamma)
+    rows = []
+    for b, n in enumerate(np.asarray(n_nodes).tolist()):
+        n = max(1, min(int(n), T))
+        rows += [b * R + i for i in range(n)]
+        rows += [b * R + T + i * gamma + j for i in range(n) for j in range(gamma)]
+    return np.asarray(rows, np.int32)
+
+
+def msa_attention_pruned(q, k_new, v_new, k_cache, v_cache, block_table, seq_lens, parent, gamma: int, scale: float,
+                         n_nodes, flags: int = 0):
+    """a2 on pruned trees.  Arrays as for msa_attention (T-node layout); n_nodes [B].  Returns out [B,R,H,D]
+    float64, zero in the rows of padding nodes."""
+    q, k_new, v_new = _f32(q), _f32(k_new), _f32(v_new)
+    block_table, seq_lens, parent = _i32(block_table), _i32(seq_lens), _i32(parent)
+    B, R, H, D = q.shape
+    T = parent.shape[1]
+    out = np.zeros((B, R, H, D), np.float64)
+    for b in range(B):
+        n = max(1, min(int(n_nodes[b]), T))
+        rows = live_rows([n], T, gamma)                      # rows of this sequence, in the order of the n-node tree
+        sub = msa_attention(q[b:b + 1, rows], k_new[b:b + 1, rows], v_new[b:b + 1, rows], k_cache, v_cache,
+                            block_table[b:b + 1], seq_lens[b:b + 1], parent[b:b + 1, :n], gamma, scale, flags)
+        out[b, rows] = sub[0]
+    return out
+
+
+def linear_rows_live(x, W, rows):
+    """n1 on the kept rows only: y [N,V] float64, zero elsewhere."""
+    x = _f32(x)
+    y = np.zeros((x.shape[0], np.asarray(W).shape[0]), np.float64)
+    rows = np.asarray(rows, np.int64)
+    if rows.size:
+        y[rows] = linear_rows(x[rows], W)
+    return y
+
+
+def lm_head_topk_live(hidden, W, K: int, rows, want_logits: bool = False):
+    """a3 on the kept rows only: (idx, val[, logits]) with idx -1 and val / logits 0 in the other rows."""
+    hidden = _f32(hidden)
+    N, V = hidden.shape[0], np.asarray(W).shape[0]
+    rows = np.asarray(rows, np.int64)
+    idx = -np.ones((N, K), np.int32)
+    val = np.zeros((N, K), np.float64)
+    z = np.zeros((N, V), np.float64) if want_logits else None
+    if rows.size:
+        r = lm_head_topk(hidden[rows], W, K, want_logits=want_logits)
+        idx[rows], val[rows] = r[0], r[1]
+        if want_logits:
+            z[rows] = r[2]
+    return (idx, val, z) if want_logits else (idx, val)
