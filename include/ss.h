@@ -511,6 +511,57 @@ int ss_kv_commit(const void* k_new, const void* v_new, void* k_cache, void* v_ca
                  int32_t* new_seq_lens, void* stream);
 
 /*
+ * n2, making pruning pay (Sec. 3.2.3: pruning exists to keep the step from
+ * becoming compute-bound).  After ss_tree_prune sequence b keeps the nodes
+ * 0 .. n_nodes[b]-1 of its compacted tree and the arrays are padded back to T
+ * nodes; the calls below take n_nodes (or the list of kept rows made from it)
+ * and do not compute the rows of padding nodes.  Everything stays on the device:
+ * no call needs the counts on the host.
+ *
+ * ss_live_rows: live_rows[0 .. *n_live) = the rows b*R + r, ascending, of the
+ *  kept nodes (main row r = i, stream rows r = T + i*gamma + j-1 for i <
+ *  n_nodes[b], clamped to [1,T]); live_rows [B*R] int32, n_live [1] int32.
+ *
+ * ss_msa_attention_pruned: ss_msa_attention with n_nodes [B]: the rows of
+ *  padding nodes are neither computed nor written (`out` keeps what it held
+ *  there); the kept rows are packed into the first row chunks of a launch, so
+ *  that whole workgroups leave at once; kept rows are those of
+ *  ss_msa_attention up to floating-point summation order (padding nodes hang
+ *  off the root, so no kept row attends to them).
+ *
+ * ss_linear_rows_live, ss_lm_head_argmax_topk_live, ss_lm_head_verify_draft_live:
+ *  the calls without the suffix, computing only the rows listed in live_rows
+ *  (device, ascending, *n_live of them) and leaving every other row of their
+ *  outputs untouched.  plan_rows (HOST) is the number of rows the launch is
+ *  shaped for: 0 = all N; a smaller number, e.g. what a serving loop expects to
+ *  survive pruning, lets fewer, fuller workgroups do the work; if more rows turn
+ *  out to be listed than planned for, workgroups take several row chunks in turn
+ *  (slower, never wrong).
+ */
+int ss_live_rows(const int32_t* n_nodes, int B, int T, int gamma, int32_t* live_rows, int32_t* n_live,
+                 void* stream);
+int ss_msa_attention_pruned(const void* q, const void* k_new, const void* v_new, const void* k_cache,
+                            const void* v_cache, const int32_t* block_table, int max_pages_per_seq,
+                            int num_pages, const int32_t* seq_lens, const int32_t* parent,
+                            const int32_t* n_nodes, int B, int T, int gamma, int H, int Hkv, int D,
+                            int page_size, float scale, int dtype, uint32_t flags, void* out,
+                            void* workspace, size_t workspace_bytes, void* stream);
+int ss_linear_rows_live(const void* x, const void* W, int N, int d, int V, int dtype, void* y,
+                        const int32_t* live_rows, const int32_t* n_live, int plan_rows, void* stream);
+int ss_lm_head_argmax_topk_live(const void* hidden, const void* W, int N, int d, int V, int K, int dtype,
+                                int32_t* idx, float* val, const int32_t* live_rows,
+                                const int32_t* n_live, int plan_rows, void* workspace,
+                                size_t workspace_bytes, void* stream);
+int ss_lm_head_verify_draft_live(const void* hidden, const void* W, int d, int V, int K, int dtype,
+                                 const int32_t* tok, const int32_t* parent, int B, int T, int gamma,
+                                 int max_depth, const int32_t* tmpl_parent, const int32_t* tmpl_rank,
+                                 const int32_t* branching, int T2, int32_t* n_accept, int32_t* last,
+                                 int32_t* bonus, int32_t* path, int32_t* out_tokens, int32_t* next_tok,
+                                 int32_t* next_parent, int32_t* main_argmax, const int32_t* live_rows,
+                                 const int32_t* n_live, int plan_rows, void* workspace,
+                                 size_t workspace_bytes, void* stream);
+
+/*
  * n3, page allocation (Appendix A.1: the cache grows by the accepted tokens
  * after every generation step).  Sequence b uses the first
  * ceil(seq_lens[b]/page_size) entries of its block-table row; its accepted path

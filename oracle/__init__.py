@@ -286,7 +286,8 @@ def stream_insert_linear(M, P, W, fM=None):
 # After pruning, sequence b keeps the nodes 0 .. n_nodes[b]-1 of its (compacted) tree; the other entries of the
 # T-node arrays are padding.  The step on a pruned tree IS the step on the smaller tree: these functions cut every
 # sequence down to its kept nodes, run the definitions above on that, and put the rows back where the T-node row
-# order has them; rows of padding nodes come back as zeros.
+# order has them; rows of padding nodes come back as zeros (the kernels leave them untouched: tests compare the
+# kept rows).
 
 def live_rows(n_nodes, T: int, gamma: int):
     """Row numbers b*R + r (ascending) of the rows whose node is kept: main rows r = i and stream rows

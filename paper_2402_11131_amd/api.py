@@ -29,7 +29,8 @@ EXPORTS = (
     "ss_version", "ss_last_error", "ss_probe_hbm_read", "ss_probe_mfma_bf16", "ss_check_tree_host", "ss_build_mask", "ss_msa_workspace_bytes",
     "ss_msa_attention", "ss_msa_workspace_init", "ss_msa_attention_static", "ss_msa_static_scratch_bytes", "ss_msa_plan", "ss_msa_set_split_keys", "ss_msa_set_merge_in_kernel", "ss_lm_head_workspace_bytes", "ss_lm_set_flavour", "ss_lm_set_stagger", "ss_lm_head_argmax_topk", "ss_lm_head_verify_draft",
     "ss_tree_verify", "ss_tree_draft", "ss_full_tree_template_host", "ss_kv_commit", "ss_kv_alloc_pages", "ss_linear_rows", "ss_stream_insert", "ss_stream_insert_linear", "ss_stream_insert_linear_workspace_bytes", "ss_value_rotate",
-    "ss_lm_head_logsumexp", "ss_transition_probs", "ss_tree_prune",
+    "ss_lm_head_logsumexp", "ss_transition_probs", "ss_tree_prune", "ss_live_rows", "ss_msa_attention_pruned",
+    "ss_linear_rows_live", "ss_lm_head_argmax_topk_live", "ss_lm_head_verify_draft_live",
 )
 
 _lib = None
@@ -91,6 +92,12 @@ def load_library() -> ctypes.CDLL:
     lib.ss_lm_head_logsumexp.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, sz, vp]
     lib.ss_transition_probs.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp]
     lib.ss_tree_prune.argtypes = [vp, vp, vp, c.c_float, i32, i32, vp, vp, vp, vp, vp, vp]
+    lib.ss_live_rows.argtypes = [vp, i32, i32, i32, vp, vp, vp]
+    lib.ss_msa_attention_pruned.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32,
+                                            c.c_float, i32, u32, vp, vp, sz, vp]
+    lib.ss_linear_rows_live.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, vp, i32, vp]
+    lib.ss_lm_head_argmax_topk_live.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, i32, vp, sz, vp]
+    lib.ss_lm_head_verify_draft_live.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, i32, i32, i32, i32, vp, vp, vp, i32] + [vp] * 8 + [vp, vp, i32, vp, sz, vp]
     for name in EXPORTS:
         getattr(lib, name)
     _lib = lib
@@ -209,10 +216,11 @@ def _msa_shapes(q, k_new, v_new, k_cache, v_cache, block_table, seq_lens, parent
 
 def ss_msa_attention(q, k_new, v_new, k_cache, v_cache, block_table, seq_lens, parent, gamma: int, scale: float,
                      flags: int = 0, out: Optional[torch.Tensor] = None,
-                     workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+                     workspace: Optional[torch.Tensor] = None, n_nodes: Optional[torch.Tensor] = None) -> torch.Tensor:
     """a2.  q [B,R,H,D]; k_new, v_new [B,R,Hkv,D]; k_cache [P,Hkv,page,D]; v_cache [P,Hkv,D,page];
     block_table [B,max_pages] int32; seq_lens [B] int32; parent [B,T] int32.  Returns out [B,R,H,D].
-    `workspace`: a tensor from ss_msa_workspace (zero-filled once); made here if not given."""
+    `workspace`: a tensor from ss_msa_workspace (zero-filled once); made here if not given.
+    `n_nodes` [B] int32 (after pruning): ss_msa_attention_pruned is called, rows of padding nodes are left untouched."""
     lib = load_library()
     dt = q.dtype
     code = _dtype_code(q)
@@ -222,6 +230,16 @@ def ss_msa_attention(q, k_new, v_new, k_cache, v_cache, block_table, seq_lens, p
         out = torch.empty_like(q)
     if workspace is None:
         workspace = ss_msa_workspace(B, T, gamma, H, Hkv, D, max_pages * page, code, q.device)
+    if n_nodes is not None:
+        if tuple(n_nodes.shape) != (B,):
+            raise ValueError("n_nodes must be [B]")
+        _check(lib.ss_msa_attention_pruned(
+            _dev(q, dt, "q"), _dev(k_new, dt, "k_new"), _dev(v_new, dt, "v_new"), _dev(k_cache, dt, "k_cache"),
+            _dev(v_cache, dt, "v_cache"), _dev(block_table, torch.int32, "block_table"), max_pages, P,
+            _dev(seq_lens, torch.int32, "seq_lens"), _dev(parent, torch.int32, "parent"), _dev(n_nodes, torch.int32, "n_nodes"),
+            B, T, gamma, H, Hkv, D, page, float(scale), code, flags, _dev(out, dt, "out"),
+            _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream()))
+        return out
     _check(lib.ss_msa_attention(
         _dev(q, dt, "q"), _dev(k_new, dt, "k_new"), _dev(v_new, dt, "v_new"), _dev(k_cache, dt, "k_cache"),
         _dev(v_cache, dt, "v_cache"), _dev(block_table, torch.int32, "block_table"), max_pages, P,
@@ -229,6 +247,20 @@ def ss_msa_attention(q, k_new, v_new, k_cache, v_cache, block_table, seq_lens, p
         float(scale), code, flags, _dev(out, dt, "out"), _dev(workspace, torch.uint8, "workspace"),
         workspace.numel(), _stream()))
     return out
+
+
+def ss_live_rows(n_nodes: torch.Tensor, T: int, gamma: int, live_rows: Optional[torch.Tensor] = None,
+                 n_live: Optional[torch.Tensor] = None):
+    """Rows of the kept nodes after pruning: (live_rows [B*R] int32, of which the first n_live[0] count; n_live [1])."""
+    B = n_nodes.shape[0]
+    i32 = torch.int32
+    if live_rows is None:
+        live_rows = torch.empty(max(B * T * (1 + gamma), 1), dtype=i32, device=n_nodes.device)
+    if n_live is None:
+        n_live = torch.empty(1, dtype=i32, device=n_nodes.device)
+    _check(load_library().ss_live_rows(_dev(n_nodes, i32, "n_nodes"), B, T, gamma, _dev(live_rows, i32, "live_rows"),
+                                       _dev(n_live, i32, "n_live"), _stream()))
+    return live_rows, n_live
 
 
 def ss_msa_static_scratch_bytes() -> int:
@@ -271,8 +303,9 @@ def ss_lm_set_stagger(blocks: int) -> int:
     return load_library().ss_lm_set_stagger(int(blocks))
 
 
-def ss_lm_head_argmax_topk(hidden, W, K: int, idx=None, val=None, workspace=None):
-    """a3.  hidden [N,d], W [V,d] -> (idx [N,K] int32, val [N,K] float32)."""
+def ss_lm_head_argmax_topk(hidden, W, K: int, idx=None, val=None, workspace=None, live=None, plan_rows: int = 0):
+    """a3.  hidden [N,d], W [V,d] -> (idx [N,K] int32, val [N,K] float32).  `live` = (live_rows, n_live) from
+    ss_live_rows: only those rows are computed (the others of idx / val are left as they are)."""
     lib = load_library()
     dt = hidden.dtype
     code = _dtype_code(hidden)
@@ -287,6 +320,13 @@ def ss_lm_head_argmax_topk(hidden, W, K: int, idx=None, val=None, workspace=None
     need = lib.ss_lm_head_workspace_bytes(N, d, V, K, code)
     if workspace is None:
         workspace = torch.empty(max(need, 1), dtype=torch.uint8, device=hidden.device)
+    if live is not None:
+        _check(lib.ss_lm_head_argmax_topk_live(_dev(hidden, dt, "hidden"), _dev(W, dt, "W"), N, d, V, K, code,
+                                               _dev(idx, torch.int32, "idx"), _dev(val, torch.float32, "val"),
+                                               _dev(live[0], torch.int32, "live_rows"), _dev(live[1], torch.int32, "n_live"),
+                                               int(plan_rows), _dev(workspace, torch.uint8, "workspace"), workspace.numel(),
+                                               _stream()))
+        return idx, val
     _check(lib.ss_lm_head_argmax_topk(_dev(hidden, dt, "hidden"), _dev(W, dt, "W"), N, d, V, K, code,
                                       _dev(idx, torch.int32, "idx"), _dev(val, torch.float32, "val"),
                                       _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream()))
@@ -385,7 +425,7 @@ def ss_tree_draft(stream_topk, K: int, last, bonus, T: int, gamma: int, tmpl_par
 
 def ss_lm_head_verify_draft(hidden, W, K: int, tok, parent, gamma: int, max_depth: int, tmpl_parent=None,
                             tmpl_rank=None, branching: Optional[Sequence[int]] = None, T2: Optional[int] = None,
-                            workspace=None, out: Optional[dict] = None) -> dict:
+                            workspace=None, out: Optional[dict] = None, live=None, plan_rows: int = 0) -> dict:
     """a3 + a4 + a5 in one call.  hidden [B*T*(1+gamma), d] (main rows of a sequence first, then its stream
     rows node by node), W [V,d], tok/parent [B,T] int32.  Returns the outputs of ss_tree_verify plus next_tok
     [B,T2], next_parent [T2] and main_argmax [B,T]; `out` (a dict from an earlier call) is reused if given."""
@@ -428,13 +468,17 @@ def ss_lm_head_verify_draft(hidden, W, K: int, tok, parent, gamma: int, max_dept
     need = lib.ss_lm_head_workspace_bytes(N, d, V, K, code)
     if workspace is None:
         workspace = torch.empty(max(need, 1), dtype=torch.uint8, device=dev)
-    _check(lib.ss_lm_head_verify_draft(
-        _dev(hidden, dt, "hidden"), _dev(W, dt, "W"), d, V, K, code, _dev(tok, i32, "tok"), _dev(parent, i32, "parent"),
-        B, T, gamma, max_depth, None if tmpl_parent is None else _dev(tmpl_parent, i32, "tmpl_parent"),
-        None if tmpl_rank is None else _dev(tmpl_rank, i32, "tmpl_rank"), br_ptr, T2,
-        *[_dev(out[k], i32, k) for k in ("n_accept", "last", "bonus", "path", "out_tokens", "next_tok", "next_parent",
-                                        "main_argmax")],
-        _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream()))
+    head = (_dev(hidden, dt, "hidden"), _dev(W, dt, "W"), d, V, K, code, _dev(tok, i32, "tok"), _dev(parent, i32, "parent"),
+            B, T, gamma, max_depth, None if tmpl_parent is None else _dev(tmpl_parent, i32, "tmpl_parent"),
+            None if tmpl_rank is None else _dev(tmpl_rank, i32, "tmpl_rank"), br_ptr, T2,
+            *[_dev(out[k], i32, k) for k in ("n_accept", "last", "bonus", "path", "out_tokens", "next_tok", "next_parent",
+                                            "main_argmax")])
+    if live is not None:
+        _check(lib.ss_lm_head_verify_draft_live(*head, _dev(live[0], i32, "live_rows"), _dev(live[1], i32, "n_live"),
+                                                int(plan_rows), _dev(workspace, torch.uint8, "workspace"), workspace.numel(),
+                                                _stream()))
+    else:
+        _check(lib.ss_lm_head_verify_draft(*head, _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream()))
     return out
 
 
@@ -485,8 +529,10 @@ def ss_kv_alloc_pages(block_table, seq_lens, n_accept, page: int, max_depth: int
     return n_commit
 
 
-def ss_linear_rows(x: torch.Tensor, W: torch.Tensor, y: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """n1.  y [N,V] = x [N,d] . W[V,d]^T in the inputs' dtype (fp32 or bf16)."""
+def ss_linear_rows(x: torch.Tensor, W: torch.Tensor, y: Optional[torch.Tensor] = None, live=None,
+                   plan_rows: int = 0) -> torch.Tensor:
+    """n1.  y [N,V] = x [N,d] . W[V,d]^T in the inputs' dtype (fp32 or bf16).  `live` = (live_rows, n_live) from
+    ss_live_rows: only those rows are computed (the others of y are left as they are)."""
     lib = load_library()
     code = _dtype_code(x)
     dt = x.dtype
@@ -498,6 +544,11 @@ def ss_linear_rows(x: torch.Tensor, W: torch.Tensor, y: Optional[torch.Tensor] =
         y = torch.empty(N, V, dtype=dt, device=x.device)
     elif tuple(y.shape) != (N, V):
         raise ValueError("y must be [%d,%d]" % (N, V))
+    if live is not None:
+        _check(lib.ss_linear_rows_live(_dev(x, dt, "x"), _dev(W, dt, "W"), N, d, V, code, _dev(y, dt, "y"),
+                                       _dev(live[0], torch.int32, "live_rows"), _dev(live[1], torch.int32, "n_live"),
+                                       int(plan_rows), _stream()))
+        return y
     _check(lib.ss_linear_rows(_dev(x, dt, "x"), _dev(W, dt, "W"), N, d, V, code, _dev(y, dt, "y"), _stream()))
     return y
 

@@ -28,7 +28,17 @@ struct LmArgs {
   float* val;          // [N,K]
   void* y;             // [N,V], plain-projection flavour only (same type as the inputs)
   float* lse;          // [N], log-sum-exp flavour only; its parts (max, sum) per (row, tile) use cand_key's memory
+  const int32_t* live_rows;  // rows to compute, ascending ([N], the first *n_live entries count), or NULL = all N rows
+  const int32_t* n_live;     // [1] device, or NULL
 };
+
+// Rows a launch computes, and the row of `hidden` / of the outputs that its r-th computed row is (r is clamped
+// to the last computed row, ids to [0,N): addresses formed from them are always valid).
+SS_DEV int lm_rows(const LmArgs& a) { return a.n_live ? min(max(*a.n_live, 0), a.N) : a.N; }
+SS_DEV int lm_row_id(const LmArgs& a, int r, int n_rows) {
+  const int rc = min(r, n_rows - 1);
+  return a.live_rows ? min(max(a.live_rows[rc], 0), a.N - 1) : rc;
+}
 
 SS_DEV bool cand_better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
 SS_DEV bool cand_after(float v, int i, float pv, int pi) { return v < pv || (v == pv && i > pi); }
@@ -72,6 +82,8 @@ __global__ __launch_bounds__(256) void lm_head_f32_kernel(LmArgs a) {
   __shared__ float Z[BM][BN + 1];
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
   const int v0 = blockIdx.x * BN, r0 = blockIdx.y * BM;
+  const int n_rows = lm_rows(a);
+  if (r0 >= n_rows) return;
   const float* hidden = (const float*)a.hidden;
   const float* W = (const float*)a.W;
   float acc[BM / 4];
@@ -81,7 +93,7 @@ __global__ __launch_bounds__(256) void lm_head_f32_kernel(LmArgs a) {
     __syncthreads();
     for (int e = tid; e < BM * BK; e += 256) {
       const int r = e / BK, kk = e % BK;
-      As[r][kk] = (r0 + r < a.N && k0 + kk < a.d) ? hidden[(size_t)(r0 + r) * a.d + k0 + kk] : 0.f;
+      As[r][kk] = (r0 + r < n_rows && k0 + kk < a.d) ? hidden[(size_t)lm_row_id(a, r0 + r, n_rows) * a.d + k0 + kk] : 0.f;
     }
     for (int e = tid; e < BN * BK; e += 256) {
       const int cc = e / BK, kk = e % BK;
@@ -99,7 +111,7 @@ __global__ __launch_bounds__(256) void lm_head_f32_kernel(LmArgs a) {
 #pragma unroll
     for (int i = 0; i < BM / 4; ++i) {
       const int row = r0 + w + 4 * i, col = v0 + lane;
-      if (row < a.N && col < a.V) ((float*)a.y)[(size_t)row * a.V + col] = acc[i];
+      if (row < n_rows && col < a.V) ((float*)a.y)[(size_t)lm_row_id(a, row, n_rows) * a.V + col] = acc[i];
     }
     return;
   }
@@ -108,8 +120,8 @@ __global__ __launch_bounds__(256) void lm_head_f32_kernel(LmArgs a) {
   __syncthreads();
   if constexpr (MODE == 2) {
     for (int rr = w; rr < BM; rr += 4) {
-      const int row = r0 + rr;
-      if (row >= a.N) break;
+      if (r0 + rr >= n_rows) break;
+      const int row = lm_row_id(a, r0 + rr, n_rows);
       float2 p = v0 + lane < a.V ? make_float2(Z[rr][lane], 1.f) : make_float2(-INFINITY, 0.f);
       for (int off = 32; off > 0; off >>= 1)
         p = lse_merge(p, make_float2(__shfl_xor(p.x, off, 64), __shfl_xor(p.y, off, 64)));
@@ -119,8 +131,8 @@ __global__ __launch_bounds__(256) void lm_head_f32_kernel(LmArgs a) {
   }
   // wave w selects for rows w, w+4, ...: K rounds of a wave-wide arg-max over the 64 columns
   for (int rr = w; rr < BM; rr += 4) {
-    const int row = r0 + rr;
-    if (row >= a.N) break;
+    if (r0 + rr >= n_rows) break;
+    const int row = lm_row_id(a, r0 + rr, n_rows);
     const int col = v0 + lane;
     const float v = col < a.V ? Z[rr][lane] : -INFINITY;
     const int ci = col < a.V ? col : INT_MAX;
@@ -245,8 +257,8 @@ struct TopList {  // the KT best keys seen so far, best first
 // and token id v0 + 8*(e/4) + 4*lh + e%4.  `hbuf` (64*NW + 16 bytes per row of the tile) must be free:
 // the callers end their loops with a barrier.
 template <int NRT, int KT, int NW>  // NW waves of 32 ids each
-SS_DEV void lm_epilogue(const LmArgs& a, floatx16 (&acc)[NRT], unsigned char* hbuf, int tile, int row0, int v0, int w,
-                        int tid) {
+SS_DEV void lm_epilogue(const LmArgs& a, floatx16 (&acc)[NRT], unsigned char* hbuf, int tile, int row0, int n_rows, int v0,
+                        int w, int tid) {
   constexpr int ROWS = 32 * NRT;
   constexpr int TI = 32 * NW;  // ids per tile
   const int lane = tid & 63, ln = lane & 31, lh = lane >> 5;
@@ -273,7 +285,7 @@ SS_DEV void lm_epilogue(const LmArgs& a, floatx16 (&acc)[NRT], unsigned char* hb
       float2 p = pairs[r * NW];
 #pragma unroll
       for (int j = 1; j < NW; ++j) p = lse_merge(p, pairs[r * NW + j]);
-      if (row0 + r < a.N) reinterpret_cast<float2*>(a.cand_key)[(size_t)(row0 + r) * a.n_tiles + tile] = p;
+      if (row0 + r < n_rows) reinterpret_cast<float2*>(a.cand_key)[(size_t)lm_row_id(a, row0 + r, n_rows) * a.n_tiles + tile] = p;
     }
     return;
   } else if constexpr (KT == 0) {
@@ -295,8 +307,9 @@ SS_DEV void lm_epilogue(const LmArgs& a, floatx16 (&acc)[NRT], unsigned char* hb
     uint16_t* y = (uint16_t*)a.y;
     for (int p = tid; p < ROWS * (TI / 8); p += 64 * NW) {
       const int r = p / (TI / 8), ch = p % (TI / 8);
-      const int row = row0 + r, id0 = tile * TI + 8 * ch;
-      if (row >= a.N || id0 >= a.V) continue;
+      const int id0 = tile * TI + 8 * ch;
+      if (row0 + r >= n_rows || id0 >= a.V) continue;
+      const int row = lm_row_id(a, row0 + r, n_rows);
       const uintx4 piece = *reinterpret_cast<const uintx4*>(hbuf + r * YS + ch * 16);
       uint16_t* dst = y + (size_t)row * a.V + id0;
       if (vec_ok) {
@@ -356,8 +369,8 @@ SS_DEV void lm_epilogue(const LmArgs& a, floatx16 (&acc)[NRT], unsigned char* hb
       head[j] = L[j * KT];
       pos[j] = 0;
     }
-    const int row = row0 + r;
-    const size_t o = ((size_t)row * a.n_tiles + tile) * a.K;
+    const bool row_ok = row0 + r < n_rows;
+    const size_t o = ((size_t)lm_row_id(a, row0 + r, n_rows) * a.n_tiles + tile) * a.K;
 #pragma unroll
     for (int k = 0; k < KT; ++k) {
       uint64_t best = head[0];
@@ -368,7 +381,7 @@ SS_DEV void lm_epilogue(const LmArgs& a, floatx16 (&acc)[NRT], unsigned char* hb
         best = up ? head[j] : best;
         bw = up ? j : bw;
       }
-      if (row < a.N && k < a.K) a.cand_key[o + k] = best;
+      if (row_ok && k < a.K) a.cand_key[o + k] = best;
       if (k + 1 < KT) {
         // the winner's list moves on (lists are distinct ids, so the winner is unique unless all heads are empty)
         int np = 0;
@@ -415,7 +428,7 @@ __global__ __launch_bounds__(64 * NW, 1) void lm_head_bf16_kernel(LmArgs a) {
   const int tile = (turn / a.n_chunks) * 8 + xcd;
   if (tile >= a.n_tiles) return;
   const int v0 = tile * TI + 32 * w;
-  const int row0 = (turn % a.n_chunks) * ROWS;
+  const int n_rows = lm_rows(a);
   const int d = a.d, n_k = d / 64;
   // Feature blocks are walked from a start that differs from tile to tile (by one block between neighbours,
   // when the host asks for it) and wrap around: workgroups that all read the same 128-byte column of W's rows
@@ -424,6 +437,9 @@ __global__ __launch_bounds__(64 * NW, 1) void lm_head_bf16_kernel(LmArgs a) {
   const int k_start = (tile * a.k_stagger) % n_k;
   auto blk = [&](int J) { const int p = J + k_start; return p >= n_k ? p - n_k : p; };
 
+  // Row chunks of this workgroup: one, unless the launch was shaped for fewer rows than turn out to be computed
+  // (the number of listed rows lives on the device); none if its chunk lies behind the last computed row.
+  for (int row0 = (turn % a.n_chunks) * ROWS; row0 < n_rows; row0 += a.n_chunks * ROWS) {
   // load slots of 8 rows x 128 bytes; lane -> (row lane/8 of the slot, chunk position lane%8, which
   // receives chunk (lane%8) ^ swizzle(row)).  hidden: wave w takes slots w, w+NW, ...; W: its own rows.
   uint32_t h_voff[NH], w_voff[4];
@@ -432,7 +448,7 @@ __global__ __launch_bounds__(64 * NW, 1) void lm_head_bf16_kernel(LmArgs a) {
   for (int i = 0; i < NH; ++i) {
     h_slot[i] = (w + NW * i) % (4 * NRT);
     const int r = 8 * h_slot[i] + (lane >> 3);
-    h_voff[i] = ((uint32_t)min(row0 + r, a.N - 1) * (uint32_t)d + (((lane & 7) ^ ((r >> 1) & 7)) * 8)) * 2;
+    h_voff[i] = ((uint32_t)lm_row_id(a, row0 + r, n_rows) * (uint32_t)d + (((lane & 7) ^ ((r >> 1) & 7)) * 8)) * 2;
   }
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -520,7 +536,9 @@ __global__ __launch_bounds__(64 * NW, 1) void lm_head_bf16_kernel(LmArgs a) {
   }
   __builtin_amdgcn_s_waitcnt(WAIT_ALL);  // the redundant tail loads, before LDS is reused
   __syncthreads();
-  lm_epilogue<NRT, KT, NW>(a, acc, hbuf, tile, row0, v0, w, tid);
+  lm_epilogue<NRT, KT, NW>(a, acc, hbuf, tile, row0, n_rows, v0, w, tid);
+  __syncthreads();  // the buffers are free for another row chunk
+  }
 }
 
 // ------------------------------------------------------------------ merge of the parts' candidates
@@ -556,8 +574,9 @@ SS_DEV void row_topk(const uint64_t* __restrict__ ck, int n, int K, int lane, Em
 
 __global__ __launch_bounds__(64) void lm_head_reduce_kernel(LmArgs a) {
   const int lane = threadIdx.x;
-  const int row = blockIdx.x;
-  if (row >= a.N) return;
+  const int n_rows = lm_rows(a);
+  if ((int)blockIdx.x >= n_rows) return;
+  const int row = lm_row_id(a, blockIdx.x, n_rows);
   const int n = a.n_tiles * a.K;
   row_topk(a.cand_key + (size_t)row * n, n, a.K, lane, [&](int k, uint64_t best) {
     if (lane == 0) {
@@ -778,6 +797,20 @@ static void lm_flavour_override(bool linear, int N, int V, LmFlavour* f, LmArgs*
   a->n_tiles = ceil_div(V, wide ? 256 : 128);
 }
 
+// Which rows a call computes: all N (rows == NULL), or the rows listed on the device; plan_rows is the number of
+// rows the launch is shaped for (0 = N).
+struct RowSel {
+  const int32_t* rows;
+  const int32_t* n;
+  int plan_rows;
+};
+static int plan_n(const RowSel& sel, int N) { return (sel.rows && sel.plan_rows > 0 && sel.plan_rows < N) ? sel.plan_rows : N; }
+static int check_sel(const char* fn, const RowSel& sel) {
+  SS_REQUIRE((sel.rows == nullptr) == (sel.n == nullptr), SS_ERR_INVALID_ARG, "%s: live_rows and n_live must both be given", fn);
+  SS_REQUIRE(sel.plan_rows >= 0, SS_ERR_INVALID_ARG, "%s: plan_rows=%d", fn, sel.plan_rows);
+  return SS_OK;
+}
+
 // Candidate parts per row: one per vocabulary tile (64 ids in the fp32 kernel, 128 in the MFMA kernel).
 static int lm_tiles(int V, int dtype) { return ceil_div(V, dtype == SS_BF16 ? 128 : 64); }
 
@@ -817,7 +850,7 @@ size_t ss_lm_head_workspace_bytes(int N, int d, int V, int K, int dtype) {
 // The first kernel of a3: K candidates per (row, vocabulary tile) into the workspace.  Arguments are checked
 // by the callers; fills *a for the kernel that merges the candidates.
 static int lm_candidates(const char* fn, const void* hidden, const void* W, int N, int d, int V, int K, int dtype,
-                         void* workspace, hipStream_t st, ss::LmArgs* out) {
+                         const ss::RowSel& sel, void* workspace, hipStream_t st, ss::LmArgs* out) {
   using namespace ss;
   LmArgs a;
   a.hidden = hidden; a.W = W; a.N = N; a.d = d; a.V = V; a.K = K;
@@ -828,13 +861,14 @@ static int lm_candidates(const char* fn, const void* hidden, const void* W, int 
   a.cand_key = (uint64_t*)ws;
   a.idx = nullptr; a.val = nullptr;
   a.y = nullptr; a.lse = nullptr;
+  a.live_rows = sel.rows; a.n_live = sel.n;
   if (dtype == SS_F32) {
     dim3 grid(a.n_tiles, ceil_div(N, 32));
     SS_REQUIRE(grid.y <= 65535, SS_ERR_UNSUPPORTED, "%s: N too large", fn);
     hipLaunchKernelGGL(lm_head_f32_kernel<0>, grid, dim3(256), 0, st, a);
   } else {
-    LmFlavour f = lm_choose(N, V, &a);
-    lm_flavour_override(false, N, V, &f, &a);
+    LmFlavour f = lm_choose(plan_n(sel, N), V, &a);
+    lm_flavour_override(false, plan_n(sel, N), V, &f, &a);
     SS_REQUIRE((long)a.n_chunks * (a.n_tiles + 7) < (1L << 27), SS_ERR_UNSUPPORTED, "%s: N x V too large", fn);
     const int KT = K == 1 ? 1 : (K <= 4 ? 4 : 8);
     if (int rc = launch_lm_bf16(f, KT, st, a)) return rc;
@@ -843,12 +877,12 @@ static int lm_candidates(const char* fn, const void* hidden, const void* W, int 
   return check_launch(fn);
 }
 
-int ss_lm_head_argmax_topk(const void* hidden, const void* W, int N, int d, int V, int K, int dtype, int32_t* idx,
-                           float* val, void* workspace, size_t workspace_bytes, void* stream) {
+static int lm_topk_run(const char* fn, const void* hidden, const void* W, int N, int d, int V, int K, int dtype,
+                       int32_t* idx, float* val, const ss::RowSel& sel, void* workspace, size_t workspace_bytes,
+                       void* stream) {
   using namespace ss;
-  clear_error();
-  const char* fn = "ss_lm_head_argmax_topk";
   if (int rc = lm_check(fn, N, d, V, K, dtype)) return rc;
+  if (int rc = check_sel(fn, sel)) return rc;
   SS_REQUIRE(N == 0 || (hidden && W && idx && val), SS_ERR_INVALID_ARG, "%s: NULL tensor argument", fn);
   const size_t need = ss_lm_head_workspace_bytes(N, d, V, K, dtype);
   SS_REQUIRE(N == 0 || (workspace != nullptr && workspace_bytes >= need), SS_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given",
@@ -856,21 +890,36 @@ int ss_lm_head_argmax_topk(const void* hidden, const void* W, int N, int d, int 
   if (N == 0) return SS_OK;
   hipStream_t st = (hipStream_t)stream;
   LmArgs a;
-  if (int rc = lm_candidates(fn, hidden, W, N, d, V, K, dtype, workspace, st, &a)) return rc;
+  if (int rc = lm_candidates(fn, hidden, W, N, d, V, K, dtype, sel, workspace, st, &a)) return rc;
   a.idx = idx; a.val = val;
   hipLaunchKernelGGL(lm_head_reduce_kernel, dim3(N), dim3(64), 0, st, a);
   return check_launch(fn);
 }
 
-int ss_lm_head_verify_draft(const void* hidden, const void* W, int d, int V, int K, int dtype, const int32_t* tok,
-                            const int32_t* parent, int B, int T, int gamma, int max_depth, const int32_t* tmpl_parent,
-                            const int32_t* tmpl_rank, const int32_t* branching, int T2, int32_t* n_accept,
-                            int32_t* last, int32_t* bonus, int32_t* path, int32_t* out_tokens, int32_t* next_tok,
-                            int32_t* next_parent, int32_t* main_argmax, void* workspace, size_t workspace_bytes,
-                            void* stream) {
+int ss_lm_head_argmax_topk(const void* hidden, const void* W, int N, int d, int V, int K, int dtype, int32_t* idx,
+                           float* val, void* workspace, size_t workspace_bytes, void* stream) {
+  ss::clear_error();
+  return lm_topk_run("ss_lm_head_argmax_topk", hidden, W, N, d, V, K, dtype, idx, val, ss::RowSel{nullptr, nullptr, 0},
+                     workspace, workspace_bytes, stream);
+}
+
+int ss_lm_head_argmax_topk_live(const void* hidden, const void* W, int N, int d, int V, int K, int dtype, int32_t* idx,
+                                float* val, const int32_t* live_rows, const int32_t* n_live, int plan_rows,
+                                void* workspace, size_t workspace_bytes, void* stream) {
+  ss::clear_error();
+  SS_REQUIRE(N == 0 || (live_rows && n_live), SS_ERR_INVALID_ARG, "ss_lm_head_argmax_topk_live: NULL row list");
+  return lm_topk_run("ss_lm_head_argmax_topk_live", hidden, W, N, d, V, K, dtype, idx, val,
+                     ss::RowSel{live_rows, n_live, plan_rows}, workspace, workspace_bytes, stream);
+}
+
+static int lm_tail_run(const char* fn, const void* hidden, const void* W, int d, int V, int K, int dtype, const int32_t* tok,
+                       const int32_t* parent, int B, int T, int gamma, int max_depth, const int32_t* tmpl_parent,
+                       const int32_t* tmpl_rank, const int32_t* branching, int T2, int32_t* n_accept,
+                       int32_t* last, int32_t* bonus, int32_t* path, int32_t* out_tokens, int32_t* next_tok,
+                       int32_t* next_parent, int32_t* main_argmax, const ss::RowSel& sel, void* workspace,
+                       size_t workspace_bytes, void* stream) {
   using namespace ss;
-  clear_error();
-  const char* fn = "ss_lm_head_verify_draft";
+  if (int rc = check_sel(fn, sel)) return rc;
   SS_REQUIRE(B >= 0 && B <= (1 << 20), SS_ERR_INVALID_ARG, "%s: B=%d", fn, B);
   SS_REQUIRE(T >= 1 && T <= SS_MAX_T && T2 >= 1 && T2 <= SS_MAX_T, SS_ERR_UNSUPPORTED, "%s: T=%d or T2=%d outside [1,%d]",
              fn, T, T2, SS_MAX_T);
@@ -898,7 +947,7 @@ int ss_lm_head_verify_draft(const void* hidden, const void* W, int d, int V, int
   if (B == 0) return SS_OK;
   hipStream_t st = (hipStream_t)stream;
   LmArgs a;
-  if (int rc = lm_candidates(fn, hidden, W, N, d, V, K, dtype, workspace, st, &a)) return rc;
+  if (int rc = lm_candidates(fn, hidden, W, N, d, V, K, dtype, sel, workspace, st, &a)) return rc;
   t.cand_key = a.cand_key; t.n_parts = a.n_tiles; t.K = K;
   t.tok = tok; t.parent = parent;
   t.T = T; t.gamma = gamma; t.max_depth = max_depth; t.T2 = T2;
@@ -907,6 +956,32 @@ int ss_lm_head_verify_draft(const void* hidden, const void* W, int d, int V, int
   t.next_tok = next_tok; t.next_parent = next_parent; t.main_argmax = main_argmax;
   hipLaunchKernelGGL(lm_tail_kernel, dim3(B), dim3(1024), 0, st, t);
   return check_launch(fn);
+}
+
+int ss_lm_head_verify_draft(const void* hidden, const void* W, int d, int V, int K, int dtype, const int32_t* tok,
+                            const int32_t* parent, int B, int T, int gamma, int max_depth, const int32_t* tmpl_parent,
+                            const int32_t* tmpl_rank, const int32_t* branching, int T2, int32_t* n_accept,
+                            int32_t* last, int32_t* bonus, int32_t* path, int32_t* out_tokens, int32_t* next_tok,
+                            int32_t* next_parent, int32_t* main_argmax, void* workspace, size_t workspace_bytes,
+                            void* stream) {
+  ss::clear_error();
+  return lm_tail_run("ss_lm_head_verify_draft", hidden, W, d, V, K, dtype, tok, parent, B, T, gamma, max_depth, tmpl_parent,
+                     tmpl_rank, branching, T2, n_accept, last, bonus, path, out_tokens, next_tok, next_parent, main_argmax,
+                     ss::RowSel{nullptr, nullptr, 0}, workspace, workspace_bytes, stream);
+}
+
+int ss_lm_head_verify_draft_live(const void* hidden, const void* W, int d, int V, int K, int dtype, const int32_t* tok,
+                                 const int32_t* parent, int B, int T, int gamma, int max_depth,
+                                 const int32_t* tmpl_parent, const int32_t* tmpl_rank, const int32_t* branching, int T2,
+                                 int32_t* n_accept, int32_t* last, int32_t* bonus, int32_t* path, int32_t* out_tokens,
+                                 int32_t* next_tok, int32_t* next_parent, int32_t* main_argmax,
+                                 const int32_t* live_rows, const int32_t* n_live, int plan_rows, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
+  ss::clear_error();
+  SS_REQUIRE(B == 0 || (live_rows && n_live), SS_ERR_INVALID_ARG, "ss_lm_head_verify_draft_live: NULL row list");
+  return lm_tail_run("ss_lm_head_verify_draft_live", hidden, W, d, V, K, dtype, tok, parent, B, T, gamma, max_depth,
+                     tmpl_parent, tmpl_rank, branching, T2, n_accept, last, bonus, path, out_tokens, next_tok, next_parent,
+                     main_argmax, ss::RowSel{live_rows, n_live, plan_rows}, workspace, workspace_bytes, stream);
 }
 
 int ss_lm_head_logsumexp(const void* hidden, const void* W, int N, int d, int V, int dtype, float* lse,
@@ -928,6 +1003,7 @@ int ss_lm_head_logsumexp(const void* hidden, const void* W, int N, int d, int V,
   a.cand_key = (uint64_t*)(((uintptr_t)workspace + 255) & ~(uintptr_t)255);
   a.idx = nullptr; a.val = nullptr; a.y = nullptr;
   a.lse = lse;
+  a.live_rows = nullptr; a.n_live = nullptr;
   hipStream_t st = (hipStream_t)stream;
   if (dtype == SS_F32) {
     dim3 grid(a.n_tiles, ceil_div(N, 32));
@@ -944,10 +1020,10 @@ int ss_lm_head_logsumexp(const void* hidden, const void* W, int N, int d, int V,
   return check_launch(fn);
 }
 
-int ss_linear_rows(const void* x, const void* W, int N, int d, int V, int dtype, void* y, void* stream) {
+static int linear_run(const char* fn, const void* x, const void* W, int N, int d, int V, int dtype, void* y,
+                      const ss::RowSel& sel, void* stream) {
   using namespace ss;
-  clear_error();
-  const char* fn = "ss_linear_rows";
+  if (int rc = check_sel(fn, sel)) return rc;
   if (int rc = gemm_check(fn, N, d, V, dtype)) return rc;
   SS_REQUIRE(N == 0 || (x && W && y), SS_ERR_INVALID_ARG, "%s: NULL tensor argument", fn);
   SS_REQUIRE((long)(N < 1 ? 1 : N) * V < (1L << 31), SS_ERR_UNSUPPORTED, "%s: y (%d x %d) has 2^31 elements or more", fn, N, V);
@@ -958,6 +1034,7 @@ int ss_linear_rows(const void* x, const void* W, int N, int d, int V, int dtype,
   a.n_chunks = 1;
   a.k_stagger = 0;
   a.cand_key = nullptr; a.idx = nullptr; a.val = nullptr; a.lse = nullptr;
+  a.live_rows = sel.rows; a.n_live = sel.n;
   a.y = y;
   hipStream_t st = (hipStream_t)stream;
   if (dtype == SS_F32) {
@@ -965,12 +1042,25 @@ int ss_linear_rows(const void* x, const void* W, int N, int d, int V, int dtype,
     SS_REQUIRE(grid.y <= 65535, SS_ERR_UNSUPPORTED, "%s: N too large", fn);
     hipLaunchKernelGGL(lm_head_f32_kernel<1>, grid, dim3(256), 0, st, a);
   } else {
-    LmFlavour f = lm_choose(N, V, &a);
-    lm_flavour_override(true, N, V, &f, &a);
+    LmFlavour f = lm_choose(plan_n(sel, N), V, &a);
+    lm_flavour_override(true, plan_n(sel, N), V, &f, &a);
     SS_REQUIRE((long)a.n_chunks * (a.n_tiles + 7) < (1L << 27), SS_ERR_UNSUPPORTED, "%s: N x V too large", fn);
     if (int rc = launch_lm_bf16(f, 0, st, a)) return rc;
   }
   return check_launch(fn);
+}
+
+
+int ss_linear_rows(const void* x, const void* W, int N, int d, int V, int dtype, void* y, void* stream) {
+  ss::clear_error();
+  return linear_run("ss_linear_rows", x, W, N, d, V, dtype, y, ss::RowSel{nullptr, nullptr, 0}, stream);
+}
+
+int ss_linear_rows_live(const void* x, const void* W, int N, int d, int V, int dtype, void* y, const int32_t* live_rows,
+                        const int32_t* n_live, int plan_rows, void* stream) {
+  ss::clear_error();
+  SS_REQUIRE(N == 0 || (live_rows && n_live), SS_ERR_INVALID_ARG, "ss_linear_rows_live: NULL row list");
+  return linear_run("ss_linear_rows_live", x, W, N, d, V, dtype, y, ss::RowSel{live_rows, n_live, plan_rows}, stream);
 }
 
 }  // extern "C"

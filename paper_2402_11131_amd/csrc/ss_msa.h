@@ -15,6 +15,7 @@ struct MsaArgs {
   const int32_t* block_table;
   const int32_t* seq_lens;
   const int32_t* parent;
+  const int32_t* n_nodes;  // [B] kept nodes per sequence after pruning (rows of the others are not computed), or NULL
   void* out;
   float* part_o;    // [B,H,S,R,D]  per-split outputs, already divided by their own sum
   float* part_lse;  // [B,H,S,R]    log2-domain log-sum-exp of each split
@@ -39,6 +40,8 @@ SS_DEV int clamp_len(int L, const MsaArgs& a) { return min(max(L, 0), a.max_page
 SS_DEV int active_splits(int L, const MsaArgs& a) {
   return L <= a.split0_keys ? 1 : 1 + (L - a.split0_keys + a.split_keys - 1) / a.split_keys;
 }
+// Kept nodes of sequence b: all T unless the call passes n_nodes (clamped to [1,T]).
+SS_DEV int kept_nodes(int b, const MsaArgs& a) { return a.n_nodes ? min(max(a.n_nodes[b], 1), a.T) : a.T; }
 SS_DEV int split_begin(int s, const MsaArgs& a) { return s == 0 ? 0 : a.split0_keys + (s - 1) * a.split_keys; }
 SS_DEV int split_len(int s, const MsaArgs& a) { return s == 0 ? a.split0_keys : a.split_keys; }
 

@@ -41,6 +41,7 @@ __global__ __launch_bounds__(256) void msa_f32_kernel(MsaArgs a) {
   const int total = n_prefix + n_new;
   const int r0 = chunk * RC;
   const int R = a.R, T = a.T;
+  const int n_kept = kept_nodes(b, a);
 
   const float* q = (const float*)a.q;
   const float* k_new = (const float*)a.k_new;
@@ -152,6 +153,7 @@ __global__ __launch_bounds__(256) void msa_f32_kernel(MsaArgs a) {
   for (int i = 0; i < RW; ++i) {
     const int row = r0 + w * RW + i;
     if (row >= R) continue;
+    if ((row < T ? row : (row - T) / max(a.gamma, 1)) >= n_kept) continue;  // rows of removed nodes are not written
     const float inv = l[i] > 0.f ? 1.f / l[i] : 0.f;
     if (a.n_splits == 1) {
       float* out = (float*)a.out + (((size_t)b * R + row) * a.H + h) * D;
@@ -182,6 +184,7 @@ __global__ __launch_bounds__(256) void msa_combine_kernel(MsaArgs a) {
   const int h = item % a.H;
   const int r = (item / a.H) % a.R;
   const int b = item / ((long)a.H * a.R);
+  if ((r < a.T ? r : (r - a.T) / max(a.gamma, 1)) >= kept_nodes(b, a)) return;  // rows of removed nodes: no partials, not written
   const int n_active = active_splits(clamp_len(a.seq_lens[b], a), a);
   const size_t base = (((size_t)b * a.H + h) * a.n_splits) * a.R + r;
   float m = -INFINITY, wsum = 0.f;
@@ -382,8 +385,8 @@ static int static_scratch(const char* fn, void** ptr) {
 // here on every call.
 static int msa_run(const char* fn, const void* q, const void* k_new, const void* v_new, const void* k_cache,
                    const void* v_cache, const int32_t* block_table, int max_pages_per_seq, int num_pages,
-                   const int32_t* seq_lens, const int32_t* parent, int B, int T, int gamma, int H, int Hkv, int D,
-                   int page_size, float scale, int dtype, uint32_t flags, void* out, void* workspace,
+                   const int32_t* seq_lens, const int32_t* parent, const int32_t* n_nodes, int B, int T, int gamma, int H,
+                   int Hkv, int D, int page_size, float scale, int dtype, uint32_t flags, void* out, void* workspace,
                    size_t workspace_bytes, bool library_scratch, void* stream) {
   if (int rc = check_shape(fn, B, T, gamma, H, Hkv, D, dtype)) return rc;
   SS_REQUIRE(B == 0 || (q && k_new && v_new && k_cache && v_cache && block_table && seq_lens && parent && out),
@@ -415,7 +418,7 @@ static int msa_run(const char* fn, const void* q, const void* k_new, const void*
 
   MsaArgs a;
   a.q = q; a.k_new = k_new; a.v_new = v_new; a.k_cache = k_cache; a.v_cache = v_cache;
-  a.block_table = block_table; a.seq_lens = seq_lens; a.parent = parent; a.out = out;
+  a.block_table = block_table; a.seq_lens = seq_lens; a.parent = parent; a.n_nodes = n_nodes; a.out = out;
   char* ws = (char*)(((uintptr_t)workspace + 255) & ~(uintptr_t)255);
   a.part_o = (float*)ws;
   a.part_lse = (float*)(ws + plan.part_o_bytes);
@@ -496,8 +499,20 @@ int ss_msa_attention(const void* q, const void* k_new, const void* v_new, const 
                      int dtype, uint32_t flags, void* out, void* workspace, size_t workspace_bytes, void* stream) {
   ss::clear_error();
   return ss::msa_run("ss_msa_attention", q, k_new, v_new, k_cache, v_cache, block_table, max_pages_per_seq, num_pages,
-                     seq_lens, parent, B, T, gamma, H, Hkv, D, page_size, scale, dtype, flags, out, workspace,
+                     seq_lens, parent, nullptr, B, T, gamma, H, Hkv, D, page_size, scale, dtype, flags, out, workspace,
                      workspace_bytes, false, stream);
+}
+
+int ss_msa_attention_pruned(const void* q, const void* k_new, const void* v_new, const void* k_cache,
+                            const void* v_cache, const int32_t* block_table, int max_pages_per_seq, int num_pages,
+                            const int32_t* seq_lens, const int32_t* parent, const int32_t* n_nodes, int B, int T,
+                            int gamma, int H, int Hkv, int D, int page_size, float scale, int dtype, uint32_t flags,
+                            void* out, void* workspace, size_t workspace_bytes, void* stream) {
+  ss::clear_error();
+  SS_REQUIRE(B == 0 || n_nodes != nullptr, SS_ERR_INVALID_ARG, "ss_msa_attention_pruned: NULL n_nodes");
+  return ss::msa_run("ss_msa_attention_pruned", q, k_new, v_new, k_cache, v_cache, block_table, max_pages_per_seq,
+                     num_pages, seq_lens, parent, n_nodes, B, T, gamma, H, Hkv, D, page_size, scale, dtype, flags, out,
+                     workspace, workspace_bytes, false, stream);
 }
 
 size_t ss_msa_static_scratch_bytes(void) { return ss::kStaticScratchBytes; }
@@ -511,8 +526,8 @@ int ss_msa_attention_static(const void* q, const void* k_new, const void* v_new,
   const char* fn = "ss_msa_attention_static";
   void* scratch = nullptr;
   if (int rc = static_scratch(fn, &scratch)) return rc;
-  return msa_run(fn, q, k_new, v_new, k_cache, v_cache, block_table, max_pages_per_seq, num_pages, seq_lens, parent, B,
-                 T, gamma, H, Hkv, D, page_size, scale, dtype, flags, out, scratch, kStaticScratchBytes, true, stream);
+  return msa_run(fn, q, k_new, v_new, k_cache, v_cache, block_table, max_pages_per_seq, num_pages, seq_lens, parent,
+                 nullptr, B, T, gamma, H, Hkv, D, page_size, scale, dtype, flags, out, scratch, kStaticScratchBytes, true, stream);
 }
 
 }  // extern "C"

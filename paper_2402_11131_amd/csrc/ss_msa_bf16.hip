@@ -233,12 +233,19 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
   };
   refill_pages(0);
   const int L_raw = a.seq_lens[b];
+  const int n_kept = kept_nodes(b, a);
   int par_v = tid < T ? clamp_parent(a.parent[(size_t)b * T + tid], tid) : 0;
 
   // this wave's query tile: MFMA B operands (lane (lq, lg) holds features 8*(4*ks+lg).. of folded query row f)
+  // Rows of nodes that pruning removed are neither computed nor written: the folded row index runs over the
+  // kept rows only (per query head the n_kept main rows, then the n_kept*gamma stream rows of those nodes), so
+  // the kept rows fill the first row chunks and the workgroups of the others leave at once.
+  const int R_kept = n_kept * (1 + a.gamma);
+  if (qc * (16 * NW) >= a.g * R_kept) return;
   const int f = qc * (16 * NW) + 16 * wt + lq;
-  const bool f_valid = f < F;
-  const int q_r = f_valid ? f % R : 0, q_h = hk * a.g + (f_valid ? f / R : 0);
+  const bool f_valid = f < a.g * R_kept;
+  const int f_row = f_valid ? f % R_kept : 0;
+  const int q_r = f_row < n_kept ? f_row : T + (f_row - n_kept), q_h = hk * a.g + (f_valid ? f / R_kept : 0);
   bf16x8 Qr[KS];
   {
     const uint16_t* qp = q + (((size_t)b * R + q_r) * a.H + q_h) * D + lg * 8;

@@ -116,6 +116,28 @@ __global__ __launch_bounds__(64) void tree_prune_kernel(PruneArgs a) {
   if (i == 0) a.n_nodes[b] = n;
 }
 
+// The rows of the kept nodes, ascending, for the calls that skip the rows of padding nodes: sequence b
+// contributes its main rows b*R + i and its stream rows b*R + T + i*gamma + (j-1) of the nodes i < n_nodes[b].
+// One workgroup: thread 0 lays the sequences' offsets down in batch order, then all threads write the rows.
+struct LiveArgs {
+  const int32_t* n_nodes;
+  int32_t* live_rows;
+  int32_t* n_live;
+  int B, T, gamma;
+};
+__global__ __launch_bounds__(256) void live_rows_kernel(LiveArgs a) {
+  const int R = a.T * (1 + a.gamma);
+  int off = 0;
+  for (int b = 0; b < a.B; ++b) {
+    const int n = min(max(a.n_nodes[b], 1), a.T);
+    const int per = n * (1 + a.gamma);
+    for (int r = threadIdx.x; r < per; r += 256)
+      a.live_rows[off + r] = b * R + (r < n ? r : a.T + (r - n));  // stream rows of kept nodes are T .. T + n*gamma - 1
+    off += per;
+  }
+  if (threadIdx.x == 0) *a.n_live = off;
+}
+
 }  // namespace ss
 
 extern "C" {
@@ -157,6 +179,21 @@ int ss_tree_prune(const int32_t* tok, const int32_t* parent, const float* prob, 
   a.keep = keep; a.new_tok = new_tok; a.new_parent = new_parent; a.old_index = old_index; a.n_nodes = n_nodes;
   a.B = B; a.T = T;
   hipLaunchKernelGGL(tree_prune_kernel, dim3((unsigned)B), dim3(64), 0, (hipStream_t)stream, a);
+  return check_launch(fn);
+}
+
+int ss_live_rows(const int32_t* n_nodes, int B, int T, int gamma, int32_t* live_rows, int32_t* n_live, void* stream) {
+  using namespace ss;
+  clear_error();
+  const char* fn = "ss_live_rows";
+  SS_REQUIRE(B >= 0, SS_ERR_INVALID_ARG, "%s: B=%d", fn, B);
+  SS_REQUIRE(T >= 1 && T <= SS_MAX_T, SS_ERR_UNSUPPORTED, "%s: T=%d outside [1,%d]", fn, T, SS_MAX_T);
+  SS_REQUIRE(gamma >= 0 && gamma <= SS_MAX_GAMMA, SS_ERR_UNSUPPORTED, "%s: gamma=%d outside [0,%d]", fn, gamma, SS_MAX_GAMMA);
+  SS_REQUIRE((long)B * T * (1 + gamma) <= 0x7fffffffL, SS_ERR_UNSUPPORTED, "%s: too many rows", fn);
+  SS_REQUIRE(n_live != nullptr && (B == 0 || (n_nodes && live_rows)), SS_ERR_INVALID_ARG, "%s: NULL argument", fn);
+  LiveArgs a;
+  a.n_nodes = n_nodes; a.live_rows = live_rows; a.n_live = n_live; a.B = B; a.T = T; a.gamma = gamma;
+  hipLaunchKernelGGL(live_rows_kernel, dim3(1), dim3(256), 0, (hipStream_t)stream, a);
   return check_launch(fn);
 }
 
