@@ -102,16 +102,30 @@ __global__ __launch_bounds__(256) void expand_rows_kernel(ExpandArgs a) {
   const size_t zm = (size_t)b * a.T + node;
   const size_t zf = a.has_f ? a.BT + zm : zm, zp = (size_t)a.BT * (a.has_f ? 2 : 1) + (strm > 0 ? strm - 1 : 0);
   const size_t yo = ((size_t)b * R + r) * a.V;
-  for (int v = threadIdx.x; v < a.V; v += 256) {
-    if constexpr (BF16) {
-      const uint16_t* Z = (const uint16_t*)a.Z;
-      uint16_t* Y = (uint16_t*)a.Y;
-      Y[yo + v] = strm == 0 ? Z[zm * a.V + v]
-                            : (uint16_t)f32_to_bf16_bits(bf16_bits_to_f32(Z[zf * a.V + v]) + bf16_bits_to_f32(Z[zp * a.V + v]));
+  if constexpr (BF16) {
+    const uint16_t* Z = (const uint16_t*)a.Z;
+    uint16_t* Y = (uint16_t*)a.Y;
+    if ((a.V & 7) == 0 && ((((uintptr_t)a.Z | (uintptr_t)a.Y)) & 15) == 0) {  // 16-byte pieces
+      for (int c = threadIdx.x; c < a.V / 8; c += 256) {
+        uintx4 m = *reinterpret_cast<const uintx4*>(Z + (strm == 0 ? zm : zf) * a.V + 8 * c);
+        if (strm > 0) {
+          const uintx4 p = *reinterpret_cast<const uintx4*>(Z + zp * a.V + 8 * c);
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+            m[q] = pack_bf16x2(bf16_bits_to_f32(m[q] & 0xffffu) + bf16_bits_to_f32(p[q] & 0xffffu),
+                               bf16_bits_to_f32(m[q] >> 16) + bf16_bits_to_f32(p[q] >> 16));
+        }
+        *reinterpret_cast<uintx4*>(Y + yo + 8 * c) = m;
+      }
     } else {
-      const float* Z = (const float*)a.Z;
-      ((float*)a.Y)[yo + v] = strm == 0 ? Z[zm * a.V + v] : Z[zf * a.V + v] + Z[zp * a.V + v];
+      for (int v = threadIdx.x; v < a.V; v += 256)
+        Y[yo + v] = strm == 0 ? Z[zm * a.V + v]
+                              : (uint16_t)f32_to_bf16_bits(bf16_bits_to_f32(Z[zf * a.V + v]) + bf16_bits_to_f32(Z[zp * a.V + v]));
     }
+  } else {
+    const float* Z = (const float*)a.Z;
+    for (int v = threadIdx.x; v < a.V; v += 256)
+      ((float*)a.Y)[yo + v] = strm == 0 ? Z[zm * a.V + v] : Z[zf * a.V + v] + Z[zp * a.V + v];
   }
 }
 
