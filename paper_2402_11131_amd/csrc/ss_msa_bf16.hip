@@ -87,6 +87,23 @@ SS_DEV void st_counter_device(unsigned int* p, unsigned int v) {
   __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// Maximum as one instruction: the median of (a, b, +inf).  fmaxf() on matrix-core results costs an extra
+// instruction per operand (the compiler first quiets signalling NaNs), a fifth of all vector work in the softmax
+// of a 32-key block.  `pinf` is +inf in a register the compiler cannot see through (it would turn the median back
+// into that maximum).  A compiler builtin, not inline assembly: the wait states between a matrix instruction or a
+// row swap and the first reader of its result are inserted by the compiler only for instructions it knows.
+SS_DEV float vmax2(float a, float b, float pinf) { return __builtin_amdgcn_fmed3f(a, b, pinf); }
+// Maximum over the four lanes l, l^16, l^32, l^48 (the lanes that share a query row), left in all four, by
+// the row-swap instructions: rows of 16 lanes [r0 r1 r2 r3] and a copy become [r0 r0 r2 r2] and [r1 r1 r3 r3],
+// then halves of 32 lanes likewise.  No trip through LDS, unlike a general lane shuffle.
+SS_DEV float max_over_lane_groups(float x, float pinf) {
+  const unsigned int u = __float_as_uint(x);
+  const auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  const unsigned int v = __float_as_uint(vmax2(__uint_as_float(a[0]), __uint_as_float(a[1]), pinf));
+  const auto b = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+  return vmax2(__uint_as_float(b[0]), __uint_as_float(b[1]), pinf);
+}
+
 constexpr float kLazyLog2 = 16.0f;
 constexpr int kMaxGroups = 4;  // wave groups per workgroup
 constexpr int kMaxWaves = 16;  // waves per workgroup: 4 per SIMD leaves each wave 128 vector registers
@@ -182,9 +199,11 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
   constexpr int VHALF = D * 32;                // bytes of one 16-key half of the V tile: D feature rows of 32 bytes
 
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  // smem: [n_groups][n_stages][STAGE_BYTES] ring stages (reused by the final merge) | par | anc | ml
+  // smem: [n_groups][n_stages][STAGE_BYTES] ring stages, overlaid by the buffer of the final merge of the groups
+  // ([n_groups - 1][NW][DT] KB); behind the larger of the two: par | anc | ml
   unsigned char* stages = smem;
-  int* par = reinterpret_cast<int*>(smem + (size_t)n_groups * n_stages * STAGE_BYTES);
+  const int ring_bytes = n_groups * n_stages * STAGE_BYTES, merge_bytes = (n_groups - 1) * NW * DT * 1024;
+  int* par = reinterpret_cast<int*>(smem + max(ring_bytes, merge_bytes));
   uint64_t* anc = reinterpret_cast<uint64_t*>(par + SS_MAX_T);
   float* ml = reinterpret_cast<float*>(anc + SS_MAX_T);  // [n_groups][NW][2][16]: max, sum per query
 
@@ -260,7 +279,15 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
   floatx4 O[DT];
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt) O[dt] = floatx4{0.f, 0.f, 0.f, 0.f};
-  float m_run = -1e30f, l_run = 0.f;
+  // Running maximum, and the running sum of the probabilities as the matrix cores add it up: one more
+  // instruction per block, a row of ones times P^T, instead of eight vector additions per lane; all four
+  // entries of a lane hold the sum of its query row over all keys of the block (the bf16 probabilities that
+  // also enter P V, so numerator and denominator round alike).
+  float m_run = -1e30f;
+  floatx4 Lacc = floatx4{0.f, 0.f, 0.f, 0.f};
+  bf16x8 ones;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) ones[i] = (__bf16)1.0f;
 
   // ---- how a block reaches LDS.  A unit is moved in 1 KB slots, one direct-to-LDS load each: K slot sl
   // holds rows ROWS_PER_SLOT*sl + lane/CPR, the lane at chunk position p = lane%CPR fetching chunk
@@ -401,6 +428,8 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
   compute_anc(par, T, anc, tid);
   __syncthreads();
 
+  float pinf = INFINITY;  // see vmax2
+  asm volatile("" : "+s"(pinf));
   const RowVis no_vis = RowVis{0, 0, 0};
   // One unit out of an LDS stage: scores, softmax update, O += P V.  `full` (a compile-time flag) is
   // the unmasked main-loop flavour; otherwise the unit is the ragged block of the prefix, or (is_new)
@@ -438,30 +467,26 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
         }
     }
     // ---- online softmax (log2 domain, lazy rescale), probabilities to bf16
-    float mx = fmaxf(fmaxf(fmaxf(S[0][0], S[0][1]), fmaxf(S[0][2], S[0][3])),
-                     fmaxf(fmaxf(S[1][0], S[1][1]), fmaxf(S[1][2], S[1][3])));
-    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    float mx = vmax2(vmax2(vmax2(S[0][0], S[0][1], pinf), vmax2(S[0][2], S[0][3], pinf), pinf),
+                     vmax2(vmax2(S[1][0], S[1][1], pinf), vmax2(S[1][2], S[1][3], pinf), pinf), pinf);
+    mx = max_over_lane_groups(mx, pinf);
     if (__any((mx - m_run) * c > kLazyLog2)) {
       const float m_new = fmaxf(m_run, mx);
       const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
-      l_run *= alpha;
+      Lacc *= alpha;
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt) O[dt] *= alpha;
       m_run = m_new;
     }
     const float mc = m_run * c;
     bf16x8 P;
-    float ps = 0.f;
 #pragma unroll
     for (int X = 0; X < 2; ++X)
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const float pr = __builtin_amdgcn_exp2f(fmaf(S[X][i], c, -mc));
-        ps += pr;
-        P[4 * X + i] = (__bf16)pr;
+        P[4 * X + i] = (__bf16)__builtin_amdgcn_exp2f(fmaf(S[X][i], c, -mc));
       }
-    l_run += ps;
+    Lacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, P, Lacc, 0, 0, 0);
     // ---- O^T += V^T P^T
     if (FULL) {
 #pragma unroll
@@ -561,8 +586,7 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
     ctr = a.arrive + (((size_t)b * a.Hkv + hk) * a.n_qc + qc) * kArriveTiles + wt;
     early = ld_counter_device(ctr);
   }
-  l_run += __shfl_xor(l_run, 16, 64);
-  l_run += __shfl_xor(l_run, 32, 64);
+  float l_run = Lacc[0];  // already summed over the four lane groups
   floatx4* obuf = reinterpret_cast<floatx4*>(stages);  // [(grp-1)*NW + wt][DT][64]
   float* my_ml = ml + (grp * NW + wt) * 32;
   __syncthreads();  // every group is done with its stages (the merge buffer overlays them)
@@ -720,6 +744,7 @@ static int launch_dns(const MsaArgs& a, hipStream_t stream) {
   size_t lds = (size_t)n_groups * n_stages * stage_bytes;
   if (merge_bytes > lds) lds = merge_bytes;
   lds += SS_MAX_T * 4 + SS_MAX_T * 8 + (size_t)n_groups * NW * 32 * 4;
+  SS_REQUIRE(lds <= 160 * 1024, SS_ERR_UNSUPPORTED, "ss_msa_attention: %zu bytes of LDS needed", lds);
   auto kern = msa_bf16_kernel<D, NW, STREAM>;
   static std::once_flag attr_once;
   static hipError_t attr_err = hipSuccess;
