@@ -8,17 +8,17 @@
 // slice of O live in registers) and all NW waves walk the same sequence of
 // 32-key units; the G groups take the units of the split round-robin and their
 // partial (max, sum, O) states are merged through LDS at the end.  With 80 rows
-// that is 3 groups x 5 waves = 15 waves per compute unit, which is what hides the
-// LDS, MFMA and exp latencies (no wave depends on long instruction-level overlap).
+// that is up to 3 groups x 5 waves = 15 waves per compute unit, which is what hides
+// the LDS, MFMA and exp latencies (no wave depends on long instruction-level overlap).
 //
-// Memory pipeline.  The unit a group works on sits in one of its two LDS stages
-// (8 KB of K rows + 8 KB of V for D = 128).  While it is being consumed, the
-// group's waves hold the next unit in registers (16-byte global loads issued at
-// the top of the iteration, one unit = 16 KB in flight per group); it is written
-// to the other stage after the compute and one workgroup barrier per unit
-// publishes it.  Global addresses are chosen so that one K load instruction
-// covers whole 256-byte key rows (4 consecutive keys = 1 KB contiguous) and one V
-// instruction covers two 512-byte runs of a feature-major page.
+// Memory pipeline.  Every group has a ring of n_stages LDS stages (8 KB of K rows + 8 KB of V for D = 128).
+// Blocks reach it by direct global -> LDS loads (16 bytes per lane, no staging register, counted in the issuing
+// wave's vector-memory counter and completed in issue order); up to four waves of a group issue them, one 1 KB
+// slot per instruction, n_stages - 1 blocks ahead.  An iteration waits (hand-written s_waitcnt) for its own
+// block, one workgroup barrier publishes it and frees the stage consumed one iteration earlier, which the next
+// block is then sent to.  Global addresses are chosen so that one K instruction covers whole 256-byte key rows
+// (4 consecutive keys = 1 KB contiguous) and one V instruction one contiguous KB of a feature-major page; the
+// XOR swizzles of the LDS tiles are applied on the source side, by the lane -> address mapping.
 //
 // Matrix-core mapping (v_mfma_f32_16x16x32_bf16, wave64).  Scores are computed
 // transposed, S^T = K Q^T (A = 16 keys x 32 features, B = 32 features x 16
@@ -44,6 +44,7 @@
 // generated in registers from ancestor bit sets and stream ranges; V rows are
 // token-major there: they are staged row-major and read with the LDS transpose
 // read ds_read_b64_tr_b16, which hands a lane 4 consecutive keys of one feature).
+// The ragged block alone goes through registers (per-lane page lookups, clamped).
 //
 // Order of work.  The step's own rows belong to split 0, which every sequence has,
 // and are scanned FIRST: their addresses do not depend on the page table, so they
