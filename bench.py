@@ -442,6 +442,14 @@ def main():
         w_copies = [lm["W"], lm["W"].clone()]
         us_lm = kernel_timed(lambda i: api.ss_lm_head_argmax_topk(hidden, w_copies[i & 1], cfg.K, idx=idx, val=val,
                                                                   workspace=lm_ws), torch)
+        # the matrix kernel alone (the call stops before the kernel that merges the tiles' candidates)
+        api.ss_lm_set_candidates_only(True)
+        try:
+            us_lm_kernel = kernel_timed(lambda i: api.ss_lm_head_argmax_topk(hidden, w_copies[i & 1], cfg.K, idx=idx, val=val,
+                                                                             workspace=lm_ws), torch)
+        finally:
+            api.ss_lm_set_candidates_only(False)
+        api.ss_lm_head_argmax_topk(hidden, w_copies[0], cfg.K, idx=idx, val=val, workspace=lm_ws)  # idx / val valid again
         tail_out = state.get("tail") or api.ss_lm_head_verify_draft(hidden, lm["W"], cfg.K, tok, parent, cfg.gamma, cfg.max_depth,
                                                                     branching=cfg.draft_branching, workspace=lm_ws)
         us_tail = kernel_timed(lambda i: api.ss_lm_head_verify_draft(hidden, w_copies[i & 1], cfg.K, tok, parent, cfg.gamma,
@@ -464,7 +472,8 @@ def main():
         us_commit = kernel_timed(lambda i: [api.ss_kv_commit(l["k_new"], l["v_new"], l["k_cache"], l["v_cache"], l["block_table"], short,
                                                               ver["path"], ver["n_accept"], cfg.gamma, new_seq_lens=new_lens)
                                             for l in work.layers[:cfg.n_layers]], torch)
-        kern.update({"lm_head_call_us": round(us_lm, 2), "lm_head_verify_draft_call_us": round(us_tail, 2),
+        kern.update({"lm_head_call_us": round(us_lm, 2), "lm_head_kernel_us": round(us_lm_kernel, 2),
+                     "lm_head_verify_draft_call_us": round(us_tail, 2),
                      "verify_us": round(us_ver, 2), "draft_us": round(us_draft, 2),
                      "kv_commit_all_layers_us": round(us_commit, 2)})
         f_lm = 2.0 * N * cfg.vocab * cfg.d_model
@@ -476,6 +485,9 @@ def main():
         extra["roofline_lm_head"] = {"kernel": "lm_head_bf16_kernel + lm_head_reduce_kernel", "bound": "mfma", "achieved": round(tf, 1),
                                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                                      "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                                     # lm_head_bf16_kernel alone, as a kernel trace shows it
+                                     "matrix_kernel_alone": {"us": round(us_lm_kernel, 2),
+                                                             "frac": round(f_lm / (us_lm_kernel * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)},
                                      "hbm_gbps": round((cfg.vocab * cfg.d_model * 2 + N * cfg.d_model * 2) /
                                                        (us_lm * 1e-6) / 1e9, 1),
                                      # register-only matrix-core work on the whole chip, at the clock it is granted

@@ -276,9 +276,14 @@ int ss_lm_head_argmax_topk(const void* hidden, const void* W, int N, int d, int 
  * Both return the previous setting.  Initial values can be given by the
  * environment variables SS_LM_FLAVOUR / SS_LINEAR_FLAVOUR ("3" or "3w") and
  * SS_LM_STAGGER, which are read once per process.
+ * ss_lm_set_candidates_only: a profiling aid like SS_MSA_PARTIALS_ONLY.  While
+ *  it is on, ss_lm_head_argmax_topk (and its _live form) stops after the matrix
+ *  kernel that leaves K candidates per row and vocabulary tile in the workspace:
+ *  idx and val are NOT written.  Returns the previous setting; off by default.
  */
 int ss_lm_set_flavour(int linear, int row_tiles, int wide);
 int ss_lm_set_stagger(int blocks);
+int ss_lm_set_candidates_only(int on);
 
 /*
  * n1. Dense projection of the step's rows (Sec. 3.1: queries, keys and values

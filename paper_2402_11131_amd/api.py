@@ -27,7 +27,7 @@ SS_MAX_T, SS_MAX_GAMMA, SS_MAX_K = 64, 8, 8
 
 EXPORTS = (
     "ss_version", "ss_last_error", "ss_probe_hbm_read", "ss_probe_mfma_bf16", "ss_check_tree_host", "ss_build_mask", "ss_msa_workspace_bytes",
-    "ss_msa_attention", "ss_msa_workspace_init", "ss_msa_attention_static", "ss_msa_static_scratch_bytes", "ss_msa_plan", "ss_msa_set_split_keys", "ss_msa_set_merge_in_kernel", "ss_lm_head_workspace_bytes", "ss_lm_set_flavour", "ss_lm_set_stagger", "ss_lm_head_argmax_topk", "ss_lm_head_verify_draft",
+    "ss_msa_attention", "ss_msa_workspace_init", "ss_msa_attention_static", "ss_msa_static_scratch_bytes", "ss_msa_plan", "ss_msa_set_split_keys", "ss_msa_set_merge_in_kernel", "ss_lm_head_workspace_bytes", "ss_lm_set_flavour", "ss_lm_set_stagger", "ss_lm_set_candidates_only", "ss_lm_head_argmax_topk", "ss_lm_head_verify_draft",
     "ss_tree_verify", "ss_tree_draft", "ss_full_tree_template_host", "ss_kv_commit", "ss_kv_alloc_pages", "ss_linear_rows", "ss_stream_insert", "ss_stream_insert_linear", "ss_stream_insert_linear_workspace_bytes", "ss_value_rotate",
     "ss_lm_head_logsumexp", "ss_transition_probs", "ss_tree_prune", "ss_live_rows", "ss_msa_attention_pruned",
     "ss_linear_rows_live", "ss_lm_head_argmax_topk_live", "ss_lm_head_verify_draft_live",
@@ -75,6 +75,7 @@ def load_library() -> ctypes.CDLL:
     lib.ss_lm_head_workspace_bytes.argtypes = [i32] * 5
     lib.ss_lm_set_flavour.argtypes = [i32, i32, i32]
     lib.ss_lm_set_stagger.argtypes = [i32]
+    lib.ss_lm_set_candidates_only.argtypes = [i32]
     lib.ss_lm_head_workspace_bytes.restype = sz
     lib.ss_lm_head_argmax_topk.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, sz, vp]
     lib.ss_tree_verify.argtypes = [vp, vp, vp, lng, lng, i32, i32, i32, vp, vp, vp, vp, vp, vp]
@@ -301,6 +302,11 @@ def ss_lm_set_flavour(linear: bool, flavour) -> int:
 def ss_lm_set_stagger(blocks: int) -> int:
     """Tuning knob: feature blocks between the starting blocks of neighbouring vocabulary tiles (-1 = automatic)."""
     return load_library().ss_lm_set_stagger(int(blocks))
+
+
+def ss_lm_set_candidates_only(on: bool) -> bool:
+    """Profiling aid: while on, ss_lm_head_argmax_topk stops after the matrix kernel (idx / val are not written)."""
+    return bool(load_library().ss_lm_set_candidates_only(1 if on else 0))
 
 
 def ss_lm_head_argmax_topk(hidden, W, K: int, idx=None, val=None, workspace=None, live=None, plan_rows: int = 0):

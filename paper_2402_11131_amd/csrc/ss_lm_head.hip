@@ -654,6 +654,7 @@ __global__ __launch_bounds__(1024) void lm_tail_kernel(TailArgs t) {
 struct LmTuning {
   std::atomic<int> flavour[2];  // [LM head, projection]: row tiles | wide << 8, 0 = automatic
   std::atomic<int> stagger;     // feature blocks between neighbouring tiles' starts, -1 = automatic
+  std::atomic<int> candidates_only;  // profiling aid: ss_lm_head_argmax_topk stops after the matrix kernel
 };
 static int flavour_code(long want, int wide) { return (want < 1 || want > (wide ? 5 : 6)) ? 0 : (int)want | (wide ? 256 : 0); }
 static int flavour_from_env(const char* var) {
@@ -672,6 +673,7 @@ static LmTuning& tuning() {
     const char* e = getenv("SS_LM_STAGGER");
     const int v = e ? atoi(e) : -1;
     t.stagger = v < 0 ? -1 : (v > 1024 ? 1024 : v);
+    t.candidates_only = 0;
   });
   return t;
 }
@@ -841,6 +843,8 @@ int ss_lm_set_stagger(int blocks) {
   return ss::tuning().stagger.exchange(blocks < 0 ? -1 : (blocks > 1024 ? 1024 : blocks));
 }
 
+int ss_lm_set_candidates_only(int on) { return ss::tuning().candidates_only.exchange(on ? 1 : 0); }
+
 size_t ss_lm_head_workspace_bytes(int N, int d, int V, int K, int dtype) {
   ss::clear_error();
   if (ss::lm_check("ss_lm_head_workspace_bytes", N, d, V, K, dtype) != SS_OK) return 0;
@@ -892,6 +896,7 @@ static int lm_topk_run(const char* fn, const void* hidden, const void* W, int N,
   LmArgs a;
   if (int rc = lm_candidates(fn, hidden, W, N, d, V, K, dtype, sel, workspace, st, &a)) return rc;
   a.idx = idx; a.val = val;
+  if (tuning().candidates_only.load()) return SS_OK;  // profiling aid: idx / val are not written
   hipLaunchKernelGGL(lm_head_reduce_kernel, dim3(N), dim3(64), 0, st, a);
   return check_launch(fn);
 }

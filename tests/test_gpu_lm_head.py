@@ -104,3 +104,22 @@ def test_planted_argmax_is_found():
     a = idx.cpu().numpy().reshape(cfg.B, cfg.R)[:, :cfg.T]
     r = oracle.tree_verify(tok, parent, a, cfg.max_depth)
     assert np.array_equal(r["n_accept"], planted) and planted.max() >= 1
+
+
+def test_candidates_only_is_a_profiling_aid_that_leaves_the_outputs_alone():
+    # while it is on the call stops after the matrix kernel: idx / val keep what they held; off again, same results as before
+    cfg = synth.scaled(synth.CONFIGS["c4"], vocab=1500, d_model=256)
+    inp = synth.make_lm_head_inputs(cfg, 5, N=96)
+    h, W = inp["hidden"].to(DEV), inp["W"].to(DEV)
+    want_idx, want_val = api.ss_lm_head_argmax_topk(h, W, 4)
+    idx = torch.full_like(want_idx, -7)
+    val = torch.full_like(want_val, -7.0)
+    assert api.ss_lm_set_candidates_only(True) is False
+    try:
+        api.ss_lm_head_argmax_topk(h, W, 4, idx=idx, val=val)
+        torch.cuda.synchronize()
+        assert (idx == -7).all() and (val == -7.0).all()
+    finally:
+        assert api.ss_lm_set_candidates_only(False) is True
+    api.ss_lm_head_argmax_topk(h, W, 4, idx=idx, val=val)
+    assert torch.equal(idx, want_idx) and torch.equal(val, want_val)
