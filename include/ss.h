@@ -160,8 +160,10 @@ int ss_build_mask(const int32_t* parent, int B, int T, int gamma, uint32_t flags
  *  seq_lens [B] int32: cached tokens per sequence, 0 <= seq_lens[b] <=
  *          max_pages_per_seq*page_size (larger values are clamped on device)
  *  parent [B,T] int32 as in a1.
- * dtype: SS_F32 (all of q,k,v,out fp32) or SS_BF16 (bf16 storage, fp32 softmax
- * and accumulation).  Limits: D in {64,128}, page_size in {16,32,64}, H % Hkv
+ * dtype: SS_F32 (all of q,k,v,out fp32) or SS_BF16 (bf16 storage, fp32 scores,
+ * softmax and accumulation; the probabilities are rounded to bf16 where they
+ * enter the product with V, and the softmax denominator is the fp32 sum of
+ * those rounded probabilities).  Limits: D in {64,128}, page_size in {16,32,64}, H % Hkv
  * == 0, T <= SS_MAX_T, gamma <= SS_MAX_GAMMA.  scale is the factor applied to
  * the dot products (1/sqrt(D) in the paper's MHA).
  * workspace: device scratch of at least ss_msa_workspace_bytes(...) bytes with
