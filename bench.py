@@ -208,6 +208,11 @@ def calibrate_copy(torch, dev):
     torch.cuda.synchronize()
 
 
+def weight_copies(nbytes, footprint=1 << 30):
+    """Copies of a weight matrix to use in turn so that no cache (256 MB last level) can hold them."""
+    return max(2, -(-footprint // nbytes))
+
+
 def time_rows_after_hot_path(api, synth, torch, cfg, dev, N, lm, lm_ws, tok, parent, extra):
     """Rows after the hot path (not part of `value`), each in a loop of its own; fills `extra`."""
     # Dense projections of one MSA layer on the step's N rows: fused QKV, attention output, fused gate+up and
@@ -217,12 +222,16 @@ def time_rows_after_hot_path(api, synth, torch, cfg, dev, N, lm, lm_ws, tok, par
     total = 0.0
     for name, (din, dout) in (("qkv", (dm, 3 * cfg.H * cfg.D)), ("attn_out", (cfg.H * cfg.D, dm)),
                               ("gate_up", (dm, 2 * dff)), ("down", (dff, dm))):
-        xs = [synth.make_lm_head_inputs(synth.scaled(cfg, vocab=dout, d_model=din), 50 + j, device=dev, N=N)
-              for j in range(2)]
+        # Weights come from HBM in a model (a layer's 400 MB, 13 GB for all layers): as many copies in turn as
+        # make up 1 GB, four times the last-level cache.  With two copies of a 90 MB matrix the cache serves
+        # them and the map reads 40 % faster than it ever would in a layer sequence.
+        copies = weight_copies(din * dout * 2)
+        x0 = synth.make_lm_head_inputs(synth.scaled(cfg, vocab=dout, d_model=din), 50, device=dev, N=N)
+        xs = [x0] + [{"hidden": x0["hidden"], "W": x0["W"].clone()} for _ in range(copies - 1)]
         y = torch.empty(N, dout, dtype=xs[0]["hidden"].dtype, device=dev)
-        us = kernel_timed(lambda i: api.ss_linear_rows(xs[i % 2]["hidden"], xs[i % 2]["W"], y), torch)
+        us = kernel_timed(lambda i: api.ss_linear_rows(xs[i % copies]["hidden"], xs[i % copies]["W"], y), torch)
         total += us
-        dense[name] = {"d_in": din, "d_out": dout, "us": round(us, 2),
+        dense[name] = {"d_in": din, "d_out": dout, "us": round(us, 2), "weight_copies_in_turn": copies,
                        "tflops": round(2.0 * N * din * dout / (us * 1e-6) / 1e12, 1),
                        "hbm_gbps": round((din * dout + N * din + N * dout) * 2 / (us * 1e-6) / 1e9, 1)}
         del xs, y
@@ -249,17 +258,19 @@ def time_rows_after_hot_path(api, synth, torch, cfg, dev, N, lm, lm_ws, tok, par
     # ... and Eq. 3 through the QKV projection of the first multi-stream layer: rows written out and projected, against
     # the one call that projects the B*T states and the gamma embeddings only and adds the results
     dq = 3 * cfg.H * cfg.D
-    wq = [synth.make_lm_head_inputs(synth.scaled(cfg, vocab=dq, d_model=dm), 62 + j, device=dev, N=8)["W"] for j in range(2)]
+    wq = [synth.make_lm_head_inputs(synth.scaled(cfg, vocab=dq, d_model=dm), 62, device=dev, N=8)["W"]]
+    n_wq = weight_copies(dq * dm * 2)
+    wq += [wq[0].clone() for _ in range(n_wq - 1)]
     Yq = torch.empty(cfg.B, cfg.R, dq, dtype=hm.dtype, device=dev)
     sil_ws = torch.empty(api.load_library().ss_stream_insert_linear_workspace_bytes(cfg.B, cfg.T, cfg.gamma, dm, dq, api.SS_BF16, 0),
                          dtype=torch.uint8, device=dev)
 
     def unfused(i):
         api.ss_stream_insert(hm, P_emb, X=X_rows)
-        api.ss_linear_rows(X_rows.view(cfg.B * cfg.R, dm), wq[i & 1], Yq.view(cfg.B * cfg.R, dq))
+        api.ss_linear_rows(X_rows.view(cfg.B * cfg.R, dm), wq[i % n_wq], Yq.view(cfg.B * cfg.R, dq))
     extra["stream_insert_qkv"] = {
         "insert_then_project_us": round(kernel_timed(unfused, torch), 2),
-        "one_call_us": round(kernel_timed(lambda i: api.ss_stream_insert_linear(hm, P_emb, wq[i & 1], Y=Yq, workspace=sil_ws), torch), 2)}
+        "one_call_us": round(kernel_timed(lambda i: api.ss_stream_insert_linear(hm, P_emb, wq[i % n_wq], Y=Yq, workspace=sil_ws), torch), 2)}
     del wq, Yq
     # The appendix's value-rotation variant on one layer's value block [B,R,Hkv,D], in place
     v_blk = X_rows.view(cfg.B, cfg.R, cfg.Hkv, dm // cfg.Hkv) if dm % cfg.Hkv == 0 and (dm // cfg.Hkv) % 2 == 0 else None

@@ -758,34 +758,36 @@ static int launch_lm_bf16(LmFlavour f, int KT, hipStream_t st, const LmArgs& arg
   }
 }
 
-// Which MFMA kernel, how many rows per workgroup and how many row chunks.  A compute unit holds one
-// workgroup (LDS), so the aim is one round of at most 256 workgroups with as many rows each as that
-// allows: rows are cut into more chunks while the workgroups still fit the chip (the chunks of a
-// vocabulary tile share its part of W in L2).  Up to 192 rows, or few outputs (V <= 8192): 4 waves,
-// tiles of 128 ids.  Otherwise 8 waves, tiles of 256 ids, at most 160 rows: measured faster than both
-// the 4-wave tile with 160 rows and a 320-row tile fed from registers (LM head of 320 x 4096 x 32000:
-// 92 against 112 us; projection to 22016 outputs: 66 against 76 us).
+// Which MFMA kernel, how many rows per workgroup and how many row chunks.  A compute unit holds one workgroup
+// (LDS) and sustains a fixed number of outstanding reads, so a launch takes about (rounds of 256 workgroups) x
+// (bytes a workgroup loads) x (latency): the shape with the smallest rounds x (ids + rows) per tile wins; among
+// equals the one with more workgroups.  Measured with weights that no cache holds, 320 rows: 32000 outputs ->
+// 8 waves, 256 ids x 160 rows, 250 workgroups (4 waves x 128 ids would need two rounds); 22016 -> the same
+// shape, 172 workgroups; 12288 -> 4 waves, 128 ids x 160 rows, 192 workgroups (50 us; 256 ids x 64 rows in 240
+// workgroups: 59 us); 4096 -> 4 waves, 128 ids x 64 rows.  Only balanced chunkings are considered (every
+// chunk as many 32-row tiles as the largest needs).
 static LmFlavour lm_choose(int N, int V, LmArgs* a) {
-  const int n32 = ceil_div(N, 32);
-  const int tiles128 = ceil_div(V, 128), tiles256 = ceil_div(V, 256);
-  LmFlavour f;
-  int c, cap;
-  if (n32 <= 6 || tiles128 <= 64) {
-    f.wide = 0;
-    cap = 6;
-    c = 256 / tiles128;
-    a->n_tiles = tiles128;
-  } else {
-    f.wide = 1;
-    cap = 5;
-    c = 256 / tiles256;
-    a->n_tiles = tiles256;
+  const int n32 = ceil_div(N < 1 ? 1 : N, 32);
+  LmFlavour best{1, 0};
+  long best_cost = -1, best_wgs = 0;
+  for (int wide = 0; wide <= 1; ++wide) {
+    const int ids = wide ? 256 : 128, cap = wide ? 5 : 6;
+    const long tiles = ceil_div(V, ids);
+    for (int nrt = 1; nrt <= cap; ++nrt) {
+      const int chunks = ceil_div(n32, nrt);
+      if (ceil_div(n32, chunks) != nrt) continue;  // the same chunking with fewer tiles per chunk comes by itself
+      const long wgs = tiles * chunks, rounds = (wgs + 255) / 256;
+      const long cost = rounds * (ids + 32 * nrt);
+      if (best_cost < 0 || cost < best_cost || (cost == best_cost && wgs > best_wgs)) {
+        best_cost = cost;
+        best_wgs = wgs;
+        best = LmFlavour{nrt, wide};
+      }
+    }
   }
-  const int c_min = ceil_div(n32, cap);
-  c = c < c_min ? c_min : (c > n32 ? n32 : c);
-  f.nrt = ceil_div(n32, c);
-  a->n_chunks = ceil_div(n32, f.nrt);
-  return f;
+  a->n_tiles = ceil_div(V, best.wide ? 256 : 128);
+  a->n_chunks = ceil_div(n32, best.nrt);
+  return best;
 }
 
 static void lm_flavour_override(bool linear, int N, int V, LmFlavour* f, LmArgs* a) {
