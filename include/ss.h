@@ -304,6 +304,22 @@ int ss_linear_rows(const void* x, const void* W, int N, int d, int V, int dtype,
                    void* stream);
 
 /*
+ * n1 with a workspace.  The same map as ss_linear_rows; with scratch memory at
+ * hand a bf16 map with few outputs and many features (a layer's down and output
+ * maps) is cut along the feature dimension: ss_linear_rows_splits(...) slices of
+ * d run as workgroups of their own, leave fp32 partial products [slices,N,V] in
+ * the workspace, and a second kernel adds them in slice order and rounds once.
+ * The result differs from ss_linear_rows only by the order of the fp32 sum.
+ *  workspace: device scratch of at least ss_linear_rows_workspace_bytes(...)
+ *  bytes (any contents; 256 when the shape is not cut, and then it is not used).
+ * Errors as ss_linear_rows, and SS_ERR_WORKSPACE.  SS_F32 runs ss_linear_rows.
+ */
+size_t ss_linear_rows_workspace_bytes(int N, int d, int V, int dtype);
+int ss_linear_rows_splits(int N, int d, int V, int dtype);
+int ss_linear_rows_ws(const void* x, const void* W, int N, int d, int V, int dtype, void* y,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * n4. Stream insertion (Eq. 3): the rows of a step as they enter the first
  * multi-stream layer, from the main-stream hidden states of the tree nodes.
  *    X[b, i]                 = M[b,i]                 main row of node i

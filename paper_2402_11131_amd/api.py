@@ -28,7 +28,7 @@ SS_MAX_T, SS_MAX_GAMMA, SS_MAX_K = 64, 8, 8
 EXPORTS = (
     "ss_version", "ss_last_error", "ss_probe_hbm_read", "ss_probe_mfma_bf16", "ss_check_tree_host", "ss_build_mask", "ss_msa_workspace_bytes",
     "ss_msa_attention", "ss_msa_workspace_init", "ss_msa_attention_static", "ss_msa_static_scratch_bytes", "ss_msa_plan", "ss_msa_set_split_keys", "ss_msa_set_merge_in_kernel", "ss_lm_head_workspace_bytes", "ss_lm_set_flavour", "ss_lm_set_stagger", "ss_lm_set_candidates_only", "ss_lm_head_argmax_topk", "ss_lm_head_verify_draft",
-    "ss_tree_verify", "ss_tree_draft", "ss_full_tree_template_host", "ss_kv_commit", "ss_kv_alloc_pages", "ss_linear_rows", "ss_stream_insert", "ss_stream_insert_linear", "ss_stream_insert_linear_workspace_bytes", "ss_value_rotate",
+    "ss_tree_verify", "ss_tree_draft", "ss_full_tree_template_host", "ss_kv_commit", "ss_kv_alloc_pages", "ss_linear_rows", "ss_linear_rows_ws", "ss_linear_rows_workspace_bytes", "ss_linear_rows_splits", "ss_stream_insert", "ss_stream_insert_linear", "ss_stream_insert_linear_workspace_bytes", "ss_value_rotate",
     "ss_lm_head_logsumexp", "ss_transition_probs", "ss_tree_prune", "ss_live_rows", "ss_msa_attention_pruned",
     "ss_linear_rows_live", "ss_lm_head_argmax_topk_live", "ss_lm_head_verify_draft_live",
 )
@@ -85,6 +85,10 @@ def load_library() -> ctypes.CDLL:
     lib.ss_kv_commit.argtypes = [vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp, vp]
     lib.ss_kv_alloc_pages.argtypes = [vp, i32, vp, vp, i32, i32, i32, vp, vp, vp, vp]
     lib.ss_linear_rows.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp]
+    lib.ss_linear_rows_ws.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, sz, vp]
+    lib.ss_linear_rows_workspace_bytes.argtypes = [i32, i32, i32, i32]
+    lib.ss_linear_rows_workspace_bytes.restype = sz
+    lib.ss_linear_rows_splits.argtypes = [i32, i32, i32, i32]
     lib.ss_stream_insert.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp, vp]
     lib.ss_stream_insert_linear_workspace_bytes.argtypes = [i32] * 7
     lib.ss_stream_insert_linear_workspace_bytes.restype = sz
@@ -556,6 +560,37 @@ def ss_linear_rows(x: torch.Tensor, W: torch.Tensor, y: Optional[torch.Tensor] =
                                        int(plan_rows), _stream()))
         return y
     _check(lib.ss_linear_rows(_dev(x, dt, "x"), _dev(W, dt, "W"), N, d, V, code, _dev(y, dt, "y"), _stream()))
+    return y
+
+
+def ss_linear_rows_workspace_bytes(N: int, d: int, V: int, dtype_code: int) -> int:
+    return int(load_library().ss_linear_rows_workspace_bytes(N, d, V, dtype_code))
+
+
+def ss_linear_rows_splits(N: int, d: int, V: int, dtype_code: int) -> int:
+    """Slices of the feature dimension ss_linear_rows_ws uses for this shape (1 = the map is not cut)."""
+    return int(load_library().ss_linear_rows_splits(N, d, V, dtype_code))
+
+
+def ss_linear_rows_ws(x: torch.Tensor, W: torch.Tensor, y: Optional[torch.Tensor] = None,
+                      workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """n1 with a workspace: the same map as ss_linear_rows; maps with few outputs and many features are cut along
+    the feature dimension (fp32 partial products in the workspace, added by a second kernel)."""
+    lib = load_library()
+    code = _dtype_code(x)
+    dt = x.dtype
+    N, d = x.shape
+    V = W.shape[0]
+    if tuple(W.shape) != (V, d):
+        raise ValueError("W must be [V,%d]" % d)
+    if y is None:
+        y = torch.empty(N, V, dtype=dt, device=x.device)
+    elif tuple(y.shape) != (N, V):
+        raise ValueError("y must be [%d,%d]" % (N, V))
+    if workspace is None:
+        workspace = torch.empty(max(ss_linear_rows_workspace_bytes(N, d, V, code), 1), dtype=torch.uint8, device=x.device)
+    _check(lib.ss_linear_rows_ws(_dev(x, dt, "x"), _dev(W, dt, "W"), N, d, V, code, _dev(y, dt, "y"),
+                                 _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream()))
     return y
 
 

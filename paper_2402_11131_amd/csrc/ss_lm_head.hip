@@ -30,6 +30,8 @@ struct LmArgs {
   float* lse;          // [N], log-sum-exp flavour only; its parts (max, sum) per (row, tile) use cand_key's memory
   const int32_t* live_rows;  // rows to compute, ascending ([N], the first *n_live entries count), or NULL = all N rows
   const int32_t* n_live;     // [1] device, or NULL
+  int n_ksplit;        // workgroups that share a tile's feature dimension (bf16 projection with a workspace), else 1
+  float* part;         // [n_ksplit, N, V] fp32 partial products of those workgroups, else NULL
 };
 
 // Rows a launch computes, and the row of `hidden` / of the outputs that its r-th computed row is (r is clamped
@@ -288,6 +290,43 @@ SS_DEV void lm_epilogue(const LmArgs& a, floatx16 (&acc)[NRT], unsigned char* hb
       if (row0 + r < n_rows) reinterpret_cast<float2*>(a.cand_key)[(size_t)lm_row_id(a, row0 + r, n_rows) * a.n_tiles + tile] = p;
     }
     return;
+  } else if constexpr (KT == -2) {
+    // Partial product of one slice of the feature dimension: the fp32 tile is turned round through LDS in two
+    // halves of the rows (a whole tile of 160 x 256 floats would not fit beside nothing) and leaves in 16-byte
+    // pieces, 4*TI contiguous bytes per row, into this slice's plane of the workspace.
+    constexpr int YS = 4 * TI + 16;
+    constexpr int HALF = (NRT + 1) / 2;  // row tiles per pass
+    const int ks = a.n_ksplit > 1 ? (int)((blockIdx.x >> 3) % (a.n_chunks * a.n_ksplit)) / a.n_chunks : 0;
+    float* plane = a.part + (size_t)ks * a.N * a.V;
+    const bool vec_ok = (a.V % 4) == 0 && ((uintptr_t)a.part & 15) == 0;
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+      if (pass == 1) __syncthreads();
+#pragma unroll
+      for (int rt = pass * HALF; rt < NRT && rt < (pass + 1) * HALF; ++rt)
+#pragma unroll
+        for (int eg = 0; eg < 4; ++eg) {
+          const floatx4 v = floatx4{acc[rt][4 * eg], acc[rt][4 * eg + 1], acc[rt][4 * eg + 2], acc[rt][4 * eg + 3]};
+          *reinterpret_cast<floatx4*>(hbuf + (32 * (rt - pass * HALF) + ln) * YS + (32 * w + 8 * eg + 4 * lh) * 4) = v;
+        }
+      __syncthreads();
+      const int rows_here = 32 * ((pass == 0 ? HALF : NRT - HALF));
+      for (int p = tid; p < rows_here * (TI / 4); p += 64 * NW) {
+        const int r = p / (TI / 4), ch = p % (TI / 4);
+        const int id0 = tile * TI + 4 * ch, rr = row0 + 32 * pass * HALF + r;
+        if (rr >= n_rows || id0 >= a.V) continue;
+        const floatx4 piece = *reinterpret_cast<const floatx4*>(hbuf + r * YS + ch * 16);
+        float* dst = plane + (size_t)lm_row_id(a, rr, n_rows) * a.V + id0;
+        if (vec_ok) {
+          *reinterpret_cast<floatx4*>(dst) = piece;
+        } else {
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            if (id0 + j < a.V) dst[j] = piece[j];
+        }
+      }
+    }
+    return;
   } else if constexpr (KT == 0) {
     // Plain projection: the tile is rounded to bf16 and turned round through LDS ([ROWS] rows of TI
     // outputs, padded by 16 bytes so that the 8-byte writes of 32 rows spread over the banks), then
@@ -416,6 +455,7 @@ __global__ __launch_bounds__(64 * NW, 1) void lm_head_bf16_kernel(LmArgs a) {
   constexpr int BB = HB + TI * 128;  // ... and of W behind it
   static_assert(NBUF * BB <= 160 * 1024, "buffers must fit 160 KB");
   static_assert(NBUF * BB >= ROWS * (2 * TI + 16) && NBUF * BB >= ROWS * NW * 64, "epilogue must fit the buffers");
+  static_assert(KT != -2 || NBUF * BB >= ((NRT + 1) / 2) * 32 * (4 * TI + 16), "half of the fp32 tile must fit the buffers");
   constexpr int NH = (4 * NRT + NW - 1) / NW;  // hidden loads per wave and step
   constexpr int NLD = NH + 4;                  // global loads per wave and step
   extern __shared__ __attribute__((aligned(16))) unsigned char hbuf[];  // [NBUF][BB], reused by the epilogue
@@ -424,12 +464,15 @@ __global__ __launch_bounds__(64 * NW, 1) void lm_head_bf16_kernel(LmArgs a) {
   // Workgroup -> (vocabulary tile, row chunk).  Workgroups are dealt to the eight XCDs in turn; the row
   // chunks of one vocabulary tile take consecutive turns of ONE XCD, so that they run together and
   // share that tile of W in its L2.
+  // With a split feature dimension the n_ksplit slices of a (tile, chunk) are further workgroups of the same XCD.
   const int xcd = blockIdx.x & 7, turn = blockIdx.x >> 3;
-  const int tile = (turn / a.n_chunks) * 8 + xcd;
+  const int per_tile = a.n_chunks * a.n_ksplit;
+  const int tile = (turn / per_tile) * 8 + xcd;
   if (tile >= a.n_tiles) return;
   const int v0 = tile * TI + 32 * w;
   const int n_rows = lm_rows(a);
-  const int d = a.d, n_k = d / 64;
+  const int d = a.d, n_k = d / 64 / a.n_ksplit;                       // feature blocks of this workgroup
+  const size_t k_off = (size_t)((turn % per_tile) / a.n_chunks) * n_k * 128;  // bytes to its first block in a row
   // Feature blocks are walked from a start that differs from tile to tile (by one block between neighbours,
   // when the host asks for it) and wrap around: workgroups that all read the same 128-byte column of W's rows
   // at the same time meet in few memory channels (a read-only probe of this pattern: 5.0 TB/s in step, 6.9 TB/s
@@ -439,7 +482,7 @@ __global__ __launch_bounds__(64 * NW, 1) void lm_head_bf16_kernel(LmArgs a) {
 
   // Row chunks of this workgroup: one, unless the launch was shaped for fewer rows than turn out to be computed
   // (the number of listed rows lives on the device); none if its chunk lies behind the last computed row.
-  for (int row0 = (turn % a.n_chunks) * ROWS; row0 < n_rows; row0 += a.n_chunks * ROWS) {
+  for (int row0 = ((turn % per_tile) % a.n_chunks) * ROWS; row0 < n_rows; row0 += a.n_chunks * ROWS) {
   // load slots of 8 rows x 128 bytes; lane -> (row lane/8 of the slot, chunk position lane%8, which
   // receives chunk (lane%8) ^ swizzle(row)).  hidden: wave w takes slots w, w+NW, ...; W: its own rows.
   uint32_t h_voff[NH], w_voff[4];
@@ -469,8 +512,8 @@ __global__ __launch_bounds__(64 * NW, 1) void lm_head_bf16_kernel(LmArgs a) {
     for (int e = 0; e < 16; ++e) acc[rt][e] = 0.f;
 
   auto load_block = [&](int J, int buf) {
-    const unsigned char* hb = (const unsigned char*)a.hidden + (size_t)J * 128;
-    const unsigned char* wb = (const unsigned char*)a.W + (size_t)J * 128;
+    const unsigned char* hb = (const unsigned char*)a.hidden + k_off + (size_t)J * 128;
+    const unsigned char* wb = (const unsigned char*)a.W + k_off + (size_t)J * 128;
 #pragma unroll
     for (int i = 0; i < NH; ++i) load_to_lds16(hb, h_voff[i], lds0 + buf * BB + h_slot[i] * 1024);
 #pragma unroll
@@ -507,8 +550,8 @@ __global__ __launch_bounds__(64 * NW, 1) void lm_head_bf16_kernel(LmArgs a) {
     const unsigned char* cur = hbuf + buf * BB;
     const unsigned char* nxt = hbuf + buf_next * BB;
     const int Jn = blk(min(J + NBUF - 1, n_k - 1));
-    const unsigned char* h_base = (const unsigned char*)a.hidden + (size_t)Jn * 128;
-    const unsigned char* w_base = (const unsigned char*)a.W + (size_t)Jn * 128;
+    const unsigned char* h_base = (const unsigned char*)a.hidden + k_off + (size_t)Jn * 128;
+    const unsigned char* w_base = (const unsigned char*)a.W + k_off + (size_t)Jn * 128;
     const uint32_t dst = lds0 + buf_fill * BB;
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
@@ -715,13 +758,14 @@ static int launch_lm_bf16_rk(hipStream_t st, const LmArgs& a) {
   });
   if (attr_err[variant] != hipSuccess)
     SS_FAIL(SS_ERR_HIP, "lm_head_bf16_kernel: hipFuncSetAttribute: %s", hipGetErrorString(attr_err[variant]));
-  const dim3 grid(8 * a.n_chunks * ceil_div(a.n_tiles, 8));
+  const dim3 grid(8 * a.n_chunks * a.n_ksplit * ceil_div(a.n_tiles, 8));
   hipLaunchKernelGGL(kern, grid, dim3(threads), lds, st, a);
   return check_launch("lm_head_bf16_kernel");
 }
 template <int NRT, int WIDE>
 static int launch_lm_bf16_r(int KT, hipStream_t st, const LmArgs& a) {
   switch (KT) {
+    case -2: return launch_lm_bf16_rk<NRT, -2, WIDE>(st, a);
     case -1: return launch_lm_bf16_rk<NRT, -1, WIDE>(st, a);
     case 0: return launch_lm_bf16_rk<NRT, 0, WIDE>(st, a);
     case 1: return launch_lm_bf16_rk<NRT, 1, WIDE>(st, a);
@@ -787,6 +831,62 @@ static LmFlavour lm_choose(int N, int V, LmArgs* a) {
   }
   a->n_tiles = ceil_div(V, best.wide ? 256 : 128);
   a->n_chunks = ceil_div(n32, best.nrt);
+  return best;
+}
+
+// Sum of the feature slices' fp32 partial products, in slice order, rounded once to bf16: four outputs per thread.
+__global__ __launch_bounds__(256) void linear_ksplit_reduce_kernel(const float* __restrict__ part, uint16_t* __restrict__ y,
+                                                                 size_t nv, int n_ksplit) {
+  const size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (i >= nv) return;
+  if (i + 4 <= nv && (nv & 3) == 0 && (((uintptr_t)part | (uintptr_t)y) & 15) == 0) {
+    floatx4 sum = *reinterpret_cast<const floatx4*>(part + i);
+    for (int sl = 1; sl < n_ksplit; ++sl) sum += *reinterpret_cast<const floatx4*>(part + (size_t)sl * nv + i);
+    *reinterpret_cast<uintx2*>(y + i) = uintx2{pack_bf16x2(sum[0], sum[1]), pack_bf16x2(sum[2], sum[3])};
+  } else {
+    for (size_t j = i; j < nv && j < i + 4; ++j) {
+      float sum = part[j];
+      for (int sl = 1; sl < n_ksplit; ++sl) sum += part[(size_t)sl * nv + j];
+      y[j] = (uint16_t)f32_to_bf16_bits(sum);
+    }
+  }
+}
+
+// Shape of a bf16 projection that may split the feature dimension between workgroups (the caller gave a
+// workspace for the fp32 partial products).  Estimated time, by the reasoning of lm_choose: a workgroup loads
+// (ids + rows) x (d / slices) x 2 bytes at about 16 KB per 0.3 us; with slices, the partial products are written
+// and read back by a second kernel (5 us + their bytes at 3 TB/s).  Few outputs and many features (a layer's
+// down and output maps: 4096 outputs fill 160 of 256 compute units with tiles of 128 ids x 64 rows) gain from
+// four slices with tiles of 128 ids x 160 rows; maps with many outputs stay unsplit.
+struct LinearPlan {
+  LmFlavour f;
+  int n_tiles, n_chunks, n_ksplit;
+};
+static LinearPlan linear_plan(int N, int d, int V) {
+  const int n32 = ceil_div(N < 1 ? 1 : N, 32), blocks = d / 64;
+  LinearPlan best{LmFlavour{1, 0}, 1, 1, 1};
+  double best_us = -1.0;
+  long best_wgs = 0;
+  for (int ks = 1; ks <= 4; ks *= 2) {
+    if (blocks % ks != 0 || blocks / ks < 2) continue;
+    const double reduce_us = ks > 1 ? 5.0 + ((double)ks * N * V * 4 + (double)N * V * 2) / 3.0e6 : 0.0;
+    for (int wide = 0; wide <= 1; ++wide) {
+      const int ids = wide ? 256 : 128, cap = wide ? 5 : 6;
+      const long tiles = ceil_div(V, ids);
+      for (int nrt = 1; nrt <= cap; ++nrt) {
+        const int chunks = ceil_div(n32, nrt);
+        if (ceil_div(n32, chunks) != nrt) continue;
+        const long wgs = tiles * chunks * ks, rounds = (wgs + 255) / 256;
+        // a cut map has to look a sixth better than the best uncut one before the second kernel is taken on
+        const double us = ((double)rounds * (ids + 32 * nrt) * ((double)d / ks) * 2.0 * 0.30 / 16384.0 + reduce_us) * (ks > 1 ? 1.2 : 1.0);
+        if (best_us < 0 || us < best_us - 1e-9 || (us < best_us + 1e-9 && wgs > best_wgs)) {
+          best_us = us;
+          best_wgs = wgs;
+          best = LinearPlan{LmFlavour{nrt, wide}, (int)tiles, chunks, ks};
+        }
+      }
+    }
+  }
   return best;
 }
 
@@ -868,6 +968,7 @@ static int lm_candidates(const char* fn, const void* hidden, const void* W, int 
   a.idx = nullptr; a.val = nullptr;
   a.y = nullptr; a.lse = nullptr;
   a.live_rows = sel.rows; a.n_live = sel.n;
+  a.n_ksplit = 1; a.part = nullptr;
   if (dtype == SS_F32) {
     dim3 grid(a.n_tiles, ceil_div(N, 32));
     SS_REQUIRE(grid.y <= 65535, SS_ERR_UNSUPPORTED, "%s: N too large", fn);
@@ -1011,6 +1112,7 @@ int ss_lm_head_logsumexp(const void* hidden, const void* W, int N, int d, int V,
   a.idx = nullptr; a.val = nullptr; a.y = nullptr;
   a.lse = lse;
   a.live_rows = nullptr; a.n_live = nullptr;
+  a.n_ksplit = 1; a.part = nullptr;
   hipStream_t st = (hipStream_t)stream;
   if (dtype == SS_F32) {
     dim3 grid(a.n_tiles, ceil_div(N, 32));
@@ -1042,6 +1144,7 @@ static int linear_run(const char* fn, const void* x, const void* W, int N, int d
   a.k_stagger = 0;
   a.cand_key = nullptr; a.idx = nullptr; a.val = nullptr; a.lse = nullptr;
   a.live_rows = sel.rows; a.n_live = sel.n;
+  a.n_ksplit = 1; a.part = nullptr;
   a.y = y;
   hipStream_t st = (hipStream_t)stream;
   if (dtype == SS_F32) {
@@ -1068,6 +1171,50 @@ int ss_linear_rows_live(const void* x, const void* W, int N, int d, int V, int d
   ss::clear_error();
   SS_REQUIRE(N == 0 || (live_rows && n_live), SS_ERR_INVALID_ARG, "ss_linear_rows_live: NULL row list");
   return linear_run("ss_linear_rows_live", x, W, N, d, V, dtype, y, ss::RowSel{live_rows, n_live, plan_rows}, stream);
+}
+
+size_t ss_linear_rows_workspace_bytes(int N, int d, int V, int dtype) {
+  ss::clear_error();
+  if (ss::gemm_check("ss_linear_rows_workspace_bytes", N, d, V, dtype) != SS_OK) return 0;
+  if (dtype != SS_BF16 || N == 0) return 256;
+  const ss::LinearPlan p = ss::linear_plan(N, d, V);
+  return p.n_ksplit > 1 ? (size_t)p.n_ksplit * N * V * sizeof(float) + 256 : 256;
+}
+
+int ss_linear_rows_splits(int N, int d, int V, int dtype) {
+  ss::clear_error();
+  if (ss::gemm_check("ss_linear_rows_splits", N, d, V, dtype) != SS_OK) return 0;
+  return (dtype == SS_BF16 && N > 0) ? ss::linear_plan(N, d, V).n_ksplit : 1;
+}
+
+int ss_linear_rows_ws(const void* x, const void* W, int N, int d, int V, int dtype, void* y, void* workspace,
+                      size_t workspace_bytes, void* stream) {
+  using namespace ss;
+  clear_error();
+  const char* fn = "ss_linear_rows_ws";
+  if (int rc = gemm_check(fn, N, d, V, dtype)) return rc;
+  const LinearPlan p = (dtype == SS_BF16 && N > 0) ? linear_plan(N, d, V) : LinearPlan{LmFlavour{1, 0}, 1, 1, 1};
+  if (p.n_ksplit == 1) return linear_run(fn, x, W, N, d, V, dtype, y, RowSel{nullptr, nullptr, 0}, stream);
+  SS_REQUIRE(x && W && y, SS_ERR_INVALID_ARG, "%s: NULL tensor argument", fn);
+  SS_REQUIRE((long)N * V < (1L << 31), SS_ERR_UNSUPPORTED, "%s: y (%d x %d) has 2^31 elements or more", fn, N, V);
+  const size_t need = (size_t)p.n_ksplit * N * V * sizeof(float) + 256;
+  SS_REQUIRE(workspace != nullptr && workspace_bytes >= need, SS_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given", fn,
+             need, workspace_bytes);
+  LmArgs a;
+  a.hidden = x; a.W = W; a.N = N; a.d = d; a.V = V; a.K = 0;
+  a.n_tiles = p.n_tiles; a.n_chunks = p.n_chunks;
+  a.k_stagger = 0;
+  a.cand_key = nullptr; a.idx = nullptr; a.val = nullptr; a.lse = nullptr; a.y = nullptr;
+  a.live_rows = nullptr; a.n_live = nullptr;
+  a.n_ksplit = p.n_ksplit;
+  a.part = (float*)(((uintptr_t)workspace + 255) & ~(uintptr_t)255);
+  SS_REQUIRE((long)a.n_chunks * a.n_ksplit * (a.n_tiles + 7) < (1L << 27), SS_ERR_UNSUPPORTED, "%s: N x V too large", fn);
+  hipStream_t st = (hipStream_t)stream;
+  if (int rc = launch_lm_bf16(p.f, -2, st, a)) return rc;
+  const size_t nv = (size_t)N * V;
+  hipLaunchKernelGGL(linear_ksplit_reduce_kernel, dim3((unsigned)((nv / 4 + 256) / 256)), dim3(256), 0, st, a.part, (uint16_t*)y, nv,
+                     a.n_ksplit);
+  return check_launch(fn);
 }
 
 }  // extern "C"
