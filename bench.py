@@ -219,7 +219,7 @@ def time_rows_after_hot_path(api, synth, torch, cfg, dev, N, lm, lm_ws, tok, par
     # down of a 4096/11008 feed-forward block.
     dm, dff = cfg.d_model, 11008
     dense = {}
-    total = 0.0
+    total = total_plain = 0.0
     for name, (din, dout) in (("qkv", (dm, 3 * cfg.H * cfg.D)), ("attn_out", (cfg.H * cfg.D, dm)),
                               ("gate_up", (dm, 2 * dff)), ("down", (dff, dm))):
         # Weights come from HBM in a model (a layer's 400 MB, 13 GB for all layers): as many copies in turn as
@@ -229,13 +229,21 @@ def time_rows_after_hot_path(api, synth, torch, cfg, dev, N, lm, lm_ws, tok, par
         x0 = synth.make_lm_head_inputs(synth.scaled(cfg, vocab=dout, d_model=din), 50, device=dev, N=N)
         xs = [x0] + [{"hidden": x0["hidden"], "W": x0["W"].clone()} for _ in range(copies - 1)]
         y = torch.empty(N, dout, dtype=xs[0]["hidden"].dtype, device=dev)
-        us = kernel_timed(lambda i: api.ss_linear_rows(xs[i % copies]["hidden"], xs[i % copies]["W"], y), torch)
+        us_plain = kernel_timed(lambda i: api.ss_linear_rows(xs[i % copies]["hidden"], xs[i % copies]["W"], y), torch)
+        # the same map with a workspace: few outputs and many features are cut along the feature dimension
+        slices = api.ss_linear_rows_splits(N, din, dout, api.SS_BF16)
+        lin_ws = torch.empty(api.ss_linear_rows_workspace_bytes(N, din, dout, api.SS_BF16), dtype=torch.uint8, device=dev)
+        us = kernel_timed(lambda i: api.ss_linear_rows_ws(xs[i % copies]["hidden"], xs[i % copies]["W"], y, workspace=lin_ws),
+                          torch) if slices > 1 else us_plain
         total += us
-        dense[name] = {"d_in": din, "d_out": dout, "us": round(us, 2), "weight_copies_in_turn": copies,
+        total_plain += us_plain
+        dense[name] = {"d_in": din, "d_out": dout, "us": round(us, 2), "feature_slices": slices,
+                       "us_without_workspace": round(us_plain, 2), "weight_copies_in_turn": copies,
                        "tflops": round(2.0 * N * din * dout / (us * 1e-6) / 1e12, 1),
                        "hbm_gbps": round((din * dout + N * din + N * dout) * 2 / (us * 1e-6) / 1e9, 1)}
-        del xs, y
+        del xs, y, lin_ws
     dense["layer_total_us"] = round(total, 2)
+    dense["layer_total_without_workspace_us"] = round(total_plain, 2)
     extra["linear_rows"] = dense
     # The pruning layer: log-sum-exp of the early-exit logits of the B*T main rows over the whole vocabulary,
     # transition probabilities, pruning decision and compaction.
