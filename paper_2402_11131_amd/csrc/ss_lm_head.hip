@@ -722,7 +722,8 @@ static LmTuning& tuning() {
 }
 struct LmFlavour {
   int nrt;   // 32-row tiles per workgroup
-  int wide;  // 0: 4 waves, tile of 128 ids, nrt <= 6; 1: 8 waves, tile of 256 ids, nrt <= 5
+  int wide;  // 0: 4 waves, tile of 128 ids, nrt <= 6; 1: 8 waves, 256 ids, nrt <= 5; 2: 6 waves, 192 ids, nrt <= 5
+             // (projections only: 22016 outputs are 115 such tiles x 2 row chunks = 230 workgroups, not 172)
 };
 
 // Log-sum-exp of a row from its tiles' (max, sum) pairs: one wavefront per row.
@@ -745,6 +746,10 @@ static int launch_lm_bf16_rk(hipStream_t st, const LmArgs& a) {
     kern = lm_head_bf16_kernel<NRT, KT, 8, 3>;
     lds = 3 * ((size_t)(32 * NRT) * 128 + 256 * 128);
     threads = 512;
+  } else if constexpr (WIDE == 2) {
+    kern = lm_head_bf16_kernel<NRT, KT, 6, 3>;
+    lds = 3 * ((size_t)(32 * NRT) * 128 + 192 * 128);
+    threads = 384;
   } else {
     kern = a.n_chunks == 1 ? lm_head_bf16_kernel<NRT, KT, 4, 4, true> : lm_head_bf16_kernel<NRT, KT, 4, 4, false>;
     lds = 4 * ((size_t)(32 * NRT) * 128 + 128 * 128);
@@ -764,13 +769,19 @@ static int launch_lm_bf16_rk(hipStream_t st, const LmArgs& a) {
 }
 template <int NRT, int WIDE>
 static int launch_lm_bf16_r(int KT, hipStream_t st, const LmArgs& a) {
-  switch (KT) {
-    case -2: return launch_lm_bf16_rk<NRT, -2, WIDE>(st, a);
-    case -1: return launch_lm_bf16_rk<NRT, -1, WIDE>(st, a);
-    case 0: return launch_lm_bf16_rk<NRT, 0, WIDE>(st, a);
-    case 1: return launch_lm_bf16_rk<NRT, 1, WIDE>(st, a);
-    case 4: return launch_lm_bf16_rk<NRT, 4, WIDE>(st, a);
-    default: return launch_lm_bf16_rk<NRT, 8, WIDE>(st, a);
+  if constexpr (WIDE == 2) {  // six waves: the projections only
+    if (KT == -2) return launch_lm_bf16_rk<NRT, -2, WIDE>(st, a);
+    if (KT == 0) return launch_lm_bf16_rk<NRT, 0, WIDE>(st, a);
+    SS_FAIL(SS_ERR_UNSUPPORTED, "lm_head_bf16_kernel: no six-wave kernel for epilogue %d", KT);
+  } else {
+    switch (KT) {
+      case -2: return launch_lm_bf16_rk<NRT, -2, WIDE>(st, a);
+      case -1: return launch_lm_bf16_rk<NRT, -1, WIDE>(st, a);
+      case 0: return launch_lm_bf16_rk<NRT, 0, WIDE>(st, a);
+      case 1: return launch_lm_bf16_rk<NRT, 1, WIDE>(st, a);
+      case 4: return launch_lm_bf16_rk<NRT, 4, WIDE>(st, a);
+      default: return launch_lm_bf16_rk<NRT, 8, WIDE>(st, a);
+    }
   }
 }
 // Rows go to the workgroups in n_chunks chunks of 32*NRT rows; a.n_chunks and a.n_tiles must be set
@@ -783,6 +794,15 @@ static int launch_lm_bf16(LmFlavour f, int KT, hipStream_t st, const LmArgs& arg
   a.k_stagger = a.n_chunks == 1 ? 1 : 0;
   const int forced_stagger = tuning().stagger.load();
   if (forced_stagger >= 0) a.k_stagger = forced_stagger;
+  if (f.wide == 2) {
+    switch (f.nrt) {
+      case 1: return launch_lm_bf16_r<1, 2>(KT, st, a);
+      case 2: return launch_lm_bf16_r<2, 2>(KT, st, a);
+      case 3: return launch_lm_bf16_r<3, 2>(KT, st, a);
+      case 4: return launch_lm_bf16_r<4, 2>(KT, st, a);
+      default: return launch_lm_bf16_r<5, 2>(KT, st, a);
+    }
+  }
   if (f.wide) {
     switch (f.nrt) {
       case 1: return launch_lm_bf16_r<1, 1>(KT, st, a);
@@ -805,31 +825,33 @@ static int launch_lm_bf16(LmFlavour f, int KT, hipStream_t st, const LmArgs& arg
 // Which MFMA kernel, how many rows per workgroup and how many row chunks.  A compute unit holds one workgroup
 // (LDS) and sustains a fixed number of outstanding reads, so a launch takes about (rounds of 256 workgroups) x
 // (bytes a workgroup loads) x (latency): the shape with the smallest rounds x (ids + rows) per tile wins; among
-// equals the one with more workgroups.  Measured with weights that no cache holds, 320 rows: 32000 outputs ->
+// equals the one with fewer workgroups, i.e. less traffic through the L2 in all (12288 outputs: 192 workgroups of
+// 128 ids x 160 rows take 50 us, 256 workgroups of 192 ids x 96 rows 53 us).  Measured with weights that no cache holds, 320 rows: 32000 outputs ->
 // 8 waves, 256 ids x 160 rows, 250 workgroups (4 waves x 128 ids would need two rounds); 22016 -> the same
-// shape, 172 workgroups; 12288 -> 4 waves, 128 ids x 160 rows, 192 workgroups (50 us; 256 ids x 64 rows in 240
+// shape, 172 workgroups (projections: 6 waves, 192 ids x 160 rows, 230 workgroups, 68 us against 75); 12288 -> 4 waves, 128 ids x 160 rows, 192 workgroups (50 us; 256 ids x 64 rows in 240
 // workgroups: 59 us); 4096 -> 4 waves, 128 ids x 64 rows.  Only balanced chunkings are considered (every
 // chunk as many 32-row tiles as the largest needs).
-static LmFlavour lm_choose(int N, int V, LmArgs* a) {
+static int flavour_ids(int wide) { return wide == 0 ? 128 : (wide == 1 ? 256 : 192); }
+static LmFlavour lm_choose(int N, int V, LmArgs* a, bool six_waves_ok = false) {
   const int n32 = ceil_div(N < 1 ? 1 : N, 32);
   LmFlavour best{1, 0};
   long best_cost = -1, best_wgs = 0;
-  for (int wide = 0; wide <= 1; ++wide) {
-    const int ids = wide ? 256 : 128, cap = wide ? 5 : 6;
+  for (int wide = 0; wide <= (six_waves_ok ? 2 : 1); ++wide) {
+    const int ids = flavour_ids(wide), cap = wide ? 5 : 6;
     const long tiles = ceil_div(V, ids);
     for (int nrt = 1; nrt <= cap; ++nrt) {
       const int chunks = ceil_div(n32, nrt);
       if (ceil_div(n32, chunks) != nrt) continue;  // the same chunking with fewer tiles per chunk comes by itself
       const long wgs = tiles * chunks, rounds = (wgs + 255) / 256;
       const long cost = rounds * (ids + 32 * nrt);
-      if (best_cost < 0 || cost < best_cost || (cost == best_cost && wgs > best_wgs)) {
+      if (best_cost < 0 || cost < best_cost || (cost == best_cost && wgs < best_wgs)) {
         best_cost = cost;
         best_wgs = wgs;
         best = LmFlavour{nrt, wide};
       }
     }
   }
-  a->n_tiles = ceil_div(V, best.wide ? 256 : 128);
+  a->n_tiles = ceil_div(V, flavour_ids(best.wide));
   a->n_chunks = ceil_div(n32, best.nrt);
   return best;
 }
@@ -870,8 +892,8 @@ static LinearPlan linear_plan(int N, int d, int V) {
   for (int ks = 1; ks <= 4; ks *= 2) {
     if (blocks % ks != 0 || blocks / ks < 2) continue;
     const double reduce_us = ks > 1 ? 5.0 + ((double)ks * N * V * 4 + (double)N * V * 2) / 3.0e6 : 0.0;
-    for (int wide = 0; wide <= 1; ++wide) {
-      const int ids = wide ? 256 : 128, cap = wide ? 5 : 6;
+    for (int wide = 0; wide <= 2; ++wide) {
+      const int ids = flavour_ids(wide), cap = wide ? 5 : 6;
       const long tiles = ceil_div(V, ids);
       for (int nrt = 1; nrt <= cap; ++nrt) {
         const int chunks = ceil_div(n32, nrt);
@@ -879,7 +901,7 @@ static LinearPlan linear_plan(int N, int d, int V) {
         const long wgs = tiles * chunks * ks, rounds = (wgs + 255) / 256;
         // a cut map has to look a sixth better than the best uncut one before the second kernel is taken on
         const double us = ((double)rounds * (ids + 32 * nrt) * ((double)d / ks) * 2.0 * 0.30 / 16384.0 + reduce_us) * (ks > 1 ? 1.2 : 1.0);
-        if (best_us < 0 || us < best_us - 1e-9 || (us < best_us + 1e-9 && wgs > best_wgs)) {
+        if (best_us < 0 || us < best_us - 1e-9 || (us < best_us + 1e-9 && wgs < best_wgs)) {
           best_us = us;
           best_wgs = wgs;
           best = LinearPlan{LmFlavour{nrt, wide}, (int)tiles, chunks, ks};
@@ -1152,7 +1174,7 @@ static int linear_run(const char* fn, const void* x, const void* W, int N, int d
     SS_REQUIRE(grid.y <= 65535, SS_ERR_UNSUPPORTED, "%s: N too large", fn);
     hipLaunchKernelGGL(lm_head_f32_kernel<1>, grid, dim3(256), 0, st, a);
   } else {
-    LmFlavour f = lm_choose(plan_n(sel, N), V, &a);
+    LmFlavour f = lm_choose(plan_n(sel, N), V, &a, true);
     lm_flavour_override(true, plan_n(sel, N), V, &f, &a);
     SS_REQUIRE((long)a.n_chunks * (a.n_tiles + 7) < (1L << 27), SS_ERR_UNSUPPORTED, "%s: N x V too large", fn);
     if (int rc = launch_lm_bf16(f, 0, st, a)) return rc;
