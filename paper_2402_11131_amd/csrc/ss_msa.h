@@ -47,7 +47,7 @@ SS_DEV int split_len(int s, const MsaArgs& a) { return s == 0 ? a.split0_keys : 
 
 // Arrival counters of the in-kernel split merge: one per (sequence, KV head, row chunk, query tile of at most
 // kArriveTiles per chunk).
-constexpr int kArriveTiles = 5;
+constexpr int kArriveTiles = 8;
 
 // MFMA path (bf16, D = 64 or 128).  Returns SS_OK or an error code.
 int launch_msa_bf16(const MsaArgs& a, hipStream_t stream);

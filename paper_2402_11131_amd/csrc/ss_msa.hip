@@ -281,11 +281,28 @@ static MsaPlan make_plan(int B, int R, int H, int Hkv, int D, int max_len, int d
       p.groups = 3;
       p.stages = 3;
     }
+    if (p.n_qc > 1) p.groups = msa_bf16_rows_per_chunk(g * R) == 128 ? 2 : 3;  // 16 or 15 waves per workgroup
   }
   if (split_keys <= 0) {
     int n = ceil_div(want_wgs, base);
     const int n_cap = len / 256 < 1 ? 1 : len / 256;
     if (n > n_cap) n = n_cap;
+    if (dtype == SS_BF16 && p.n_qc > 1 && base >= 256) {
+      // Several row chunks, one workgroup per compute unit: whole rounds of 256 workgroups matter more than
+      // anything else.  The fewest splits (of at least 1024 tokens) that waste the least of the last round:
+      // 320 items -> 4 splits = 5 rounds exactly (c5: 845 us; unsplit, in 2 rounds of which the second is a
+      // quarter full: 1120 us).
+      int best_n = 1;
+      double best_waste = 0.0;
+      for (int cand = 1; cand <= 8 && (cand == 1 || len / cand >= 1024); ++cand) {
+        const double wgs = (double)base * cand, waste = ceil(wgs / 256.0) * 256.0 / wgs;
+        if (cand == 1 || waste < best_waste - 1e-9) {
+          best_n = cand;
+          best_waste = waste;
+        }
+      }
+      n = best_n;
+    }
     split_keys = ceil_div(ceil_div(len, unit), n) * unit;
   }
   split_keys = (int)align_up((size_t)(split_keys < 64 ? 64 : split_keys), unit);

@@ -693,11 +693,15 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
   if (lane == 0) st_counter_device(ctr, 0u);  // the next call finds the counters zero again
 }
 
-// Folded query rows one workgroup takes (a multiple of 16, at most 80).
+// Folded query rows one workgroup takes: a multiple of 16, at most 80 (five waves per wave group) where one chunk
+// holds all rows.  With more rows (long GQA trees: the shapes bound by arithmetic and by the traffic from the L2,
+// since every row chunk of a KV head fetches all of its K/V) the chunk that pads the rows least wins among 128
+// (eight waves per group, two groups), 80, 64 and 48, the larger one on a tie: 640 rows are 5 chunks of 128
+// (5.4 GB through the compute units' L1s on c5) rather than 8 of 80 (8.7 GB).
 int msa_bf16_rows_per_chunk(int F) {
   if (F <= 80) return 16 * ceil_div(F < 1 ? 1 : F, 16);
-  int best = 80, best_pad = ceil_div(F, 80) * 80 - F;
-  const int cands[2] = {64, 48};
+  int best = 128, best_pad = ceil_div(F, 128) * 128 - F;
+  const int cands[3] = {80, 64, 48};
   for (int cnd : cands) {
     const int pad = ceil_div(F, cnd) * cnd - F;
     if (pad < best_pad) {
@@ -772,6 +776,7 @@ static int launch_d(const MsaArgs& a, hipStream_t stream) {
     case 3: return launch_dn<D, 3>(a, stream);
     case 4: return launch_dn<D, 4>(a, stream);
     case 5: return launch_dn<D, 5>(a, stream);
+    case 8: return launch_dn<D, 8>(a, stream);
     default: SS_FAIL(SS_ERR_UNSUPPORTED, "ss_msa_attention: bad row chunk %d", rows);
   }
 }

@@ -12,7 +12,7 @@ def test_attention_plans_of_the_five_workloads():
     c = synth.CONFIGS
     assert _msa_plan(c["c4"], 4096) == (2, 1)        # two splits, merged inside the attention kernel
     assert _msa_plan(c["c3"], 4096) == (1, 1)        # 512 (sequence, head) items: unsplit
-    assert _msa_plan(c["c5"], 32768) == (1, 1)       # eight row chunks per KV head fill the chip
+    assert _msa_plan(c["c5"], 32768) == (4, 2)       # five row chunks of 128 rows x 64 KV heads x 4 splits = 5 whole rounds
     splits, kernels = _msa_plan(c["c2"], 2048)
     assert splits == 8 and kernels == 2              # one sequence: 8 splits and the merge kernel
     assert _msa_plan(c["c1"], 128)[1] in (1, 2)
