@@ -1,15 +1,17 @@
 // a2, bf16 path: multi-stream attention (Eq. 1 / Eq. 2) on the gfx950 matrix cores.
 //
 // Work split.  A workgroup owns one (sequence, KV head, split of the cached
-// tokens, chunk of <= 80 folded query rows); the query heads of a GQA group are
+// tokens, chunk of <= 80 folded query rows, or of 128 where a KV head has more
+// than 80); the query heads of a GQA group are
 // folded into the row dimension, so K and V are read once per KV head.  The
 // workgroup consists of G groups of NW wavefronts.  Inside a group every wave
 // owns ONE 16-row query tile (its Q operands, running max / sum and a 16 x D
 // slice of O live in registers) and all NW waves walk the same sequence of
 // 32-key units; the G groups take the units of the split round-robin and their
 // partial (max, sum, O) states are merged through LDS at the end.  With 80 rows
-// that is up to 3 groups x 5 waves = 15 waves per compute unit, which is what hides
-// the LDS, MFMA and exp latencies (no wave depends on long instruction-level overlap).
+// that is up to 3 groups x 5 waves = 15 waves per compute unit, with 128 rows 2 groups
+// x 8 waves = 16, which is what hides the LDS, MFMA and exp latencies (no wave depends
+// on long instruction-level overlap).
 //
 // Memory pipeline.  Every group has a ring of n_stages LDS stages (8 KB of K rows + 8 KB of V for D = 128).
 // Blocks reach it by direct global -> LDS loads (16 bytes per lane, no staging register, counted in the issuing
