@@ -287,6 +287,8 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
   // entries of a lane hold the sum of its query row over all keys of the block (the bf16 probabilities that
   // also enter P V, so numerator and denominator round alike).
   float m_run = -1e30f;
+  float nmc_run = 1e30f * c;             // -(m_run * c), kept beside m_run: one multiplication less per block
+  const float lazy_thr = kLazyLog2 / c;  // the scale is positive: (mx - m_run) * c > 2^4 <=> mx - m_run > lazy_thr
   floatx4 Lacc = floatx4{0.f, 0.f, 0.f, 0.f};
   bf16x8 ones;
 #pragma unroll
@@ -473,21 +475,21 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
     float mx = vmax2(vmax2(vmax2(S[0][0], S[0][1], pinf), vmax2(S[0][2], S[0][3], pinf), pinf),
                      vmax2(vmax2(S[1][0], S[1][1], pinf), vmax2(S[1][2], S[1][3], pinf), pinf), pinf);
     mx = max_over_lane_groups(mx, pinf);
-    if (__any((mx - m_run) * c > kLazyLog2)) {
+    if (__any(mx - m_run > lazy_thr)) {
       const float m_new = fmaxf(m_run, mx);
       const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
       Lacc *= alpha;
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt) O[dt] *= alpha;
       m_run = m_new;
+      nmc_run = -(m_new * c);
     }
-    const float mc = m_run * c;
     bf16x8 P;
 #pragma unroll
     for (int X = 0; X < 2; ++X)
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        P[4 * X + i] = (__bf16)__builtin_amdgcn_exp2f(fmaf(S[X][i], c, -mc));
+        P[4 * X + i] = (__bf16)__builtin_amdgcn_exp2f(fmaf(S[X][i], c, nmc_run));
       }
     Lacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, P, Lacc, 0, 0, 0);
     // ---- O^T += V^T P^T
