@@ -27,7 +27,7 @@ struct MsaArgs {
   int n_qc;        // query-row chunks per (sequence, KV head) (MFMA path)
   int groups;      // wave groups per workgroup the plan asks for (MFMA path)
   int stages;      // ring stages per wave group the plan asks for (MFMA path)
-  unsigned int* arrive;  // MFMA path, two splits merged inside the kernel: arrival counters [B,Hkv,n_qc,5] in the
+  unsigned int* arrive;  // MFMA path, two splits merged inside the kernel: arrival counters [B,Hkv,n_qc,kArriveTiles] in the
                          // workspace (zero before the call, zero again after it), else NULL
   float scale_log2;  // softmax scale times log2(e)
   uint32_t flags;
