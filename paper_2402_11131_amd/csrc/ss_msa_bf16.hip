@@ -589,7 +589,11 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
   unsigned int early = 0;
   if (merge_here && grp == 0) {
     ctr = a.arrive + (((size_t)b * a.Hkv + hk) * a.n_qc + qc) * kArriveTiles + wt;
-    early = ld_counter_device(ctr);
+    // The address is the same in all lanes, but the compiler must not know: it would move the value to the
+    // scalar unit at once, i.e. wait for this round trip here, in front of the merge of the groups.
+    int zero = 0;
+    asm volatile("" : "+v"(zero));
+    early = ld_counter_device(ctr + zero);
   }
   float l_run = Lacc[0];  // already summed over the four lane groups
   floatx4* obuf = reinterpret_cast<floatx4*>(stages);  // [(grp-1)*NW + wt][DT][64]
@@ -608,6 +612,7 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
 
   // rows of the other split, on their way during the merge of the groups
   const int s_other = 1 - s;
+  early = __builtin_amdgcn_readfirstlane(early);
   const bool others_ready = merge_here && early + 1 == (unsigned)n_active;  // n_active is 1 or 2 here
   const bool prefetched = others_ready && n_active == 2 && f_valid;
   float l_other = -INFINITY;
