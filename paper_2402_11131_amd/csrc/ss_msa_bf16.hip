@@ -289,10 +289,13 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
   float m_run = -1e30f;
   float nmc_run = 1e30f * c;             // -(m_run * c), kept beside m_run: one multiplication less per block
   const float lazy_thr = kLazyLog2 / c;  // the scale is positive: (mx - m_run) * c > 2^4 <=> mx - m_run > lazy_thr
+  float m_lim = m_run + lazy_thr;        // scores above this move the maximum; kept beside it as well
   floatx4 Lacc = floatx4{0.f, 0.f, 0.f, 0.f};
   bf16x8 ones;
 #pragma unroll
   for (int i = 0; i < 8; ++i) ones[i] = (__bf16)1.0f;
+  // Kept in four registers from here on: as a known constant the compiler would build it anew in every block.
+  asm volatile("" : "+v"(ones));
 
   // ---- how a block reaches LDS.  A unit is moved in 1 KB slots, one direct-to-LDS load each: K slot sl
   // holds rows ROWS_PER_SLOT*sl + lane/CPR, the lane at chunk position p = lane%CPR fetching chunk
@@ -472,10 +475,12 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
         }
     }
     // ---- online softmax (log2 domain, lazy rescale), probabilities to bf16
-    float mx = vmax2(vmax2(vmax2(S[0][0], S[0][1], pinf), vmax2(S[0][2], S[0][3], pinf), pinf),
-                     vmax2(vmax2(S[1][0], S[1][1], pinf), vmax2(S[1][2], S[1][3], pinf), pinf), pinf);
-    mx = max_over_lane_groups(mx, pinf);
-    if (__any(mx - m_run > lazy_thr)) {
+    // The maximum of a query row lies in four lanes; whether any row of the wave has to move its running
+    // maximum can be told from the lanes' own eight scores, so the exchange between the lanes happens only then.
+    const float mx8 = vmax2(vmax2(vmax2(S[0][0], S[0][1], pinf), vmax2(S[0][2], S[0][3], pinf), pinf),
+                            vmax2(vmax2(S[1][0], S[1][1], pinf), vmax2(S[1][2], S[1][3], pinf), pinf), pinf);
+    if (__any(mx8 > m_lim)) {
+      const float mx = max_over_lane_groups(mx8, pinf);
       const float m_new = fmaxf(m_run, mx);
       const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
       Lacc *= alpha;
@@ -483,6 +488,7 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
       for (int dt = 0; dt < DT; ++dt) O[dt] *= alpha;
       m_run = m_new;
       nmc_run = -(m_new * c);
+      m_lim = m_new + lazy_thr;
     }
     bf16x8 P;
 #pragma unroll
