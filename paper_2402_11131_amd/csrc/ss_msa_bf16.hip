@@ -246,12 +246,15 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
   // or 64 tokens; positions past the table are clamped, such units are never used).  Lane i of every
   // wave keeps the pair for loop iteration jbase + i; one gather serves 64 iterations and a page id
   // reaches the scalar unit through a lane read.
-  int tab_a = 0, tab_b = 0;
+  // What is kept is the page's offset in the cache in units of 256 bytes (a page of one head is at least
+  // 16 x 64 x 2 bytes, and 2^32 such units are 1 TB), so that the scalar unit needs a shift, not a 64-bit product.
+  uint32_t tab_a = 0, tab_b = 0;
+  const uint32_t page_units = (uint32_t)(page_stride / 128);
   const int key_cap = max(a.max_pages * a.page - 32, 0) & ~31;  // last 32-key block the table covers
   auto refill_pages = [&](int jbase) {
     const int kb = min(k0 + 32 * (grp + (jbase + lane) * n_groups), key_cap);
-    tab_a = min(max(my_table[kb >> a.page_shift], 0), a.num_pages - 1);
-    tab_b = min(max(my_table[min((kb + 16) >> a.page_shift, a.max_pages - 1)], 0), a.num_pages - 1);
+    tab_a = (uint32_t)min(max(my_table[kb >> a.page_shift], 0), a.num_pages - 1) * page_units;
+    tab_b = (uint32_t)min(max(my_table[min((kb + 16) >> a.page_shift, a.max_pages - 1)], 0), a.num_pages - 1) * page_units;
   };
   refill_pages(0);
   const int L_raw = a.seq_lens[b];
@@ -307,19 +310,17 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
   const int ril = lane / CPR, pch = lane % CPR;
   const bool loader = wt < LW;
   const int wl = loader ? wt : 0;
-  uint32_t k_voff[KJ];            // per lane, bytes from the slot's scalar base
-  int k_soff[KJ], v_soff[KJ];     // scalar element offsets from the half's base
-  bool k_second[KJ], v_second[KJ];
+  // Slot sl lies in the second 16-key half of the unit when sl >= K_SLOTS / 2 (K and V alike); its offset inside
+  // the half is part of the lane's byte offset, so that a half has one scalar base.
+  uint32_t k_voff[KJ], v_voff[KJ];  // per lane, bytes from the half's scalar base
+  bool second[KJ];
 #pragma unroll
   for (int j = 0; j < KJ; ++j) {
     const int sl = wl + LW * j, r0 = ROWS_PER_SLOT * sl;
-    k_second[j] = r0 >= 16;
-    k_soff[j] = (r0 & 15) * D;
-    k_voff[j] = 2u * (uint32_t)(ril * D + ((pch ^ k_swz<D>(r0 + ril)) * 8));
-    v_second[j] = sl / V_DBLK != 0;
-    v_soff[j] = (sl % V_DBLK) * 32 * a.page;
+    second[j] = sl >= K_SLOTS / 2;
+    k_voff[j] = 2u * (uint32_t)((r0 & 15) * D + ril * D + ((pch ^ k_swz<D>(r0 + ril)) * 8));
+    v_voff[j] = 2u * (uint32_t)((sl % V_DBLK) * 32 * a.page + (lane >> 1) * a.page + (((lane & 1) ^ ((lane >> 4) & 1)) * 8));
   }
-  const uint32_t v_voff = 2u * (uint32_t)((lane >> 1) * a.page + (((lane & 1) ^ ((lane >> 4) & 1)) * 8));
   // operand reads: K row of score tile 0 (tile 1 is 4 rows further, same swizzle), chunk 4*ks + lg; V:
   // feature 16*dt + lq, keys 8*lg .. 8*lg+7
   const int rr0 = block_key(lq, 0);
@@ -329,20 +330,19 @@ __global__ __launch_bounds__(64 * NW * (kMaxWaves / NW < kMaxGroups ? kMaxWaves 
   const int v_rd = K_BYTES + (lg >> 1) * VHALF + lq * 32 + (((lg & 1) ^ ((lq >> 3) & 1)) * 16);
 
   // Main-loop unit u (a full block of the prefix) -> LDS stage at st_addr: scalar base per half.
-  auto dma_main = [&](int u, int pg_a, int pg_b, uint32_t st_addr) {
+  auto dma_main = [&](int u, uint32_t pg_a, uint32_t pg_b, uint32_t st_addr) {
     const int kb = k0 + 32 * u;
-    const int o_a = kb & pmask, o_b = (kb + 16) & pmask;
-    const size_t g_a = (size_t)pg_a * page_stride, g_b = (size_t)pg_b * page_stride;
-    const uint16_t* ka = k_head + g_a + (size_t)o_a * D;
-    const uint16_t* kb2 = k_head + g_b + (size_t)o_b * D;
-    const uint16_t* va = v_head + g_a + o_a;
-    const uint16_t* vb = v_head + g_b + o_b;
+    const uint32_t o_a = (uint32_t)(kb & pmask), o_b = (uint32_t)((kb + 16) & pmask);
+    const size_t g_a = (size_t)pg_a << 8, g_b = (size_t)pg_b << 8;  // bytes
+    const char* ka = (const char*)k_head + g_a + o_a * (2 * D);
+    const char* kb2 = (const char*)k_head + g_b + o_b * (2 * D);
+    const char* va = (const char*)v_head + g_a + 2 * o_a;
+    const char* vb = (const char*)v_head + g_b + 2 * o_b;
+    const uint32_t slot_addr = st_addr + (uint32_t)wl * 1024;
 #pragma unroll
-    for (int j = 0; j < KJ; ++j)
-      dma16<STREAM>((k_second[j] ? kb2 : ka) + k_soff[j], k_voff[j], st_addr + (wl + LW * j) * 1024);
+    for (int j = 0; j < KJ; ++j) dma16<STREAM>(second[j] ? kb2 : ka, k_voff[j], slot_addr + LW * j * 1024);
 #pragma unroll
-    for (int j = 0; j < KJ; ++j)
-      dma16<STREAM>((v_second[j] ? vb : va) + v_soff[j], v_voff, st_addr + K_BYTES + (wl + LW * j) * 1024);
+    for (int j = 0; j < KJ; ++j) dma16<STREAM>(second[j] ? vb : va, v_voff[j], slot_addr + K_BYTES + LW * j * 1024);
   };
   // Rows c0 .. c0+31 of the step's own block -> LDS stage at st_addr: K rows as above, V rows token-major
   // (row r at 2*D*r, chunk position p holding chunk p ^ 2*(r&3)) for the transposing operand read.  Rows past
