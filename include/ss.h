@@ -156,7 +156,8 @@ int ss_build_mask(const int32_t* parent, int B, int T, int gamma, uint32_t flags
  *          token s of a page, feature d, sits at [page, hkv, d, s]
  *  block_table [B, max_pages_per_seq] int32: physical page of logical page p,
  *          in [0, num_pages); entries outside that range are clamped on device
- *          (num_pages = first extent of k_cache / v_cache)
+ *          (num_pages = first extent of k_cache / v_cache; bf16: each cache at
+ *          most 1 TiB, else SS_ERR_UNSUPPORTED)
  *  seq_lens [B] int32: cached tokens per sequence, 0 <= seq_lens[b] <=
  *          max_pages_per_seq*page_size (larger values are clamped on device)
  *  parent [B,T] int32 as in a1.

@@ -414,6 +414,9 @@ static int msa_run(const char* fn, const void* q, const void* k_new, const void*
              max_pages_per_seq, num_pages);
   SS_REQUIRE((long)max_pages_per_seq * page_size <= (1L << 30), SS_ERR_UNSUPPORTED, "%s: sequence capacity too large",
              fn);
+  // the MFMA kernel keeps a page's offset in units of 256 bytes in 32 bits
+  SS_REQUIRE(dtype != SS_BF16 || (double)num_pages * Hkv * page_size * D * 2.0 <= 1099511627776.0, SS_ERR_UNSUPPORTED,
+             "%s: a cache of more than 1 TiB per tensor (num_pages=%d)", fn, num_pages);
   SS_REQUIRE(scale > 0.f && isfinite(scale), SS_ERR_INVALID_ARG, "%s: scale must be positive and finite", fn);
   SS_REQUIRE((flags & ~(SS_STREAM_EXCLUDE_SELF | SS_MSA_PARTIALS_ONLY | SS_MSA_MERGE_ONLY)) == 0, SS_ERR_INVALID_ARG,
              "%s: unknown flags 0x%x", fn, flags);

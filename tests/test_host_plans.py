@@ -58,3 +58,14 @@ def test_projection_workspace_matches_the_slices():
     assert b"workspace" in lib.ss_last_error()
     assert lib.ss_linear_rows_ws(one, one, 320, 11008, 4096, bf, one, None, 0, None) == 4
     assert lib.ss_linear_rows_ws(None, one, 320, 11008, 4096, bf, one, one, 1 << 30, None) == 1  # SS_ERR_INVALID_ARG
+
+
+def test_attention_refuses_a_cache_beyond_its_page_offsets():
+    # bf16 path: page offsets are kept in units of 256 bytes in 32 bits, i.e. up to 1 TiB per cache tensor; the
+    # check runs on the host before anything is enqueued (the pointers are never dereferenced)
+    lib = api.load_library()
+    one = ctypes.c_void_p(256)
+    pages = (1 << 40) // (32 * 64 * 128 * 2) + 1
+    rc = lib.ss_msa_attention(one, one, one, one, one, one, 4, pages, one, one, 1, 4, 1, 32, 32, 128, 64, 0.1,
+                              api.SS_BF16, 0, one, None, 0, None)
+    assert rc == 2 and b"1 TiB" in lib.ss_last_error()   # SS_ERR_UNSUPPORTED
